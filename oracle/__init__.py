@@ -1,0 +1,14 @@
+"""CPU oracle for the u8 x s8 -> s32 GEMM.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package; the product package never does.
+"""
+from .ngemm_oracle import (  # noqa: F401
+    build,
+    gemm_u8s8s32,
+    gemm_u8s8s64,
+    gemm_u8s8s32_sampled,
+    gemm_u8s8u8_requant,
+    num_threads,
+    requant_s32u8,
+)

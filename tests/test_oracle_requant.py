@@ -1,0 +1,85 @@
+"""Pins for the oracle's requantise-to-u8 step: an exact-rational re-derivation of
+s32 -> binary32 -> one binary32 multiply -> ties-to-even integer -> +zc -> clamp."""
+from fractions import Fraction
+
+import numpy as np
+
+
+def rne_to_binary32(x: Fraction) -> Fraction:
+    """Nearest binary32 (normal range only), ties to even, in exact arithmetic."""
+    if x == 0:
+        return x
+    mag = abs(x)
+    e = 0
+    while mag >= (1 << 24):
+        mag /= 2
+        e += 1
+    while mag < (1 << 23):
+        mag *= 2
+        e -= 1
+    assert -149 <= e <= 104, "outside the normal range this helper covers"
+    m = round(mag)                  # Python rounds a Fraction half to even
+    out = Fraction(m) * (Fraction(2) ** e)
+    return out if x > 0 else -out
+
+
+def requant_exact(c: int, scale32: np.float32, zc: int) -> int:
+    f = rne_to_binary32(Fraction(c))
+    g = rne_to_binary32(f * Fraction(float(scale32)))   # float(scale32) is exact
+    r = round(g)                                        # half to even
+    return min(255, max(0, r + zc))
+
+
+def check(oracle, cs, scale, zc):
+    cs = np.asarray(cs, dtype=np.int64)
+    C = cs.astype(np.int32).reshape(1, -1)
+    s32 = np.float32(scale)
+    got = oracle.requant_s32u8(C, s32, zc)[0]
+    want = [requant_exact(int(c), s32, zc) for c in cs]
+    assert got.tolist() == want
+
+
+def test_ties_to_even(oracle):
+    check(oracle, np.arange(-41, 42), 0.5, 20)          # odd c gives exact .5
+    check(oracle, np.arange(-1001, 1001, 2), 0.25, 128)
+    # explicit hand values: 0.5*{1,3,5,-1,-3} -> {0,2,2,-0,-2}
+    C = np.array([[1, 3, 5, -1, -3]], np.int32)
+    assert oracle.requant_s32u8(C, 0.5, 10).tolist() == [[10, 12, 12, 10, 8]]
+
+
+def test_clamp_edges(oracle):
+    C = np.array([[-2, -1, 0, 1, 254, 255, 256, 257]], np.int32)
+    assert oracle.requant_s32u8(C, 1.0, 0).tolist() == [[0, 0, 0, 1, 254, 255, 255, 255]]
+    assert oracle.requant_s32u8(C, 1.0, 1).tolist() == [[0, 0, 1, 2, 255, 255, 255, 255]]
+    check(oracle, [-2**31, -2**31 + 1, 2**31 - 1, 2**31 - 64, 2**31 - 65], 2.0**-23, 128)
+    check(oracle, [-2**31, 2**31 - 1], 2.0**-30, 0)
+    check(oracle, [-2**31, 2**31 - 1, 3, -3], 2.0**30, -5)
+
+
+def test_above_2_pow_24_conversion_rounds(oracle):
+    base = 1 << 24
+    cs = [base + d for d in range(-4, 40)] + [-(base + d) for d in range(-4, 40)]
+    cs += [(1 << 27) + d for d in range(0, 64)]
+    check(oracle, cs, 2.0**-17, 128)
+    check(oracle, cs, 7.62939453125e-06 * 1.000001, 7)
+
+
+def test_random_against_exact(oracle):
+    rng = np.random.default_rng(31)
+    for scale in (0.00096, 0.00048, 0.0123, 1.7, 3.1e-7, 2.0**-30, 123.456):
+        cs = np.concatenate([rng.integers(-2**31, 2**31, size=600),
+                             rng.integers(-400000, 400000, size=600)])
+        check(oracle, cs, scale, int(rng.integers(-300, 300)))
+
+
+def test_fused_equals_two_step(oracle):
+    rng = np.random.default_rng(32)
+    A = np.clip(np.rint(rng.normal(128, 40, size=(33, 300))), 0, 255).astype(np.uint8)
+    B = np.clip(np.rint(rng.normal(0, 30, size=(29, 300))), -127, 127).astype(np.int8)
+    C32 = oracle.gemm_u8s8s32(A, B, 128, 0)
+    two = oracle.requant_s32u8(C32, 0.00096, 128)
+    one = oracle.gemm_u8s8u8_requant(A, B, 128, 0, 0.00096, 128)
+    assert np.array_equal(one, two)
+    assert 20 < len(np.unique(one)) and one.min() >= 0      # spreads over the u8 range
+    want = [[requant_exact(int(c), np.float32(0.00096), 128) for c in row] for row in C32]
+    assert one.tolist() == want
