@@ -1,0 +1,189 @@
+/*
+ * ngemm.h -- C ABI of the MI355X (gfx950) low-precision integer GEMM library.
+ *
+ *     C_s32[M x N] = sum_k (A_u8[M x K] - za) * (B_s8[K x N] - zb)
+ *
+ * The operation is the low-precision GEMM of the paper's problem statement
+ * (Sec. 2.1: an unsigned 8-bit matrix times a signed 8-bit matrix, 32-bit
+ * result) with the offline-packed operand of Sec. 3.1.1 / Sec. 4 "Layout"
+ * (the weight matrix is marshalled once and reused).  Per-tensor zero-points
+ * and the requantise-to-u8 epilogue are this library's reading of the
+ * "operation fusion" remark of Sec. 4; the paper gives no formula for them.
+ *
+ * Operand conventions (all matrices live in DEVICE memory owned by the caller):
+ *   A  uint8, row-major,    A[i*lda + k],  lda >= K   (activation, not packed)
+ *   B  int8,  column-major, B[j*ldb + k],  ldb >= K   (column j is K contiguous
+ *      bytes: the paper's [N x K] storage; packed once by ngemm_pack_b)
+ *   C  int32 (or uint8 for the requantised variant), row-major, C[i*ldc + j],
+ *      ldc >= N.  Exactly the M x N window is written; the gaps left by a
+ *      larger ldc are never touched.
+ * All arithmetic is exact integer arithmetic modulo 2^32: whenever the true
+ * sum fits in int32 the result is that sum (Sec. 2.1: any reduction order
+ * gives the same integers unless K is large enough to overflow); beyond that
+ * it is the low 32 bits of the true sum.  With zero-points 0 the sum always
+ * fits for K <= 65793.
+ *
+ * The library never allocates, frees or synchronises device memory in the
+ * run calls: everything is enqueued on the caller's HIP stream.  Host handles
+ * (ngemm_ctx, ngemm_packed_b) are small host objects.
+ *
+ * Errors are return codes; on an error nothing has been launched.
+ */
+#ifndef NGEMM_H
+#define NGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ngemm_ctx ngemm_ctx;           /* opaque host object                                  */
+typedef struct ngemm_packed_b ngemm_packed_b; /* opaque host descriptor of a caller-owned device buffer */
+
+typedef enum {
+    NGEMM_OK = 0,
+    NGEMM_ERR_INVALID_ARG = -1,      /* null pointer, zero-point or scale out of range              */
+    NGEMM_ERR_BAD_SHAPE = -2,        /* negative dimension, leading dimension too small             */
+    NGEMM_ERR_BUFFER_TOO_SMALL = -3, /* packed buffer or workspace smaller than the size functions say */
+    NGEMM_ERR_DEVICE = -4,           /* a HIP call failed (no device, launch error)                 */
+    NGEMM_ERR_UNSUPPORTED_ARCH = -5  /* the device is not gfx950                                    */
+} ngemm_status;
+
+/* Kernel selection for ngemm_set_kernel (tests and A/B measurements). */
+enum {
+    NGEMM_KERNEL_AUTO = -1,
+    NGEMM_KERNEL_SKINNY = 0,     /* split-K streaming kernel, M <= 32 only                */
+    NGEMM_KERNEL_TILE_64 = 1,    /* 64 x 64 workgroup tile                                */
+    NGEMM_KERNEL_TILE_128 = 2,   /* 128 x 128 workgroup tile                              */
+    NGEMM_KERNEL_TILE_256 = 3,   /* 256 x 256 workgroup tile (throughput configuration)   */
+    NGEMM_KERNEL_COUNT = 4
+};
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char *ngemm_status_string(ngemm_status s);
+
+/*
+ * Create a context bound to HIP device `device_ordinal`.  Fails with
+ * NGEMM_ERR_DEVICE when there is no such device and NGEMM_ERR_UNSUPPORTED_ARCH
+ * when it is not a gfx950 part.  Makes no large allocation.
+ */
+ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal);
+
+/* Destroy a context.  NULL is accepted. */
+ngemm_status ngemm_destroy(ngemm_ctx *ctx);
+
+/* Force one kernel for the run calls (NGEMM_KERNEL_*), or NGEMM_KERNEL_AUTO for
+ * the shape heuristic.  Forcing NGEMM_KERNEL_SKINNY with M > 32 makes the run
+ * call return NGEMM_ERR_INVALID_ARG. */
+ngemm_status ngemm_set_kernel(ngemm_ctx *ctx, int kernel);
+
+/*
+ * Size in bytes of the packed form of a K x N int8 operand (pure function, no
+ * device needed).  Kp = K rounded up to 64, Np = N rounded up to 32; the size
+ * is Kp*Np + 4*Np: the zero-padded matrix itself (Sec. 3.1.1: pad with 0 when
+ * the sizes are not multiples of the inner block) plus one int32 column sum per
+ * padded column.  No further blow-up: the footprint is the matrix size, as in
+ * the paper's pack-memory comparison (Sec. 5).  Returns 0 for negative K or N.
+ *
+ * Layout of the packed buffer (two-level, as in Sec. 3.1.1: an inner block that
+ * one matrix instruction consumes as a single contiguous vector, iterated by an
+ * outer order that a workgroup streams through contiguously):
+ *   inner block ("fragment") = 32 columns x 32 k-values = 1024 bytes; the byte
+ *     for (column j, depth k) of fragment (p = j/32, s = k/32) sits at
+ *       16 * (32 * ((k%32)/16) + j%32) + k%16
+ *     i.e. 16 consecutive k per wavefront lane, lane = 32*((k%32)/16) + j%32.
+ *   outer order: fragment (p, s) starts at byte 1024 * (p * (Kp/32) + s), so one
+ *     32-column panel is one contiguous run over all of K.
+ *   column sums: int32 colsum[j] = sum_k B[k][j] at byte offset Kp*Np + 4*j
+ *     (0 for the padded columns).
+ */
+size_t ngemm_packed_b_bytes(int64_t K, int64_t N);
+
+/*
+ * Pack B (device, column-major, ldb >= K) into `packed_dev` (device, caller-
+ * owned, at least ngemm_packed_b_bytes(K,N) bytes, 16-byte aligned) and compute
+ * the column sums; asynchronous on `hip_stream` (a hipStream_t, NULL = default
+ * stream).  `*out` receives a host descriptor that refers to `packed_dev`; the
+ * buffer must stay alive and unmodified while the descriptor is used.  The
+ * packed bytes are position-independent and may be copied or saved bytewise.
+ * K == 0 or N == 0 is valid.
+ */
+ngemm_status ngemm_pack_b(ngemm_ctx *ctx, int64_t K, int64_t N,
+                          const int8_t *B_dev, int64_t ldb,
+                          void *packed_dev, size_t packed_bytes,
+                          void *hip_stream, ngemm_packed_b **out);
+
+/* Free the host descriptor only; the device buffer stays with the caller.  NULL is accepted. */
+ngemm_status ngemm_packed_b_free(ngemm_packed_b *b);
+
+/* Read back the shape a descriptor was packed with. */
+ngemm_status ngemm_packed_b_shape(const ngemm_packed_b *b, int64_t *K, int64_t *N);
+
+/*
+ * Workspace the run calls need for an M-row input (device bytes, pure
+ * function): room for the int32 row sums of A, used only when b_zero_point != 0.
+ * A NULL workspace is accepted when b_zero_point == 0.
+ */
+size_t ngemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * C[i][j] = sum_k (A[i][k] - a_zero_point) * (B[k][j] - b_zero_point), int32.
+ *   a_zero_point in [0,255], b_zero_point in [-128,127], else INVALID_ARG.
+ *   M == 0 or N == 0: nothing is written, NGEMM_OK.  K == 0: C is all zeros.
+ * Asynchronous on `hip_stream`.  A and the packed buffer are only read.
+ */
+ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M,
+                               const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                               const ngemm_packed_b *B, int32_t b_zero_point,
+                               int32_t *C_dev, int64_t ldc,
+                               void *workspace_dev, size_t workspace_bytes,
+                               void *hip_stream);
+
+/*
+ * Same sum with the fused requantise-to-u8 epilogue, applied to the int32
+ * value c of every element in exactly this order:
+ *     f = (float)c            binary32, round to nearest even
+ *     g = f * scale           one binary32 multiply (not fused with anything)
+ *     r = round-half-even(g)
+ *     C[i][j] = (uint8) min(255, max(0, r + c_zero_point))
+ * `scale` must be finite and in [2^-30, 2^30] (INVALID_ARG otherwise), which
+ * keeps every intermediate a normal binary32 number.
+ */
+ngemm_status ngemm_run_u8s8u8_requant(ngemm_ctx *ctx, int64_t M,
+                                      const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                      const ngemm_packed_b *B, int32_t b_zero_point,
+                                      float scale, int32_t c_zero_point,
+                                      uint8_t *C_dev, int64_t ldc,
+                                      void *workspace_dev, size_t workspace_bytes,
+                                      void *hip_stream);
+
+/* One member of a batch of independent GEMMs (host struct, device pointers inside). */
+typedef struct ngemm_problem {
+    int64_t M;
+    const uint8_t *A_dev;
+    int64_t lda;
+    int32_t a_zero_point;
+    int32_t b_zero_point;
+    const ngemm_packed_b *B;
+    int32_t *C_dev;
+    int64_t ldc;
+} ngemm_problem;
+
+/* Workspace for a batch: the sum of the members' needs (each rounded to 256 bytes). */
+size_t ngemm_batched_workspace_bytes(int count, const ngemm_problem *problems);
+
+/*
+ * Run `count` independent int32-output GEMMs (arbitrary shapes, per-GEMM
+ * zero-points) on one stream.  All members are validated before anything is
+ * launched.  Results are those of `count` calls of ngemm_run_u8s8s32.
+ */
+ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_problem *problems,
+                                       void *workspace_dev, size_t workspace_bytes,
+                                       void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NGEMM_H */

@@ -1,0 +1,374 @@
+// Host side of the C ABI declared in include/ngemm.h: argument validation, kernel
+// selection and launches.  Every step of the path runs in the kernels of
+// ngemm_kernels.h; there is no CPU fallback.
+#include "ngemm.h"
+#include "ngemm_kernels.h"
+
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+using namespace ngemm;
+
+struct ngemm_ctx {
+    uint32_t magic;
+    int device;
+    int num_cus;
+    int force_kernel;
+};
+
+struct ngemm_packed_b {
+    uint32_t magic;
+    int device;
+    int64_t K, N, Kp, Np;
+    const uint8_t *data;     // device, caller-owned
+    size_t bytes;
+};
+
+namespace {
+
+constexpr uint32_t kCtxMagic = 0x4e47454du;   // "NGEM"
+constexpr uint32_t kPackMagic = 0x4e47504bu;  // "NGPK"
+constexpr int64_t kMaxDim = 0x7fffffff - 4096;
+constexpr int kSkinnyMaxM = 32;
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
+        if (prev == dev) prev = -1;
+    }
+    ~DeviceGuard()
+    {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+bool ctx_ok(const ngemm_ctx *c) { return c && c->magic == kCtxMagic; }
+bool pack_ok(const ngemm_packed_b *b) { return b && b->magic == kPackMagic; }
+
+template <int BM, int BN, int WGM, int WGN>
+hipError_t launch_tile(const GemmParams &p0, bool requant, hipStream_t st)
+{
+    GemmParams p = p0;
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WGM * WGN * 64);
+    if (requant)
+        hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, p);
+    else
+        hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, false>), grid, block, 0, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_skinny(const GemmParams &p, bool requant, hipStream_t st)
+{
+    const int nslices = p.Kp / 32;
+    int nwaves = 1;
+    while (nwaves < 16 && nwaves * 4 <= nslices) nwaves *= 2;   // about two fragments per wavefront
+    const int nregs = 4 * ((p.M + 7) / 8);
+    const size_t smem = nwaves > 1 ? (size_t)nwaves * nregs * 64 * sizeof(int) : 0;
+    dim3 grid((unsigned)p.npanels), block(nwaves * 64);
+    if (requant)
+        hipLaunchKernelGGL((gemm_skinny_kernel<true>), grid, block, smem, st, p, nregs);
+    else
+        hipLaunchKernelGGL((gemm_skinny_kernel<false>), grid, block, smem, st, p, nregs);
+    return hipGetLastError();
+}
+
+int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N)
+{
+    if (M <= kSkinnyMaxM) return NGEMM_KERNEL_SKINNY;
+    auto tiles = [&](int64_t b) { return ((M + b - 1) / b) * ((N + b - 1) / b); };
+    const int64_t cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
+    if (tiles(256) * 4 >= cus * 3) return NGEMM_KERNEL_TILE_256;
+    if (tiles(128) * 2 >= cus) return NGEMM_KERNEL_TILE_128;
+    return NGEMM_KERNEL_TILE_64;
+}
+
+struct RunArgs {
+    int64_t M;
+    const uint8_t *A;
+    int64_t lda;
+    int32_t za, zb;
+    const ngemm_packed_b *B;
+    void *C;
+    int64_t ldc;
+    bool requant;
+    float scale;
+    int32_t zc;
+};
+
+ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_out)
+{
+    if (!ctx_ok(ctx) || !pack_ok(a.B)) return NGEMM_ERR_INVALID_ARG;
+    if (a.B->device != ctx->device) return NGEMM_ERR_INVALID_ARG;
+    if (a.M < 0 || a.M > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
+    if (a.za < 0 || a.za > 255 || a.zb < -128 || a.zb > 127) return NGEMM_ERR_INVALID_ARG;
+    if (a.requant) {
+        if (!std::isfinite(a.scale) || a.scale < 0x1p-30f || a.scale > 0x1p30f) return NGEMM_ERR_INVALID_ARG;
+    }
+    if (a.M == 0 || a.B->N == 0) {
+        *kernel_out = NGEMM_KERNEL_AUTO;
+        return NGEMM_OK;
+    }
+    if (!a.C || (!a.A && a.B->K > 0)) return NGEMM_ERR_INVALID_ARG;
+    if (a.lda < a.B->K || a.ldc < a.B->N) return NGEMM_ERR_BAD_SHAPE;
+    int k = ctx->force_kernel;
+    if (k == NGEMM_KERNEL_AUTO) k = choose_kernel(ctx, a.M, a.B->N);
+    if (k == NGEMM_KERNEL_SKINNY && a.M > kSkinnyMaxM) return NGEMM_ERR_INVALID_ARG;
+    *kernel_out = k;
+    return NGEMM_OK;
+}
+
+size_t rowsum_bytes(int64_t M) { return (size_t)round_up(M * 4, 256); }
+
+// Launches one validated GEMM; `ws` must hold rowsum_bytes(M) when zb != 0.
+ngemm_status launch_run(const RunArgs &a, int kernel, void *ws, hipStream_t st)
+{
+    const ngemm_packed_b *B = a.B;
+    if (a.M == 0 || B->N == 0) return NGEMM_OK;
+    GemmParams p;
+    std::memset(&p, 0, sizeof p);
+    p.A = a.A;
+    p.lda = a.lda;
+    p.Bp = B->data;
+    p.colsum = (const int32_t *)(B->data + B->Kp * B->Np);
+    p.rowsum = nullptr;
+    p.C = a.C;
+    p.ldc = a.ldc;
+    p.M = (int)a.M;
+    p.N = (int)B->N;
+    p.K = (int)B->K;
+    p.Kp = (int)B->Kp;
+    p.npanels = (int)(B->Np / 32);
+    p.za_term = (uint32_t)(128 - a.za);
+    p.zb = (uint32_t)a.zb;
+    p.kconst = 0u - (uint32_t)a.zb * (uint32_t)(128 - a.za) * (uint32_t)B->K;
+    p.scale = a.scale;
+    p.zc = a.zc;
+    if (a.zb != 0 && B->K > 0) {
+        int32_t *rs = (int32_t *)ws;
+        hipLaunchKernelGGL(rowsum_a_kernel, dim3((unsigned)((a.M + 3) / 4)), dim3(256), 0, st, a.A, a.lda,
+                           (int)a.M, (int)B->K, rs);
+        if (hipGetLastError() != hipSuccess) return NGEMM_ERR_DEVICE;
+        p.rowsum = rs;
+    }
+    hipError_t e;
+    switch (kernel) {
+    case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, st); break;
+    case NGEMM_KERNEL_TILE_64: e = launch_tile<64, 64, 2, 2>(p, a.requant, st); break;
+    case NGEMM_KERNEL_TILE_128: e = launch_tile<128, 128, 2, 2>(p, a.requant, st); break;
+    case NGEMM_KERNEL_TILE_256: e = launch_tile<256, 256, 2, 2>(p, a.requant, st); break;
+    default: return NGEMM_ERR_INVALID_ARG;
+    }
+    return e == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
+}
+
+ngemm_status run_common(ngemm_ctx *ctx, const RunArgs &a, void *ws, size_t ws_bytes, void *stream)
+{
+    int kernel;
+    ngemm_status s = validate_run(ctx, a, &kernel);
+    if (s != NGEMM_OK) return s;
+    if (a.M == 0 || a.B->N == 0) return NGEMM_OK;
+    if (a.zb != 0 && a.B->K > 0) {
+        if (!ws) return NGEMM_ERR_INVALID_ARG;
+        if (ws_bytes < rowsum_bytes(a.M)) return NGEMM_ERR_BUFFER_TOO_SMALL;
+    }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return NGEMM_ERR_DEVICE;
+    return launch_run(a, kernel, ws, (hipStream_t)stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ngemm_status_string(ngemm_status s)
+{
+    switch (s) {
+    case NGEMM_OK: return "ok";
+    case NGEMM_ERR_INVALID_ARG: return "invalid argument";
+    case NGEMM_ERR_BAD_SHAPE: return "bad shape or leading dimension";
+    case NGEMM_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+    case NGEMM_ERR_DEVICE: return "HIP device error";
+    case NGEMM_ERR_UNSUPPORTED_ARCH: return "unsupported architecture (gfx950 required)";
+    }
+    return "unknown status";
+}
+
+ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
+{
+    if (!out) return NGEMM_ERR_INVALID_ARG;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device_ordinal < 0 || device_ordinal >= count) {
+        (void)hipGetLastError();
+        return NGEMM_ERR_DEVICE;
+    }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device_ordinal) != hipSuccess) return NGEMM_ERR_DEVICE;
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return NGEMM_ERR_UNSUPPORTED_ARCH;
+    ngemm_ctx *c = new (std::nothrow) ngemm_ctx;
+    if (!c) return NGEMM_ERR_DEVICE;
+    c->magic = kCtxMagic;
+    c->device = device_ordinal;
+    c->num_cus = prop.multiProcessorCount;
+    c->force_kernel = NGEMM_KERNEL_AUTO;
+    *out = c;
+    return NGEMM_OK;
+}
+
+ngemm_status ngemm_destroy(ngemm_ctx *ctx)
+{
+    if (!ctx) return NGEMM_OK;
+    if (!ctx_ok(ctx)) return NGEMM_ERR_INVALID_ARG;
+    ctx->magic = 0;
+    delete ctx;
+    return NGEMM_OK;
+}
+
+ngemm_status ngemm_set_kernel(ngemm_ctx *ctx, int kernel)
+{
+    if (!ctx_ok(ctx)) return NGEMM_ERR_INVALID_ARG;
+    if (kernel < NGEMM_KERNEL_AUTO || kernel >= NGEMM_KERNEL_COUNT) return NGEMM_ERR_INVALID_ARG;
+    ctx->force_kernel = kernel;
+    return NGEMM_OK;
+}
+
+size_t ngemm_packed_b_bytes(int64_t K, int64_t N)
+{
+    if (K < 0 || N < 0 || K > kMaxDim || N > kMaxDim) return 0;
+    const int64_t Kp = round_up(K, 64), Np = round_up(N, 32);
+    return (size_t)(Kp * Np + 4 * Np);
+}
+
+ngemm_status ngemm_pack_b(ngemm_ctx *ctx, int64_t K, int64_t N, const int8_t *B_dev, int64_t ldb,
+                          void *packed_dev, size_t packed_bytes, void *hip_stream, ngemm_packed_b **out)
+{
+    if (!out) return NGEMM_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!ctx_ok(ctx)) return NGEMM_ERR_INVALID_ARG;
+    if (K < 0 || N < 0 || K > kMaxDim || N > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
+    if (K > 0 && N > 0 && (!B_dev || ldb < K)) return B_dev ? NGEMM_ERR_BAD_SHAPE : NGEMM_ERR_INVALID_ARG;
+    const size_t need = ngemm_packed_b_bytes(K, N);
+    if (need > 0 && !packed_dev) return NGEMM_ERR_INVALID_ARG;
+    if (packed_bytes < need) return NGEMM_ERR_BUFFER_TOO_SMALL;
+    if (((uintptr_t)packed_dev & 15u) != 0) return NGEMM_ERR_INVALID_ARG;
+    const int64_t Kp = round_up(K, 64), Np = round_up(N, 32);
+
+    ngemm_packed_b *d = new (std::nothrow) ngemm_packed_b;
+    if (!d) return NGEMM_ERR_DEVICE;
+    d->magic = kPackMagic;
+    d->device = ctx->device;
+    d->K = K; d->N = N; d->Kp = Kp; d->Np = Np;
+    d->data = (const uint8_t *)packed_dev;
+    d->bytes = need;
+
+    if (Np > 0) {
+        DeviceGuard g(ctx->device);
+        if (!g.ok) { delete d; return NGEMM_ERR_DEVICE; }
+        hipStream_t st = (hipStream_t)hip_stream;
+        const int64_t nchunks = Kp * Np / 16;
+        if (nchunks > 0) {
+            hipLaunchKernelGGL(pack_b_kernel, dim3((unsigned)((nchunks + 255) / 256)), dim3(256), 0, st, B_dev,
+                               ldb, (int)K, (int)N, (int)Kp, nchunks, (uint8_t *)packed_dev);
+            if (hipGetLastError() != hipSuccess) { delete d; return NGEMM_ERR_DEVICE; }
+        }
+        hipLaunchKernelGGL(colsum_b_kernel, dim3((unsigned)((Np + 3) / 4)), dim3(256), 0, st, B_dev, ldb, (int)K,
+                           (int)N, (int)Np, (int32_t *)((uint8_t *)packed_dev + Kp * Np));
+        if (hipGetLastError() != hipSuccess) { delete d; return NGEMM_ERR_DEVICE; }
+    }
+    *out = d;
+    return NGEMM_OK;
+}
+
+ngemm_status ngemm_packed_b_free(ngemm_packed_b *b)
+{
+    if (!b) return NGEMM_OK;
+    if (!pack_ok(b)) return NGEMM_ERR_INVALID_ARG;
+    b->magic = 0;
+    delete b;
+    return NGEMM_OK;
+}
+
+ngemm_status ngemm_packed_b_shape(const ngemm_packed_b *b, int64_t *K, int64_t *N)
+{
+    if (!pack_ok(b) || !K || !N) return NGEMM_ERR_INVALID_ARG;
+    *K = b->K;
+    *N = b->N;
+    return NGEMM_OK;
+}
+
+size_t ngemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    (void)N; (void)K;
+    if (M <= 0 || M > kMaxDim) return 0;
+    return rowsum_bytes(M);
+}
+
+ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                               const ngemm_packed_b *B, int32_t b_zero_point, int32_t *C_dev, int64_t ldc,
+                               void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, false, 1.0f, 0};
+    return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
+}
+
+ngemm_status ngemm_run_u8s8u8_requant(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, int64_t lda,
+                                      int32_t a_zero_point, const ngemm_packed_b *B, int32_t b_zero_point,
+                                      float scale, int32_t c_zero_point, uint8_t *C_dev, int64_t ldc,
+                                      void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, true, scale, c_zero_point};
+    return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
+}
+
+size_t ngemm_batched_workspace_bytes(int count, const ngemm_problem *problems)
+{
+    if (count <= 0 || !problems) return 0;
+    size_t total = 0;
+    for (int t = 0; t < count; ++t)
+        if (problems[t].b_zero_point != 0 && problems[t].M > 0 && problems[t].M <= kMaxDim)
+            total += rowsum_bytes(problems[t].M);
+    return total;
+}
+
+ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_problem *problems,
+                                       void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx_ok(ctx) || count < 0 || (count > 0 && !problems)) return NGEMM_ERR_INVALID_ARG;
+    size_t need = 0;
+    for (int t = 0; t < count; ++t) {
+        const ngemm_problem &q = problems[t];
+        RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
+        int kernel;
+        ngemm_status s = validate_run(ctx, a, &kernel);
+        if (s != NGEMM_OK) return s;
+        if (q.b_zero_point != 0 && q.M > 0 && q.B->N > 0 && q.B->K > 0) need += rowsum_bytes(q.M);
+    }
+    if (need > 0 && !workspace_dev) return NGEMM_ERR_INVALID_ARG;
+    if (workspace_bytes < need) return NGEMM_ERR_BUFFER_TOO_SMALL;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return NGEMM_ERR_DEVICE;
+    size_t off = 0;
+    for (int t = 0; t < count; ++t) {
+        const ngemm_problem &q = problems[t];
+        RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
+        int kernel;
+        (void)validate_run(ctx, a, &kernel);
+        void *ws = (uint8_t *)workspace_dev + off;
+        if (q.b_zero_point != 0 && q.M > 0 && q.B->N > 0 && q.B->K > 0) off += rowsum_bytes(q.M);
+        ngemm_status s = launch_run(a, kernel, ws, (hipStream_t)hip_stream);
+        if (s != NGEMM_OK) return s;
+    }
+    return NGEMM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,290 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer and byte results must match bit for bit (tolerance 0): the integer sum
+is unique and the requantise sequence is fixed operation by operation."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_1910_00178_amd import workloads as wl  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def rt():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1910_00178_amd as ng  # noqa: F401  (raises if the library is missing)
+    from gpu_util import Runner
+    r = Runner(0)
+    yield r
+    r.close()
+
+
+def ng_mod():
+    import paper_1910_00178_amd as ng
+    return ng
+
+
+TILE_KERNELS = (1, 2, 3)
+
+
+def check_problem(rt, oracle, prob, kernels, **kw):
+    ng = ng_mod()
+    want32 = oracle.gemm_u8s8s32(prob.A, prob.B, prob.za, prob.zb)
+    h, packed = rt.pack(prob.B, ldb_pad=kw.pop("ldb_pad", 0))
+    try:
+        for k in kernels:
+            if k == ng.NGEMM_KERNEL_SKINNY and prob.M > 32:
+                continue
+            rt.set_kernel(k)
+            got = rt.run(prob.A, h, prob.N, prob.za, prob.zb, **kw)
+            assert np.array_equal(got, want32), f"{prob.name} kernel {k}: {np.count_nonzero(got != want32)} mismatches"
+            if prob.scale is not None:
+                want8 = oracle.gemm_u8s8u8_requant(prob.A, prob.B, prob.za, prob.zb, prob.scale, prob.zc)
+                got8 = rt.run(prob.A, h, prob.N, prob.za, prob.zb, scale=prob.scale, zc=prob.zc, **kw)
+                assert np.array_equal(got8, want8), f"{prob.name} kernel {k} requant"
+    finally:
+        rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+        ng.ngemm_packed_b_free(h)
+
+
+def test_pack_layout_roundtrip(rt):
+    """The packed buffer follows the documented layout, pads with zeros, holds exact column sums,
+    and is exactly the padded matrix plus 4 bytes per padded column (no blow-up)."""
+    from gpu_util import unpack_packed
+    ng = ng_mod()
+    assert ng.ngemm_packed_b_bytes(512, 512) == 512 * 512 + 4 * 512
+    rng = np.random.default_rng(5)
+    for (N, K, pad) in ((64, 256, 0), (33, 65, 3), (1, 1, 0), (100, 1000, 7), (517, 129, 1), (31, 63, 0)):
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        h, packed = rt.pack(B, ldb_pad=pad)
+        nbytes = ng.ngemm_packed_b_bytes(K, N)
+        back, pad_zero, colsum = unpack_packed(packed.cpu().numpy()[:nbytes], K, N)
+        assert np.array_equal(back, B)
+        assert pad_zero
+        assert np.array_equal(colsum[:N], B.astype(np.int64).sum(1).astype(np.int32))
+        assert not colsum[N:].any()
+        assert ng.ngemm_packed_b_shape(h) == (K, N)
+        ng.ngemm_packed_b_free(h)
+
+
+def test_config1_tiny(rt, oracle):
+    p = wl.tiny()
+    check_problem(rt, oracle, p, TILE_KERNELS + (-1,))
+    check_problem(rt, oracle, p, TILE_KERNELS, lda_pad=5, ldc_pad=3, ldb_pad=9)
+
+
+@pytest.mark.parametrize("index", [0, 1, 2])
+def test_config2_bert_fc(rt, oracle, index):
+    p = wl.bert_fc(index)
+    check_problem(rt, oracle, p, TILE_KERNELS + (-1,))
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_config3_skinny_pack_once_reuse(rt, oracle, M):
+    """Pack once, 1000 calls cycling through a pool of 16 inputs, every pool member verified,
+    packed bytes unchanged at the end."""
+    ng = ng_mod()
+    probs = wl.skinny(M)
+    B = probs[0].B
+    N, K = B.shape
+    h, packed = rt.pack(B)
+    before = packed.clone()
+    A_dev = [torch.from_numpy(p.A).cuda() for p in probs]
+    C_dev = [torch.full((M, N), -7, dtype=torch.int32, device="cuda") for _ in probs]
+    for it in range(1000):
+        t = it % len(probs)
+        ng.ngemm_run_u8s8s32(rt.ctx, M, A_dev[t], K, 0, h, 0, C_dev[t], N)
+    torch.cuda.synchronize()
+    for t, p in enumerate(probs):
+        assert np.array_equal(C_dev[t].cpu().numpy(), oracle.gemm_u8s8s32(p.A, B)), (M, t)
+    assert torch.equal(before, packed)
+    ng.ngemm_packed_b_free(h)
+
+
+def test_config4_large_square(rt, oracle):
+    """8192^3 in the benchmark's launch configuration: a slab of rows element by element, sampled
+    elements over the whole matrix, and an exact Freivalds-style check of all of C."""
+    ng = ng_mod()
+    p = wl.large_square()
+    n = p.M
+    h, packed = rt.pack(p.B)
+    Ad = torch.from_numpy(p.A).cuda()
+    Cd = torch.empty((n, n), dtype=torch.int32, device="cuda")
+    ng.ngemm_run_u8s8s32(rt.ctx, n, Ad, n, 0, h, 0, Cd, n)
+    torch.cuda.synchronize()
+    C = Cd.cpu().numpy()
+    # (1) slab: rows straddling a 256-row tile boundary
+    rows = np.r_[0:8, 252:260, n - 8:n]
+    assert np.array_equal(C[rows], oracle.gemm_u8s8s32(np.ascontiguousarray(p.A[rows]), p.B))
+    # (2) samples everywhere
+    rng = np.random.default_rng(44)
+    ri = rng.integers(0, n, size=20000)
+    ci = rng.integers(0, n, size=20000)
+    assert np.array_equal(C[ri, ci], oracle.gemm_u8s8s32_sampled(p.A, p.B, ri, ci))
+    # (3) C x == A (B x) exactly in int64 for small random x: catches any single wrong element
+    for s in range(3):
+        x = np.random.default_rng(100 + s).integers(-8, 9, size=n).astype(np.int64)
+        Bx = np.zeros(n, dtype=np.int64)
+        for j0 in range(0, n, 1024):
+            Bx += p.B[j0:j0 + 1024].astype(np.int64).T @ x[j0:j0 + 1024]
+        lhs = np.zeros(n, dtype=np.int64)
+        rhs = np.zeros(n, dtype=np.int64)
+        for i0 in range(0, n, 1024):
+            lhs[i0:i0 + 1024] = C[i0:i0 + 1024].astype(np.int64) @ x
+            rhs[i0:i0 + 1024] = p.A[i0:i0 + 1024].astype(np.int64) @ Bx
+        assert np.array_equal(lhs, rhs)
+    ng.ngemm_packed_b_free(h)
+
+
+def test_config5_batched_mixed(rt, oracle):
+    ng = ng_mod()
+    probs = wl.batched()
+    handles, keep, items, outs = [], [], [], []
+    for p in probs:
+        h, packed = rt.pack(p.B)
+        Ad = torch.from_numpy(p.A).cuda()
+        Cd = torch.full((p.M, p.N), -9, dtype=torch.int32, device="cuda")
+        handles.append(h)
+        keep.append((packed, Ad))
+        outs.append(Cd)
+        items.append((p.M, Ad, p.K, p.za, p.zb, h, Cd, p.N))
+    arr = ng.make_problems(items)
+    wsb = ng.ngemm_batched_workspace_bytes(arr)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    ng.ngemm_run_batched_u8s8s32(rt.ctx, arr, ws, wsb)
+    torch.cuda.synchronize()
+    for p, Cd in zip(probs, outs):
+        want = oracle.gemm_u8s8s32(p.A, p.B, p.za, p.zb)
+        got = Cd.cpu().numpy()
+        assert np.array_equal(got, want), f"{p.name} za={p.za} zb={p.zb}: {np.count_nonzero(got != want)} mismatches"
+    for h in handles:
+        ng.ngemm_packed_b_free(h)
+
+
+EDGE_DIMS = (1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 129, 255, 257)
+
+
+def test_edge_shapes_all_kernels(rt, oracle):
+    """Ragged tails in every dimension, every kernel, zero-points at their extremes, odd leading
+    dimensions and a misaligned A pointer."""
+    rng = np.random.default_rng(77)
+    zps = ((0, 0), (128, 0), (255, -128), (0, 127), (77, -8), (1, 1))
+    for t in range(60):
+        M = int(rng.choice(EDGE_DIMS))
+        N = int(rng.choice(EDGE_DIMS))
+        K = int(rng.choice(EDGE_DIMS + (300, 513)))
+        za, zb = zps[t % len(zps)]
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        p = wl.Problem(f"edge{t}_{M}x{N}x{K}", A, B, za=za, zb=zb,
+                       scale=float(np.float32(0.004)) if t % 3 == 0 else None, zc=100)
+        check_problem(rt, oracle, p, (0, 1, 2, 3, -1), lda_pad=int(rng.integers(0, 4)),
+                      ldc_pad=int(rng.integers(0, 3)), a_byte_offset=int(rng.integers(0, 4)))
+
+
+def test_skinny_all_row_counts(rt, oracle):
+    rng = np.random.default_rng(78)
+    for M in range(1, 33):
+        K = int(rng.choice((64, 100, 1024, 2050)))
+        N = int(rng.choice((32, 40, 4096 if M % 8 == 0 else 96)))
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        p = wl.Problem(f"skinny{M}", A, B, za=int(rng.integers(0, 256)), zb=int(rng.integers(-3, 4)),
+                       scale=float(np.float32(0.002)), zc=128)
+        check_problem(rt, oracle, p, (0,))
+
+
+def test_extreme_values_and_wrap(rt, oracle):
+    """All-255 x all-(-128)/127 operands: no 16-bit stage, exact at the int32 bound, wraps beyond."""
+    for (K, b) in ((64, 127), (64, -128), (65793, -128), (65794, -128), (66311, 127), (66312, 127)):
+        A = np.full((33, K), 255, np.uint8)
+        B = np.full((40, K), b, np.int8)
+        p = wl.Problem(f"extreme_K{K}_b{b}", A, B)
+        check_problem(rt, oracle, p, (1, 3))
+    A = np.full((8, 65794), 255, np.uint8)
+    B = np.full((32, 65794), -128, np.int8)
+    check_problem(rt, oracle, wl.Problem("extreme_skinny", A, B), (0,))
+
+
+def test_degenerate_sizes(rt, oracle):
+    ng = ng_mod()
+    # K == 0: every element is the empty sum
+    h, packed = rt.pack(np.zeros((5, 0), np.int8))
+    got = rt.run(np.zeros((3, 0), np.uint8), h, 5, za=9, zb=4)
+    assert np.array_equal(got, np.zeros((3, 5), np.int32))
+    got = rt.run(np.zeros((40, 0), np.uint8), h, 5, za=9, zb=4)
+    assert np.array_equal(got, np.zeros((40, 5), np.int32))
+    # M == 0: nothing written
+    got = rt.run(np.zeros((0, 0), np.uint8), h, 5)
+    assert got.shape == (0, 5)
+    ng.ngemm_packed_b_free(h)
+    # N == 0
+    h, packed = rt.pack(np.zeros((0, 16), np.int8))
+    got = rt.run(np.ones((4, 16), np.uint8), h, 0)
+    assert got.shape == (4, 0)
+    ng.ngemm_packed_b_free(h)
+
+
+def test_kernels_agree_with_each_other(rt, oracle):
+    """Sec. 2.1: any tiling / reduction order gives the same integers."""
+    ng = ng_mod()
+    rng = np.random.default_rng(79)
+    A = rng.integers(0, 256, size=(300, 1111), dtype=np.uint8)
+    B = rng.integers(-128, 128, size=(555, 1111), dtype=np.int8)
+    h, packed = rt.pack(B)
+    res = []
+    for k in TILE_KERNELS:
+        rt.set_kernel(k)
+        res.append(rt.run(A, h, 555, 13, -5))
+    rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+    assert np.array_equal(res[0], res[1]) and np.array_equal(res[1], res[2])
+    assert np.array_equal(res[0], oracle.gemm_u8s8s32(A, B, 13, -5))
+    ng.ngemm_packed_b_free(h)
+
+
+def test_error_paths_launch_nothing(rt):
+    ng = ng_mod()
+    B = np.ones((8, 64), np.int8)
+    h, packed = rt.pack(B)
+    A = torch.zeros((40, 64), dtype=torch.uint8, device="cuda")
+    C = torch.full((40, 8), 5, dtype=torch.int32, device="cuda")
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+
+    def status(fn, *a, **k):
+        try:
+            fn(*a, **k)
+        except ng.NgemmError as e:
+            return e.status
+        return 0
+
+    run = ng.ngemm_run_u8s8s32
+    assert status(run, rt.ctx, 40, A, 64, 256, h, 0, C, 8) == ng.NGEMM_ERR_INVALID_ARG
+    assert status(run, rt.ctx, 40, A, 64, -1, h, 0, C, 8) == ng.NGEMM_ERR_INVALID_ARG
+    assert status(run, rt.ctx, 40, A, 64, 0, h, 128, C, 8) == ng.NGEMM_ERR_INVALID_ARG
+    assert status(run, rt.ctx, 40, A, 63, 0, h, 0, C, 8) == ng.NGEMM_ERR_BAD_SHAPE
+    assert status(run, rt.ctx, 40, A, 64, 0, h, 0, C, 7) == ng.NGEMM_ERR_BAD_SHAPE
+    assert status(run, rt.ctx, -1, A, 64, 0, h, 0, C, 8) == ng.NGEMM_ERR_BAD_SHAPE
+    assert status(run, rt.ctx, 40, None, 64, 0, h, 0, C, 8) == ng.NGEMM_ERR_INVALID_ARG
+    assert status(run, rt.ctx, 40, A, 64, 0, h, 0, None, 8) == ng.NGEMM_ERR_INVALID_ARG
+    assert status(run, rt.ctx, 40, A, 64, 0, h, 3, C, 8, None, 0) == ng.NGEMM_ERR_INVALID_ARG
+    assert status(run, rt.ctx, 40, A, 64, 0, h, 3, C, 8, ws, 16) == ng.NGEMM_ERR_BUFFER_TOO_SMALL
+    rq = ng.ngemm_run_u8s8u8_requant
+    C8 = torch.zeros((40, 8), dtype=torch.uint8, device="cuda")
+    for bad in (0.0, -1.0, float("nan"), float("inf"), 2.0**31, 2.0**-31):
+        assert status(rq, rt.ctx, 40, A, 64, 0, h, 0, bad, 0, C8, 8) == ng.NGEMM_ERR_INVALID_ARG
+    rt.set_kernel(ng.NGEMM_KERNEL_SKINNY)
+    assert status(run, rt.ctx, 40, A, 64, 0, h, 0, C, 8) == ng.NGEMM_ERR_INVALID_ARG
+    rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+    torch.cuda.synchronize()
+    assert bool((C == 5).all())                      # nothing was launched by the failed calls
+    # pack: buffer too small, bad ldb
+    Bd = torch.zeros((8, 64), dtype=torch.int8, device="cuda")
+    small = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    assert status(ng.ngemm_pack_b, rt.ctx, 64, 8, Bd, 64, small, 64) == ng.NGEMM_ERR_BUFFER_TOO_SMALL
+    big = torch.zeros(ng.ngemm_packed_b_bytes(64, 8), dtype=torch.uint8, device="cuda")
+    assert status(ng.ngemm_pack_b, rt.ctx, 64, 8, Bd, 63, big, big.numel()) == ng.NGEMM_ERR_BAD_SHAPE
+    assert status(ng.ngemm_pack_b, rt.ctx, -1, 8, Bd, 64, big, big.numel()) == ng.NGEMM_ERR_BAD_SHAPE
+    ng.ngemm_packed_b_free(h)
