@@ -1,0 +1,281 @@
+#!/usr/bin/env python3
+"""Benchmark of the gfx950 u8 x s8 -> s32 GEMM path on one MI355X.
+
+Headline workload (config 4): M = N = K = 8192, uniform u8 x uniform s8, zero-points 0, int32
+output.  A "step" is one ngemm_run_u8s8s32 call on operands already resident in HBM (B packed
+once beforehand, as the method prescribes for the weight operand).  Prints ONE JSON line.
+
+Extras in the same line: the skinny-M shapes (GB/s, as specified / with rotating weights so
+that every byte comes from HBM / a large asymptote), the transformer FC shapes with int32 and
+requantised u8 output, the batched odd shapes, and the pack kernel.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense INT8 matrix peak, TOP/s (published)
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak, GB/s (published)
+
+# HBM bytes per launch of the 8192^3 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def gpu_time_ms(fn, iters, warmup, torch):
+    """Average milliseconds per call of fn(), HIP events on the current stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--size", type=int, default=8192, help="square size of the headline workload")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle wall time")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1910_00178_amd as ng
+    from paper_1910_00178_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    ctx = ng.ngemm_create(0)
+
+    def pack(B_np):
+        N, K = B_np.shape
+        Bd = torch.from_numpy(B_np).cuda()
+        nbytes = ng.ngemm_packed_b_bytes(K, N)
+        packed = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        h = ng.ngemm_pack_b(ctx, K, N, Bd, K, packed, nbytes)
+        torch.cuda.synchronize()
+        return h, packed, Bd
+
+    # ---------------- headline: large square ----------------
+    n = args.size
+    prob = wl.large_square(n)
+    h, packed, Bd = pack(prob.B)
+    Ad = torch.from_numpy(prob.A).cuda()
+    Cd = torch.empty((n, n), dtype=torch.int32, device="cuda")
+
+    def step():
+        ng.ngemm_run_u8s8s32(ctx, n, Ad, n, 0, h, 0, Cd, n)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern_ms = ev0.elapsed_time(ev1) / args.steps
+    ops = 2.0 * n * n * n
+    tops = ops / (wall_ms * 1e-3) / 1e12
+    kern_tops = ops / (kern_ms * 1e-3) / 1e12
+
+    # correctness of the timed output on sampled elements (oracle, element by element)
+    import oracle
+    rng = np.random.default_rng(7)
+    ri = rng.integers(0, n, size=4096)
+    ci = rng.integers(0, n, size=4096)
+    Cs = Cd[torch.from_numpy(ri).cuda(), torch.from_numpy(ci).cuda()].cpu().numpy()
+    sample_ok = bool(np.array_equal(Cs, oracle.gemm_u8s8s32_sampled(prob.A, prob.B, ri, ci)))
+
+    pack_ms = gpu_time_ms(lambda: ng.ngemm_packed_b_free(
+        ng.ngemm_pack_b(ctx, n, n, Bd, n, packed, packed.numel())), 5, 1, torch)
+
+    result = {
+        "metric": "int8 GEMM TOPS (u8 x s8 -> s32, M=N=K=%d)" % n,
+        "value": round(tops, 2),
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 x int8 -> int32 (u8 operand shifted to s8)",
+        "data": "synthetic (seeded uniform u8 / s8)",
+        "config": {"workload": "large_square_%d" % n, "M": n, "N": n, "K": n, "za": 0, "zb": 0,
+                   "kernel": "gemm_tile_kernel<256,256>", "sampled_outputs_match_oracle": sample_ok},
+        "roofline": {"bound": "mfma", "achieved": round(kern_tops, 2), "peak": INT8_MFMA_PEAK_TOPS,
+                     "unit": "TOP/s", "frac": round(kern_tops / INT8_MFMA_PEAK_TOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES, "kernel_ms": round(kern_ms, 5),
+                     "algorithmic_ops_per_launch": ops,
+                     "algorithmic_bytes_per_launch": 2 * n * n + 4 * n * n},
+        "pack_b": {"ms": round(pack_ms, 4), "GBps": round(2.0 * n * n / (pack_ms * 1e-3) / 1e9, 1)},
+    }
+
+    # ---------------- CPU baseline: the oracle as it stands, bounded sample ----------------
+    if not args.no_cpu_baseline:
+        cal_rows = 4
+        t = time.perf_counter()
+        oracle.gemm_u8s8s32(np.ascontiguousarray(prob.A[:cal_rows]), prob.B)
+        per_row = (time.perf_counter() - t) / cal_rows
+        rows = int(max(oracle.num_threads(), min(n, args.cpu_seconds / max(per_row, 1e-9))))
+        rows = max(oracle.num_threads(), rows // oracle.num_threads() * oracle.num_threads())
+        rows = min(rows, n)
+        t = time.perf_counter()
+        oracle.gemm_u8s8s32(np.ascontiguousarray(prob.A[:rows]), prob.B)
+        dt = time.perf_counter() - t
+        result["cpu_baseline"] = {
+            "value": round(2.0 * rows * n * n / dt / 1e12, 5), "unit": "TOPS",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "first %d rows of A against all of B (%d x %d x %d), %.1f s" % (rows, rows, n, n, dt)}
+
+    del Ad, Cd
+    ng.ngemm_packed_b_free(h)
+    del packed, Bd
+    torch.cuda.empty_cache()
+
+    # ---------------- extras ----------------
+    if not args.no_extras:
+        extras = {}
+        # skinny-M: (i) as specified, (ii) rotating weights, (iii) asymptote
+        sk = {}
+        for M in (1, 4, 16):
+            probs = wl.skinny(M)
+            B = probs[0].B
+            N, K = B.shape
+            hb, pk, _ = pack(B)
+            A_dev = [torch.from_numpy(p.A).cuda() for p in probs]
+            C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+            cnt = [0]
+
+            def call():
+                ng.ngemm_run_u8s8s32(ctx, M, A_dev[cnt[0] % 16], K, 0, hb, 0, C, N)
+                cnt[0] += 1
+            ms = gpu_time_ms(call, 1000, 50, torch)
+            abytes = K * N + M * K + 4 * M * N
+            entry = {"as_specified_us": round(ms * 1e3, 3), "as_specified_GBps": round(abytes / (ms * 1e-3) / 1e9, 1),
+                     "algorithmic_bytes": abytes}
+            # rotating: 160 distinct packed copies (> 512 MiB, beyond the 256 MiB Infinity Cache)
+            nb = ng.ngemm_packed_b_bytes(K, N)
+            ncopies = 160
+            pool = torch.empty((ncopies, nb), dtype=torch.uint8, device="cuda")
+            pool[:] = pk
+            hs = []
+            Bd2 = torch.from_numpy(B).cuda()
+            for c in range(ncopies):
+                hs.append(ng.ngemm_pack_b(ctx, K, N, Bd2, K, pool[c], nb))
+            torch.cuda.synchronize()
+
+            def call_rot():
+                ng.ngemm_run_u8s8s32(ctx, M, A_dev[cnt[0] % 16], K, 0, hs[cnt[0] % ncopies], 0, C, N)
+                cnt[0] += 1
+            ms2 = gpu_time_ms(call_rot, 960, 160, torch)
+            entry["rotating_weights_us"] = round(ms2 * 1e3, 3)
+            entry["rotating_weights_GBps"] = round(abytes / (ms2 * 1e-3) / 1e9, 1)
+            entry["rotating_frac_of_hbm_peak"] = round(abytes / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            for x in hs:
+                ng.ngemm_packed_b_free(x)
+            ng.ngemm_packed_b_free(hb)
+            del pool
+            sk["M%d" % M] = entry
+        # asymptote: N=16384, K=4096 (64 MiB of weights), 8 rotating copies (512 MiB)
+        rngb = wl.rng_for(3, 99)
+        Nb, Kb, Mb = 16384, 4096, 16
+        Bbig = wl.uniform_s8(rngb, Nb, Kb)
+        Abig = torch.from_numpy(wl.uniform_u8(rngb, Mb, Kb)).cuda()
+        nb = ng.ngemm_packed_b_bytes(Kb, Nb)
+        pool = torch.empty((8, nb), dtype=torch.uint8, device="cuda")
+        Bd2 = torch.from_numpy(Bbig).cuda()
+        hs = [ng.ngemm_pack_b(ctx, Kb, Nb, Bd2, Kb, pool[c], nb) for c in range(8)]
+        Cb = torch.empty((Mb, Nb), dtype=torch.int32, device="cuda")
+        cnt = [0]
+
+        def call_big():
+            ng.ngemm_run_u8s8s32(ctx, Mb, Abig, Kb, 0, hs[cnt[0] % 8], 0, Cb, Nb)
+            cnt[0] += 1
+        ms3 = gpu_time_ms(call_big, 80, 16, torch)
+        ab = Kb * Nb + Mb * Kb + 4 * Mb * Nb
+        sk["asymptote_M16_N16384_K4096"] = {"us": round(ms3 * 1e3, 2), "GBps": round(ab / (ms3 * 1e-3) / 1e9, 1),
+                                            "frac_of_hbm_peak": round(ab / (ms3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        for x in hs:
+            ng.ngemm_packed_b_free(x)
+        del pool, Bd2
+        extras["skinny"] = sk
+
+        # transformer FC shapes
+        fc = {}
+        for idx in range(3):
+            p = wl.bert_fc(idx)
+            hb, pk, _ = pack(p.B)
+            A = torch.from_numpy(p.A).cuda()
+            C = torch.empty((p.M, p.N), dtype=torch.int32, device="cuda")
+            C8 = torch.empty((p.M, p.N), dtype=torch.uint8, device="cuda")
+            ms = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32(ctx, p.M, A, p.K, p.za, hb, p.zb, C, p.N), 200, 20, torch)
+            ms8 = gpu_time_ms(lambda: ng.ngemm_run_u8s8u8_requant(ctx, p.M, A, p.K, p.za, hb, p.zb, p.scale, p.zc,
+                                                                  C8, p.N), 200, 20, torch)
+            o = 2.0 * p.M * p.N * p.K
+            b32 = p.M * p.K + p.N * p.K + 4 * p.M * p.N
+            b8 = p.M * p.K + p.N * p.K + p.M * p.N
+            fc[p.name] = {"s32_us": round(ms * 1e3, 2), "s32_TOPS": round(o / (ms * 1e-3) / 1e12, 1),
+                          "s32_GBps": round(b32 / (ms * 1e-3) / 1e9, 1),
+                          "u8_us": round(ms8 * 1e3, 2), "u8_TOPS": round(o / (ms8 * 1e-3) / 1e12, 1),
+                          "u8_GBps": round(b8 / (ms8 * 1e-3) / 1e9, 1)}
+            ng.ngemm_packed_b_free(hb)
+        extras["bert_fc"] = fc
+
+        # batched odd shapes
+        probs = wl.batched()
+        items, keep, hs = [], [], []
+        for p in probs:
+            hb, pk, _ = pack(p.B)
+            A = torch.from_numpy(p.A).cuda()
+            C = torch.empty((p.M, p.N), dtype=torch.int32, device="cuda")
+            keep.append((pk, A, C))
+            hs.append(hb)
+            items.append((p.M, A, p.K, p.za, p.zb, hb, C, p.N))
+        arr = ng.make_problems(items)
+        wsb = ng.ngemm_batched_workspace_bytes(arr)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        msb = gpu_time_ms(lambda: ng.ngemm_run_batched_u8s8s32(ctx, arr, ws, wsb), 20, 3, torch)
+        o = sum(2.0 * p.M * p.N * p.K for p in probs)
+        by = sum(p.M * p.K + p.N * p.K + 4 * p.M * p.N for p in probs)
+        extras["batched_64_odd_shapes"] = {"ms": round(msb, 4), "TOPS": round(o / (msb * 1e-3) / 1e12, 2),
+                                           "GBps": round(by / (msb * 1e-3) / 1e9, 1)}
+        for x in hs:
+            ng.ngemm_packed_b_free(x)
+        result["extras"] = extras
+
+    ng.ngemm_destroy(ctx)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
