@@ -79,6 +79,11 @@ ngemm_status ngemm_destroy(ngemm_ctx *ctx);
  * call return NGEMM_ERR_INVALID_ARG. */
 ngemm_status ngemm_set_kernel(ngemm_ctx *ctx, int kernel);
 
+/* Cap the number of persistent workgroups the large-tile kernel launches (0 = one per compute
+ * unit, the default).  For sharing the device with other work, and for tests that want many
+ * tiles per workgroup on a small problem. */
+ngemm_status ngemm_set_max_workgroups(ngemm_ctx *ctx, int max_workgroups);
+
 /*
  * Size in bytes of the packed form of a K x N int8 operand (pure function, no
  * device needed).  Kp = K rounded up to 64, Np = N rounded up to 32; the size

@@ -26,7 +26,7 @@ NGEMM_KERNEL_TILE_128 = 2
 NGEMM_KERNEL_TILE_256 = 3
 
 EXPORTS = (
-    "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel",
+    "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_set_max_workgroups",
     "ngemm_packed_b_bytes", "ngemm_pack_b", "ngemm_packed_b_free", "ngemm_packed_b_shape",
     "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_u8s8u8_requant",
     "ngemm_batched_workspace_bytes", "ngemm_run_batched_u8s8s32",
@@ -51,6 +51,7 @@ _lib.ngemm_status_string.argtypes = [_int]
 _lib.ngemm_create.argtypes = [ctypes.POINTER(_p), _int]
 _lib.ngemm_destroy.argtypes = [_p]
 _lib.ngemm_set_kernel.argtypes = [_p, _int]
+_lib.ngemm_set_max_workgroups.argtypes = [_p, _int]
 _lib.ngemm_packed_b_bytes.restype = _sz
 _lib.ngemm_packed_b_bytes.argtypes = [_i64, _i64]
 _lib.ngemm_pack_b.argtypes = [_p, _i64, _i64, _p, _i64, _p, _sz, _p, ctypes.POINTER(_p)]
@@ -64,7 +65,7 @@ _lib.ngemm_run_u8s8u8_requant.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _f
 _lib.ngemm_batched_workspace_bytes.restype = _sz
 _lib.ngemm_batched_workspace_bytes.argtypes = [_int, ctypes.POINTER(ngemm_problem)]
 _lib.ngemm_run_batched_u8s8s32.argtypes = [_p, _int, ctypes.POINTER(ngemm_problem), _p, _sz, _p]
-for _name in ("ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_pack_b", "ngemm_packed_b_free",
+for _name in ("ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_set_max_workgroups", "ngemm_pack_b", "ngemm_packed_b_free",
               "ngemm_packed_b_shape", "ngemm_run_u8s8s32", "ngemm_run_u8s8u8_requant",
               "ngemm_run_batched_u8s8s32"):
     getattr(_lib, _name).restype = _int
@@ -115,6 +116,10 @@ def ngemm_destroy(ctx):
 
 def ngemm_set_kernel(ctx, kernel):
     _check(_lib.ngemm_set_kernel(ctx, int(kernel)), "ngemm_set_kernel")
+
+
+def ngemm_set_max_workgroups(ctx, max_workgroups):
+    _check(_lib.ngemm_set_max_workgroups(ctx, int(max_workgroups)), "ngemm_set_max_workgroups")
 
 
 def ngemm_packed_b_bytes(K, N):

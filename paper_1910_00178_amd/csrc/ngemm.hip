@@ -16,6 +16,7 @@ struct ngemm_ctx {
     int device;
     int num_cus;
     int force_kernel;
+    int max_workgroups;      // 0 = one per compute unit
 };
 
 struct ngemm_packed_b {
@@ -32,6 +33,10 @@ constexpr uint32_t kCtxMagic = 0x4e47454du;   // "NGEM"
 constexpr uint32_t kPackMagic = 0x4e47504bu;  // "NGPK"
 constexpr int64_t kMaxDim = 0x7fffffff - 4096;
 constexpr int kSkinnyMaxM = 32;
+#ifndef NGEMM_BK256
+#define NGEMM_BK256 64
+#endif
+constexpr int BK256 = NGEMM_BK256;               // stage depth of the 256 x 256 configuration
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
@@ -53,18 +58,64 @@ struct DeviceGuard {
 bool ctx_ok(const ngemm_ctx *c) { return c && c->magic == kCtxMagic; }
 bool pack_ok(const ngemm_packed_b *b) { return b && b->magic == kPackMagic; }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int BK>
 hipError_t launch_tile(const GemmParams &p0, bool requant, hipStream_t st)
 {
+    using Cfg = TileCfg<BM, BN, WGM, WGN, BK>;
     GemmParams p = p0;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WGM * WGN * 64);
+    const size_t smem = Cfg::kLdsBytes;
     if (requant)
-        hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, BK, true>), grid, block, smem, st, p);
     else
-        hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, false>), grid, block, 0, st, p);
+        hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, BK, false>), grid, block, smem, st, p);
     return hipGetLastError();
+}
+
+// Kernels whose LDS need exceeds the 64 KiB default must be opted in once per device.
+template <int BM, int BN, int WGM, int WGN, int BK>
+hipError_t allow_big_lds()
+{
+    using Cfg = TileCfg<BM, BN, WGM, WGN, BK>;
+    if (Cfg::kLdsBytes <= 64 * 1024) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_tile_kernel<BM, BN, WGM, WGN, BK, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)gemm_tile_kernel<BM, BN, WGM, WGN, BK, false>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+}
+
+template <int BM, int BN, int WGM, int WGN>
+hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipStream_t st)
+{
+    using Cfg = DmaCfg<BM, BN, WGM, WGN, 4>;
+    GemmParams p = p0;
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    // Persistent workgroups, one per compute unit (the LDS ring allows no second one anyway).
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int nwg = ntiles < num_cus ? ntiles : num_cus;
+    dim3 grid((unsigned)nwg), block(WGM * WGN * 64);
+    const size_t smem = Cfg::kLdsBytes;
+    if (requant)
+        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, 4, true>), grid, block, smem, st, p);
+    else
+        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, 4, false>), grid, block, smem, st, p);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int WGM, int WGN>
+hipError_t allow_big_lds_dma()
+{
+    using Cfg = DmaCfg<BM, BN, WGM, WGN, 4>;
+    if (Cfg::kLdsBytes <= 64 * 1024) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, 4, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, 4, false>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
 }
 
 hipError_t launch_skinny(const GemmParams &p, bool requant, hipStream_t st)
@@ -90,6 +141,12 @@ int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N)
     if (tiles(256) * 4 >= cus * 3) return NGEMM_KERNEL_TILE_256;
     if (tiles(128) * 2 >= cus) return NGEMM_KERNEL_TILE_128;
     return NGEMM_KERNEL_TILE_64;
+}
+
+int workgroup_budget(const ngemm_ctx *ctx)
+{
+    const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
+    return (ctx->max_workgroups > 0 && ctx->max_workgroups < cus) ? ctx->max_workgroups : cus;
 }
 
 struct RunArgs {
@@ -130,7 +187,7 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
 size_t rowsum_bytes(int64_t M) { return (size_t)round_up(M * 4, 256); }
 
 // Launches one validated GEMM; `ws` must hold rowsum_bytes(M) when zb != 0.
-ngemm_status launch_run(const RunArgs &a, int kernel, void *ws, hipStream_t st)
+ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hipStream_t st)
 {
     const ngemm_packed_b *B = a.B;
     if (a.M == 0 || B->N == 0) return NGEMM_OK;
@@ -163,9 +220,15 @@ ngemm_status launch_run(const RunArgs &a, int kernel, void *ws, hipStream_t st)
     hipError_t e;
     switch (kernel) {
     case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, st); break;
-    case NGEMM_KERNEL_TILE_64: e = launch_tile<64, 64, 2, 2>(p, a.requant, st); break;
-    case NGEMM_KERNEL_TILE_128: e = launch_tile<128, 128, 2, 2>(p, a.requant, st); break;
-    case NGEMM_KERNEL_TILE_256: e = launch_tile<256, 256, 2, 2>(p, a.requant, st); break;
+    case NGEMM_KERNEL_TILE_64: e = launch_tile<64, 64, 2, 2, 64>(p, a.requant, st); break;
+    case NGEMM_KERNEL_TILE_128: e = launch_tile<128, 128, 2, 2, 64>(p, a.requant, st); break;
+    case NGEMM_KERNEL_TILE_256:
+        // direct-to-LDS copies need 16-byte aligned rows of A
+        if ((((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0)
+            e = launch_tile_dma<256, 256, 2, 2>(p, a.requant, num_cus, st);
+        else
+            e = launch_tile<256, 256, 2, 2, BK256>(p, a.requant, st);
+        break;
     default: return NGEMM_ERR_INVALID_ARG;
     }
     return e == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
@@ -183,7 +246,7 @@ ngemm_status run_common(ngemm_ctx *ctx, const RunArgs &a, void *ws, size_t ws_by
     }
     DeviceGuard g(ctx->device);
     if (!g.ok) return NGEMM_ERR_DEVICE;
-    return launch_run(a, kernel, ws, (hipStream_t)stream);
+    return launch_run(a, kernel, workgroup_budget(ctx), ws, (hipStream_t)stream);
 }
 
 }  // namespace
@@ -221,6 +284,15 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
     c->device = device_ordinal;
     c->num_cus = prop.multiProcessorCount;
     c->force_kernel = NGEMM_KERNEL_AUTO;
+    c->max_workgroups = 0;
+    {
+        DeviceGuard g(device_ordinal);
+        if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
+            allow_big_lds_dma<256, 256, 2, 2>() != hipSuccess) {
+            delete c;
+            return NGEMM_ERR_DEVICE;
+        }
+    }
     *out = c;
     return NGEMM_OK;
 }
@@ -239,6 +311,13 @@ ngemm_status ngemm_set_kernel(ngemm_ctx *ctx, int kernel)
     if (!ctx_ok(ctx)) return NGEMM_ERR_INVALID_ARG;
     if (kernel < NGEMM_KERNEL_AUTO || kernel >= NGEMM_KERNEL_COUNT) return NGEMM_ERR_INVALID_ARG;
     ctx->force_kernel = kernel;
+    return NGEMM_OK;
+}
+
+ngemm_status ngemm_set_max_workgroups(ngemm_ctx *ctx, int max_workgroups)
+{
+    if (!ctx_ok(ctx) || max_workgroups < 0) return NGEMM_ERR_INVALID_ARG;
+    ctx->max_workgroups = max_workgroups;
     return NGEMM_OK;
 }
 
@@ -365,7 +444,7 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         (void)validate_run(ctx, a, &kernel);
         void *ws = (uint8_t *)workspace_dev + off;
         if (q.b_zero_point != 0 && q.M > 0 && q.B->N > 0 && q.B->K > 0) off += rowsum_bytes(q.M);
-        ngemm_status s = launch_run(a, kernel, ws, (hipStream_t)hip_stream);
+        ngemm_status s = launch_run(a, kernel, workgroup_budget(ctx), ws, (hipStream_t)hip_stream);
         if (s != NGEMM_OK) return s;
     }
     return NGEMM_OK;

@@ -165,18 +165,33 @@ __global__ __launch_bounds__(256) void rowsum_a_kernel(const uint8_t *__restrict
 
 // ---- tiled MFMA kernel ----------------------------------------------------------------------
 // Workgroup tile BM x BN, WGM x WGN wavefronts, each owning (TM*32) x (TN*32) of C in
-// accumulators.  A and B stages sit in LDS in fragment order (lane l's 16 bytes at 16*l of
-// its fragment), so every fragment read is one conflict-free 16-byte-per-lane LDS load.
-template <int BM, int BN, int WGM, int WGN>
+// accumulators; BK bytes of K are staged per main-loop step, double buffered in LDS.
+//
+// LDS layout of a stage.  B: the packed fragments as they are (lane l's 16 bytes at 16*l of
+// its 1 KiB fragment), so the global->LDS copy is linear and every fragment read is one
+// conflict-free 16-byte-per-lane LDS load.  A (row-major in memory, fragment order needed by
+// the matrix instruction): 16-byte chunk (row r, k-chunk c) goes to 16-byte slot
+//     (r/32) * (CPR*32) + c*32 + ((r%32) xor (c*SW)),   CPR = BK/16, SW = 16/CPR,
+// which keeps both sides conflict-free: a fragment read (fixed c, 16 consecutive rows) and a
+// stage write (CPR consecutive lanes cover BK contiguous bytes of one row, so the global load
+// is coalesced, and 16 consecutive lanes still hit 16 different 16-byte bank groups).
+template <int BM, int BN, int WGM, int WGN, int BK>
 struct TileCfg {
     static constexpr int kThreads = WGM * WGN * 64;
     static constexpr int TM = BM / (WGM * 32);
     static constexpr int TN = BN / (WGN * 32);
-    static constexpr int kAChunks = BM * kBK / 16;            // 16-byte chunks per A stage
-    static constexpr int kBChunks = BN * kBK / 16;
+    static constexpr int KS = BK / 32;                        // matrix-instruction sub-steps per stage
+    static constexpr int CPR = BK / 16;                       // 16-byte chunks per A row per stage
+    static constexpr int SW = 16 / CPR;
+    static constexpr int kAChunks = BM * BK / 16;
+    static constexpr int kBChunks = BN * BK / 16;
     static constexpr int kAIters = kAChunks / kThreads;
     static constexpr int kBIters = kBChunks / kThreads;
-    static constexpr int kStageBytes = (BM + BN) * kBK;
+    static constexpr int kABytes = BM * BK;
+    static constexpr int kStageBytes = (BM + BN) * BK;
+    static constexpr int kEpiBytes = WGM * WGN * 32 * (TN * 128 + 16) + BN * 4;   // epilogue: transposition patches + column terms
+    static constexpr int kLdsBytes = 2 * kStageBytes > kEpiBytes ? 2 * kStageBytes : kEpiBytes;
+    static_assert(BK == 64 || BK == 128, "stage depth");
     static_assert(kAChunks % kThreads == 0 && kBChunks % kThreads == 0, "loader shape");
     static_assert(TM >= 1 && TN >= 1, "wave tile");
 };
@@ -201,12 +216,153 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = in_group / gsize;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool REQUANT>
+// Workgroup barrier that orders LDS traffic only: outstanding global loads (the prefetch of a
+// later stage) stay in flight across it.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Epilogue shared by the tiled kernels: zero-point terms, optional requantisation, stores.
+// acc[i][j] is the accumulator of A block i, B block j of this wavefront with the packed
+// operand as the first matrix-instruction source: lane l holds row l%32 of the A block and, in
+// registers 4q..4q+3, the four consecutive columns 8q + 4*(l/32) + (0..3) of the B block.
+//
+// int32 results leave through an LDS patch per wavefront (`xpose`, this wavefront's own,
+// 32 rows x TN*128 bytes): a row of TN blocks is written in accumulator order and read back
+// row-wise, so that one store instruction writes full 128-byte lines (TN*128 contiguous bytes per
+// row) instead of 32-byte pieces of 32 different lines; the L2 takes one request per line piece,
+// whatever its size.  Rows are padded by one 16-byte chunk (row stride TN*128 + 16 bytes): the
+// writes (16 rows, one chunk) then fall into 16 different bank groups, the reads (consecutive
+// chunks of a row) do anyway, and every offset besides the lane's own base is a constant.
+//
+// The column terms (128 - za) * colsum[j]: after the transposition a lane keeps the same four
+// columns for all its stores, so it loads them once, before any store (a load placed between
+// stores to C would be serialised behind them: C may alias anything as far as the compiler
+// knows).  The requantised path stores bytes straight from the accumulator layout and takes its
+// column terms from LDS (`cterm_lds`, BN words) for the same reason.
+// Must be called by all threads of the workgroup; `xpose` and `cterm_lds` must not be in use.
+template <int TN>
+__device__ __forceinline__ int xpose_off(int r, int c)
+{
+    return r * (TN * 128 + 16) + c * 16;
+}
+template <int TN>
+constexpr int kXposeBytes = 32 * (TN * 128 + 16);      // per wavefront
+
+template <int TM, int TN, int BN, bool REQUANT>
+__device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[TM][TN], int m0, int n0, int wm,
+                                              int wn, int lane, int tid, int nthreads, uint8_t *xpose,
+                                              uint32_t *cterm_lds)
+{
+    const bool c_vec_ok = REQUANT ? ((((uintptr_t)p.C | (uintptr_t)p.ldc) & 3) == 0) : true;
+    constexpr int LPR = TN * 8, RPP = 64 / LPR, NPASS = 32 / RPP;   // read-back: LPR lanes per row
+    const int bcol = n0 + wn * TN * 32 + 4 * (lane % LPR);
+    const bool interior = m0 + (wm + 1) * TM * 32 <= p.M && n0 + (wn + 1) * TN * 32 <= p.N;   // this wavefront's part
+    uint4 ct_back = {0u, 0u, 0u, 0u};
+    if (REQUANT) {
+        for (int c = tid; c < BN; c += nthreads) {
+            const int col = n0 + c;
+            cterm_lds[c] = col < p.N ? p.za_term * (uint32_t)p.colsum[col] : 0u;
+        }
+        __syncthreads();
+    } else if (bcol < p.N) {
+        // after the transposition a lane keeps the same four columns for every row it stores
+        const int4 cs = *(const int4 *)(p.colsum + bcol);            // colsum is padded to 32 columns
+        ct_back.x = p.za_term * (uint32_t)cs.x; ct_back.y = p.za_term * (uint32_t)cs.y;
+        ct_back.z = p.za_term * (uint32_t)cs.z; ct_back.w = p.za_term * (uint32_t)cs.w;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = m0 + (wm * TM + i) * 32 + (lane & 31);
+        if (REQUANT && row >= p.M) continue;
+        uint32_t row_term = p.kconst;
+        if (p.rowsum && row < p.M) row_term -= p.zb * (uint32_t)p.rowsum[row];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int lcol = (wn * TN + j) * 32 + 8 * q + 4 * (lane >> 5);
+                const int col = n0 + lcol;
+                if (REQUANT && col >= p.N) continue;
+                uint4 ct = {0u, 0u, 0u, 0u};
+                if (REQUANT) ct = *(const uint4 *)(cterm_lds + lcol);
+                int32_t v[4];
+                v[0] = (int32_t)((uint32_t)acc[i][j][4 * q + 0] + ct.x + row_term);
+                v[1] = (int32_t)((uint32_t)acc[i][j][4 * q + 1] + ct.y + row_term);
+                v[2] = (int32_t)((uint32_t)acc[i][j][4 * q + 2] + ct.z + row_term);
+                v[3] = (int32_t)((uint32_t)acc[i][j][4 * q + 3] + ct.w + row_term);
+                if (REQUANT) {
+                    uint8_t *dst = (uint8_t *)p.C + (int64_t)row * p.ldc + col;
+                    uint8_t b[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) b[t] = requant_u8(v[t], p.scale, p.zc);
+                    if (col + 3 < p.N && c_vec_ok) {
+                        *(uint32_t *)dst = (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16) |
+                                           ((uint32_t)b[3] << 24);
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (col + t < p.N) dst[t] = b[t];
+                    }
+                } else {
+                    // row r = lane%32 of the block row, chunk c = 8j + 2q + lane/32
+                    v4i o;
+                    o.x = v[0]; o.y = v[1]; o.z = v[2]; o.w = v[3];
+                    *(v4i *)(xpose + xpose_off<TN>(lane & 31, 8 * j + 2 * q + (lane >> 5))) = o;
+                }
+            }
+        }
+        if (!REQUANT) {
+            // read the block row back row-wise, add the column terms, store full lines
+            const int brow0 = m0 + (wm * TM + i) * 32;
+            int32_t *dst0 = (int32_t *)p.C + (int64_t)(brow0 + lane / LPR) * p.ldc + bcol;
+            if (interior) {
+                // no predicates: all LDS reads first, then all stores
+                v4i o[NPASS];
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
+                    o[pass] = *(const v4i *)(xpose + xpose_off<TN>(RPP * pass + lane / LPR, lane % LPR));
+                }
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
+                    v4i v = o[pass];
+                    v.x = (int)((uint32_t)v.x + ct_back.x); v.y = (int)((uint32_t)v.y + ct_back.y);
+                    v.z = (int)((uint32_t)v.z + ct_back.z); v.w = (int)((uint32_t)v.w + ct_back.w);
+                    __builtin_memcpy(dst0 + (int64_t)(RPP * pass) * p.ldc, &v, 16);   // 4-byte aligned is enough
+                }
+            } else {
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
+                    const int r = RPP * pass + lane / LPR;
+                    v4i v = *(const v4i *)(xpose + xpose_off<TN>(r, lane % LPR));
+                    v.x = (int)((uint32_t)v.x + ct_back.x); v.y = (int)((uint32_t)v.y + ct_back.y);
+                    v.z = (int)((uint32_t)v.z + ct_back.z); v.w = (int)((uint32_t)v.w + ct_back.w);
+                    if (brow0 + r < p.M && bcol < p.N) {
+                        int32_t *dst = dst0 + (int64_t)(RPP * pass) * p.ldc;
+                        if (bcol + 3 < p.N) {
+                            __builtin_memcpy(dst, &v, 16);
+                        } else {
+                            dst[0] = v.x;
+                            if (bcol + 1 < p.N) dst[1] = v.y;
+                            if (bcol + 2 < p.N) dst[2] = v.z;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmParams p)
 {
-    using Cfg = TileCfg<BM, BN, WGM, WGN>;
-    constexpr int TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::kThreads;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * Cfg::kStageBytes];
+    using Cfg = TileCfg<BM, BN, WGM, WGN, BK>;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::kThreads, KS = Cfg::KS;
+    constexpr int CPR = Cfg::CPR, SW = Cfg::SW, AI = Cfg::kAIters, BI = Cfg::kBIters;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -214,59 +370,58 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmPar
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int nslices = p.Kp / 32;
-    const int nkt = p.Kp / kBK;
+    const int nfull = p.K / BK;                        // stages that lie completely inside K
+    const bool has_tail = nfull * BK < p.Kp;
 
-    // Per-thread source addresses of this thread's chunks (k advances by kBK per step).
-    const uint8_t *a_src[Cfg::kAIters];
-    int a_koff[Cfg::kAIters];
+    // This thread's chunks of a stage: source addresses (k advances by BK per stage) and LDS slots.
+    const uint8_t *a_src[AI];
+    int a_dst[AI];
 #pragma unroll
-    for (int i = 0; i < Cfg::kAIters; ++i) {
-        int c = tid + i * NT;
-        int f = c >> 6, l = c & 63;
-        int row = (f >> 1) * 32 + (l & 31);
-        int kc = (f & 1) * 2 + (l >> 5);
-        int grow = m0 + row;
+    for (int i = 0; i < AI; ++i) {
+        const int q = tid + i * NT;
+        const int r = q / CPR, c = q % CPR;
+        int grow = m0 + r;
         grow = grow < p.M ? grow : p.M - 1;            // rows past M: read a valid row, never stored
-        a_koff[i] = kc * 16;
-        a_src[i] = p.A + (int64_t)grow * p.lda + kc * 16;
+        a_src[i] = p.A + (int64_t)grow * p.lda + c * 16;
+        a_dst[i] = ((r >> 5) * (CPR * 32) + c * 32 + ((r & 31) ^ (c * SW))) * 16;
     }
-    const uint8_t *b_src[Cfg::kBIters];
+    const uint8_t *b_src[BI];
 #pragma unroll
-    for (int i = 0; i < Cfg::kBIters; ++i) {
-        int c = tid + i * NT;
-        int nb = c >> 7, within = c & 127;
+    for (int i = 0; i < BI; ++i) {
+        const int q = tid + i * NT;
+        const int nb = q / (KS * 64), within = q % (KS * 64);
         int pnl = n0 / 32 + nb;
         pnl = pnl < p.npanels ? pnl : p.npanels - 1;   // panels past N: read a valid panel, never stored
         b_src[i] = p.Bp + ((int64_t)pnl * nslices) * kFragBytes + within * 16;
     }
+    // Fragment read offsets of this lane inside the A part of a stage, one per sub-step.
+    int a_frag_off[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const int c = 2 * ks + (lane >> 5);
+        a_frag_off[ks] = (wm * TM * (CPR * 32) + c * 32 + ((lane & 31) ^ (c * SW))) * 16;
+    }
+    const int b_frag_off = Cfg::kABytes + (wn * TN * KS) * kFragBytes + lane * 16;
 
-    v4i ra[Cfg::kAIters], rb[Cfg::kBIters];
-    auto load_stage = [&](int kt) {
-        const int kbase = kt * kBK;
-        const bool full = kbase + kBK <= p.K;
-#pragma unroll
-        for (int i = 0; i < Cfg::kAIters; ++i) {
-            const uint8_t *src = a_src[i] + kbase;
-            if (full) {
-                ra[i] = load16_any(src);
-            } else {
-                int valid = p.K - (kbase + a_koff[i]);
-                ra[i] = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < Cfg::kBIters; ++i)
-            rb[i] = *(const v4i *)(b_src[i] + (int64_t)kt * (2 * kFragBytes));
+    v4i ra[AI], rb[BI];
+    auto gload_a = [&](int i, int kt) { ra[i] = load16_any(a_src[i] + (int64_t)kt * BK); };
+    auto gload_b = [&](int i, int kt) { rb[i] = *(const v4i *)(b_src[i] + (int64_t)kt * (KS * kFragBytes)); };
+    auto sstore_a = [&](int i, int buf) {
+        *(v4i *)(lds + buf * Cfg::kStageBytes + a_dst[i]) = shift_u8_to_s8(ra[i]);
     };
-    auto store_stage = [&](int buf) {
-        uint8_t *As = lds + buf * Cfg::kStageBytes;
-        uint8_t *Bs = As + BM * kBK;
+    auto sstore_b = [&](int i, int buf) {
+        *(v4i *)(lds + buf * Cfg::kStageBytes + Cfg::kABytes + (tid + i * NT) * 16) = rb[i];
+    };
+
+    v4i fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int buf, int ks, int slot) {
+        const uint8_t *base = lds + buf * Cfg::kStageBytes;
 #pragma unroll
-        for (int i = 0; i < Cfg::kAIters; ++i)
-            *(v4i *)(As + (tid + i * NT) * 16) = shift_u8_to_s8(ra[i]);
+        for (int i = 0; i < TM; ++i)
+            fa[slot][i] = *(const v4i *)(base + a_frag_off[ks] + i * (CPR * 32 * 16));
 #pragma unroll
-        for (int i = 0; i < Cfg::kBIters; ++i)
-            *(v4i *)(Bs + (tid + i * NT) * 16) = rb[i];
+        for (int j = 0; j < TN; ++j)
+            fb[slot][j] = *(const v4i *)(base + b_frag_off + (j * KS + ks) * kFragBytes);
     };
 
     v16i acc[TM][TN];
@@ -277,51 +432,396 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmPar
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    if (nkt > 0) {
-        load_stage(0);
-        store_stage(0);
-        __syncthreads();
-    }
-    for (int kt = 0; kt < nkt; ++kt) {
-        const bool more = kt + 1 < nkt;
-        if (more) load_stage(kt + 1);
-        const uint8_t *As = lds + (kt & 1) * Cfg::kStageBytes;
-        const uint8_t *Bs = As + BM * kBK;
+    // Matrix instruction with the packed operand first: lane l then holds, for row l%32 of the
+    // A block, the four consecutive columns 8*(r/4) + 4*(l/32) + r%4 of the B block in
+    // registers r = 4q..4q+3, so the epilogue stores 16 contiguous bytes per lane.
+    auto mma_one = [&](int slot, int i, int j) {
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+    };
+
+    if (nfull > 0) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v4i af[TM], bf[TN];
+        for (int i = 0; i < AI; ++i) gload_a(i, 0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = *(const v4i *)(As + (((wm * TM + i) * 2 + ks) * kFragBytes) + lane * 16);
+        for (int i = 0; i < BI; ++i) gload_b(i, 0);
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bf[j] = *(const v4i *)(Bs + (((wn * TN + j) * 2 + ks) * kFragBytes) + lane * 16);
+        for (int i = 0; i < AI; ++i) sstore_a(i, 0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < BI; ++i) sstore_b(i, 0);
+        const int kt1 = nfull > 1 ? 1 : 0;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) store_stage((kt + 1) & 1);
-        __syncthreads();
+        for (int i = 0; i < AI; ++i) gload_a(i, kt1);
+#pragma unroll
+        for (int i = 0; i < BI; ++i) gload_b(i, kt1);
+        lds_barrier();
+        read_frags(0, 0, 0);
     }
 
-    // Epilogue.  Accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its
-    // 32 x 32 block: consecutive lanes write consecutive columns of one row.
+    // Main loop over full stages.  Per stage: sub-step ks computes from fragment registers
+    // slot ks&1 while the fragments of sub-step ks+1 are being read from LDS; during sub-step 0
+    // the next stage (already in registers) is written to the other LDS buffer and the stage
+    // after it is requested from memory.
+    // The prefetch indices are clamped to the last full stage instead of being predicated: the
+    // final iterations re-load and re-store that stage into a buffer nobody reads any more,
+    // which keeps the loop body free of branches.
+    for (int kt = 0; kt < nfull; ++kt) {
+        const int cur = kt & 1, nxt = cur ^ 1;
+        const int kt2 = kt + 2 < nfull ? kt + 2 : nfull - 1;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-        if (col >= p.N) continue;
-        const uint32_t cs_term = p.za_term * (uint32_t)p.colsum[col];
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) {
+                read_frags(cur, ks + 1, (ks + 1) & 1);
+            } else {
+                lds_barrier();                          // next stage is complete in LDS[nxt]
+                read_frags(nxt, 0, 0);
+            }
+            // Scheduling fences: keep the fragment reads above the matrix ops that hide their
+            // latency, and keep the prefetch pieces between the matrix ops where they are written.
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks == 0) {
+                // interleave: matrix ops with the LDS writes / global loads of the prefetch
+                constexpr int NM = TM * TN;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int rbase = m0 + (wm * TM + i) * 32 + 4 * (lane >> 5);
+                for (int m = 0; m < NM; ++m) {
+                    mma_one(0, m / TN, m % TN);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = rbase + 8 * (r >> 2) + (r & 3);
-                if (row < p.M) store_out<REQUANT>(p, row, col, acc[i][j][r], cs_term);
+                    for (int i = 0; i < AI; ++i)
+                        if (i * NM / AI == m) {
+                            sstore_a(i, nxt);
+                            gload_a(i, kt2);
+                        }
+#pragma unroll
+                    for (int i = 0; i < BI; ++i)
+                        if (i * NM / BI == m) {
+                            sstore_b(i, nxt);
+                            gload_b(i, kt2);
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) mma_one(ks & 1, i, j);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // K tail: the last, partial stage (K not a multiple of BK).  Guarded loads, no pipelining.
+    if (has_tail) {
+        const int kbase = nfull * BK;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < AI; ++i) {
+            const int q = tid + i * NT;
+            const int kk = kbase + (q % CPR) * 16;
+            const int valid = p.K - kk;
+            const uint8_t *src = a_src[i] + kbase;
+            ra[i] = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
+            sstore_a(i, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < BI; ++i) {
+            const int q = tid + i * NT;
+            const int f = (q % (KS * 64)) >> 6;          // fragment of the stage this chunk is in
+            v4i z = {0, 0, 0, 0};
+            rb[i] = (nfull * KS + f < nslices) ? *(const v4i *)(b_src[i] + (int64_t)nfull * (KS * kFragBytes)) : z;
+            sstore_b(i, 0);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            read_frags(0, ks, 0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) mma_one(0, i, j);
+        }
+    }
+
+    __syncthreads();                                   // every wavefront is done with the stage buffers
+    tile_epilogue<TM, TN, BN, REQUANT>(p, acc, m0, n0, wm, wn, lane, tid, NT, lds + wave * kXposeBytes<TN>,
+                                       (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>));
+}
+
+// ---- tiled MFMA kernel, direct-to-LDS variant -------------------------------------------------
+// Same tiling and epilogue, but each stage (64 bytes of K) is copied memory -> LDS by the
+// load unit itself (global_load_lds_dwordx4: no register staging, no LDS store instructions),
+// into a ring of NSTAGE stage buffers.  The loads of stage s are issued three stages before
+// s is consumed, which is what hides the latency of a miss in the XCD's L2 when only one
+// wavefront per SIMD is resident.  Needs A 16-byte aligned with lda a multiple of 16; the
+// host falls back to the register-staged kernel otherwise.
+//
+// LDS layout of a stage: 1 KiB blocks, one per wavefront-wide load (lane j writes bytes
+// 16j..16j+15 of its block, as the hardware prescribes).
+//   A block b = rows 16b..16b+15: lane j = 4t + u loads row 16b+t, 16-byte chunk
+//     c = (u - t/4) mod 4, so four consecutive lanes still read 64 contiguous bytes of one row,
+//     and chunk (t, c) sits in slot 4t + (c + t/4) mod 4: the 16 rows a fragment read touches
+//     for a fixed c fall into 16 different 16-byte bank groups.
+//   B block q = fragment q%2 of panel q/2 of the tile, copied as it is.
+// The u8 -> s8 shift (xor 0x80) is applied to the A fragments after they are read from LDS.
+template <int BM, int BN, int WGM, int WGN, int NSTAGE>
+struct DmaCfg {
+    static constexpr int BK = 64;
+    static constexpr int KS = 2;
+    static constexpr int kWaves = WGM * WGN;
+    static constexpr int kThreads = kWaves * 64;
+    static constexpr int TM = BM / (WGM * 32);
+    static constexpr int TN = BN / (WGN * 32);
+    static constexpr int kABlocks = BM / 16;
+    static constexpr int kBBlocks = BN / 16;
+    static constexpr int kAIters = kABlocks / kWaves;
+    static constexpr int kBIters = kBBlocks / kWaves;
+    static constexpr int kABytes = BM * BK;
+    static constexpr int kStageBytes = (BM + BN) * BK;
+    static constexpr int kLdsBytes = NSTAGE * kStageBytes;
+    static constexpr int kLoadsPerStage = kAIters + kBIters;   // per thread
+    static_assert(kLdsBytes >= kWaves * 32 * (TN * 128 + 16) + BN * 4, "room for the epilogue patches");
+    static_assert(kABlocks % kWaves == 0 && kBBlocks % kWaves == 0, "loader shape");
+    static_assert(NSTAGE == 4, "the wait counts below assume a four-stage ring");
+    static_assert(2 * kLoadsPerStage <= 63, "vmcnt range");
+};
+
+// s_waitcnt for the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// vmcnt <= N and lgkmcnt == 0: this wavefront's older copies have landed in LDS and its own
+// LDS reads have returned.  Used right before a bare s_barrier in the direct-to-LDS kernel,
+// where a workgroup fence would also wait for the younger copies that must stay in flight.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_and_lds()
+{
+    __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
+}
+
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool REQUANT>
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const GemmParams p)
+{
+    using Cfg = DmaCfg<BM, BN, WGM, WGN, NSTAGE>;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, KS = Cfg::KS, BK = Cfg::BK;
+    constexpr int AI = Cfg::kAIters, BI = Cfg::kBIters, NW = Cfg::kWaves;
+    constexpr int LPS = Cfg::kLoadsPerStage;
+    constexpr int NM = TM * TN;
+    constexpr int NR = TM + TN;                         // fragment reads per slot
+    constexpr int RG = (NR + 1) / 2;                    // gaps used for reads (two per gap)
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int nslices = p.Kp / 32;
+    const int nfull = p.K / BK;
+    const bool has_tail = nfull * BK < p.Kp;
+
+    // Persistent workgroups: workgroup w owns tiles w, w + G, w + 2G, ... of the XCD-aware order
+    // (G = grid size: one workgroup per compute unit when there is enough work; the LDS ring and
+    // the 512 registers per lane leave no room for a second one anyway).
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int G = gridDim.x, w = blockIdx.x;
+
+    const int t16 = lane >> 2;
+    const int a_chunk = ((lane & 3) - (t16 >> 2)) & 3;
+    int a_frag_off[KS];
+    {
+        const int r = lane & 31, t = r & 15;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int c = 2 * ks + (lane >> 5);
+            a_frag_off[ks] = (wm * TM * 2 + (r >> 4)) * 1024 + (4 * t + ((c + (t >> 2)) & 3)) * 16;
+        }
+    }
+    const int b_frag_off = Cfg::kABytes + (wn * TN * KS) * kFragBytes + lane * 16;
+
+    for (int tile = w; tile < ntiles; tile += G) {
+        int tm, tn;
+        tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
+        const int m0 = tm * BM, n0 = tn * BN;
+
+        // Loader: this lane's source addresses for the blocks its wavefront copies.
+        const uint8_t *a_src[AI];
+#pragma unroll
+        for (int i = 0; i < AI; ++i) {
+            int grow = m0 + (wave + NW * i) * 16 + t16;
+            grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
+            a_src[i] = p.A + (int64_t)grow * p.lda + a_chunk * 16;
+        }
+        const uint8_t *b_src[BI];
+#pragma unroll
+        for (int i = 0; i < BI; ++i) {
+            const int q = wave + NW * i;
+            int pnl = n0 / 32 + (q >> 1);
+            pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
+            b_src[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes + lane * 16;
+        }
+        auto dma_a = [&](int i, int kt, int buf) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + (int64_t)kt * BK),
+                                             (lptr_t)(lds + buf * Cfg::kStageBytes + (wave + NW * i) * 1024), 16, 0,
+                                             0);
+        };
+        auto dma_b = [&](int i, int kt, int buf) {
+            __builtin_amdgcn_global_load_lds(
+                (gptr_t)(b_src[i] + (int64_t)kt * (KS * kFragBytes)),
+                (lptr_t)(lds + buf * Cfg::kStageBytes + Cfg::kABytes + (wave + NW * i) * 1024), 16, 0, 0);
+        };
+        auto dma_stage = [&](int kt, int buf) {
+#pragma unroll
+            for (int i = 0; i < AI; ++i) dma_a(i, kt, buf);
+#pragma unroll
+            for (int i = 0; i < BI; ++i) dma_b(i, kt, buf);
+        };
+
+        v4i fa[2][TM], fb[2][TN];
+        auto read_one = [&](int buf, int ks, int slot, int idx) {
+            const uint8_t *base = lds + buf * Cfg::kStageBytes;
+            if (idx < TM)
+                fa[slot][idx] = *(const v4i *)(base + a_frag_off[ks] + idx * 2048);
+            else
+                fb[slot][idx - TM] = *(const v4i *)(base + b_frag_off + ((idx - TM) * KS + ks) * kFragBytes);
+        };
+        auto read_frags = [&](int buf, int ks, int slot) {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) read_one(buf, ks, slot, r);
+        };
+        auto shift_frags = [&](int slot) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[slot][i] = shift_u8_to_s8(fa[slot][i]);
+        };
+        auto xor_gap = [&](int i) { return (NM - 1 - TM + i) > 0 ? (NM - 1 - TM + i) : 0; };
+
+        v16i acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+        // Matrix instruction with the packed operand first: lane l then holds, for row l%32 of
+        // the A block, the four consecutive columns 8*(r/4) + 4*(l/32) + r%4 of the B block in
+        // registers r = 4q..4q+3.
+        auto mma_one = [&](int slot, int i, int j) {
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+        };
+
+        // Stage indices past the last full stage are clamped to it: the extra copies land in
+        // buffers nobody reads any more and keep the outstanding-copy counts uniform.
+        auto clampk = [&](int it) { return it < nfull ? it : nfull - 1; };
+
+        // The previous tile's LDS traffic (last stage, K tail, epilogue patches) must be over
+        // before this tile's copies overwrite the buffers.
+        if (tile != w) __syncthreads();
+
+        // Software pipeline, one iteration per stage (two sub-steps of TM*TN matrix ops each).
+        // Everything else is issued in the gaps between matrix ops so the matrix pipe never waits:
+        //   sub-step 0 (fragment slot 0 = stage it, k-half 0):
+        //       first gaps : LDS reads of slot 1 (stage it, k-half 1)
+        //       middle     : wait until this wavefront's copies of stage it+1 have landed, barrier
+        //                    (=> stage it+1 is complete for everybody, stage it-1 is free)
+        //       last gaps  : u8 -> s8 shift of slot 1's A fragments (long since returned)
+        //   sub-step 1 (slot 1):
+        //       first gaps : LDS reads of slot 0 for stage it+1, k-half 0
+        //       then       : copies of stage it+3 into the buffer of stage it-1
+        //       last gaps  : shift of slot 0's A fragments
+        // The barrier of iteration it is what makes the reads of stage it+1 (issued after it) and
+        // the overwrite of stage it-1 (whose last reads were consumed in iteration it-1) safe.
+        // It is a bare s_barrier behind a manual wait on the copy counter: a workgroup fence
+        // would also wait for the younger copies, which must stay in flight.
+        if (nfull > 0) {
+#pragma unroll
+            for (int s = 0; s < NSTAGE - 1; ++s) dma_stage(clampk(s), s);
+            wait_vmcnt<2 * LPS>();                      // stage 0 has landed (this wavefront's part)
+            __builtin_amdgcn_s_barrier();               // ... and everybody else's
+            read_frags(0, 0, 0);
+            shift_frags(0);
+            __builtin_amdgcn_sched_barrier(0);
+
+            for (int it = 0; it < nfull; ++it) {
+                const int cur = it & (NSTAGE - 1), nxt = (it + 1) & (NSTAGE - 1), fre = (it + 3) & (NSTAGE - 1);
+                const int kload = clampk(it + 3);
+                // ---- sub-step 0 ----
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    mma_one(0, m / TN, m % TN);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int r = 0; r < NR; ++r)
+                        if (r / 2 == m || (m == NM - 1 && r / 2 > m)) read_one(cur, 1, 1, r);
+                    if (m == (NM - 1) / 2) {
+                        wait_vmcnt<LPS>();              // younger: only the copies of stage it+2
+                        __builtin_amdgcn_s_barrier();
+                    }
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        if (xor_gap(i) == m) fa[1][i] = shift_u8_to_s8(fa[1][i]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // ---- sub-step 1 ----
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    mma_one(1, m / TN, m % TN);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int r = 0; r < NR; ++r)
+                        if (r / 2 == m || (m == NM - 1 && r / 2 > m)) read_one(nxt, 0, 0, r);
+#pragma unroll
+                    for (int d = 0; d < AI + BI; ++d) {
+                        const int g = (RG + d) < NM ? (RG + d) : NM - 1;
+                        if (g == m) {
+                            if (d < AI) dma_a(d, kload, fre);
+                            else dma_b(d - AI, kload, fre);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        if (xor_gap(i) == m) fa[0][i] = shift_u8_to_s8(fa[0][i]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            wait_vmcnt<0>();                            // drain the clamped extra copies
+        }
+
+        // K tail: the last, partial stage.  Guarded register loads into buffer 0, same layout.
+        if (has_tail) {
+            const int kbase = nfull * BK;
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < AI; ++i) {
+                const int valid = p.K - (kbase + a_chunk * 16);
+                const uint8_t *src = a_src[i] + kbase;
+                v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
+                *(v4i *)(lds + (wave + NW * i) * 1024 + lane * 16) = v;
+            }
+#pragma unroll
+            for (int i = 0; i < BI; ++i) {
+                const int q = wave + NW * i;
+                v4i v = {0, 0, 0, 0};
+                if (nfull * KS + (q & 1) < nslices)
+                    v = *(const v4i *)(b_src[i] + (int64_t)nfull * (KS * kFragBytes));
+                *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) = v;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                read_frags(0, ks, 0);
+                shift_frags(0);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) mma_one(0, i, j);
             }
         }
+
+        __syncthreads();                               // every wavefront is done with the stage buffers
+        tile_epilogue<TM, TN, BN, REQUANT>(p, acc, m0, n0, wm, wn, lane, tid, Cfg::kThreads,
+                                           lds + wave * kXposeBytes<TN>, (uint32_t *)(lds + NW * kXposeBytes<TN>));
     }
 }
 

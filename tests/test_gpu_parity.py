@@ -245,6 +245,25 @@ def test_kernels_agree_with_each_other(rt, oracle):
     ng.ngemm_packed_b_free(h)
 
 
+def test_persistent_workgroups_many_tiles_each(rt, oracle):
+    """Few persistent workgroups over many 256 x 256 tiles: every workgroup walks several tiles,
+    reusing its LDS ring and epilogue patches.  Ragged M, N, K, zero-points, a leading-dimension
+    gap in C, and the requantised output."""
+    ng = ng_mod()
+    rng = np.random.default_rng(81)
+    M, N, K = 1000, 1100, 2000 + 37
+    A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+    p = wl.Problem("persistent", A, B, za=99, zb=-7, scale=float(np.float32(0.0005)), zc=120)
+    try:
+        for nwg in (1, 3, 7, 8):
+            ng.ngemm_set_max_workgroups(rt.ctx, nwg)
+            # lda_pad 27 keeps rows 16-byte aligned (K + 27 = 2064), so the direct-to-LDS kernel runs
+            check_problem(rt, oracle, p, (3,), lda_pad=27, ldc_pad=5)
+    finally:
+        ng.ngemm_set_max_workgroups(rt.ctx, 0)
+
+
 def test_error_paths_launch_nothing(rt):
     ng = ng_mod()
     B = np.ones((8, 64), np.int8)
