@@ -94,9 +94,11 @@ hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipS
     GemmParams p = p0;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
-    // Persistent workgroups, one per compute unit (the LDS ring allows no second one anyway).
+    // Persistent workgroups: as many as can be resident (the 256 x 256 configuration fills a
+    // compute unit's registers and LDS with one workgroup, the smaller ones leave room for more).
     const int ntiles = p.tiles_m * p.tiles_n;
-    const int nwg = ntiles < num_cus ? ntiles : num_cus;
+    const int per_cu = BM >= 256 ? 1 : (BM >= 128 ? 2 : 4);
+    const int nwg = ntiles < num_cus * per_cu ? ntiles : num_cus * per_cu;
     dim3 grid((unsigned)nwg), block(WGM * WGN * 64);
     const size_t smem = Cfg::kLdsBytes;
     if (requant)
@@ -122,7 +124,7 @@ hipError_t launch_skinny(const GemmParams &p, bool requant, hipStream_t st)
 {
     const int nslices = p.Kp / 32;
     int nwaves = 1;
-    while (nwaves < 16 && nwaves * 4 <= nslices) nwaves *= 2;   // about two fragments per wavefront
+    while (nwaves < 8 && nwaves * 4 <= nslices) nwaves *= 2;    // at least two fragments per wavefront, at most 8 wavefronts
     const int nregs = 4 * ((p.M + 7) / 8);
     const size_t smem = nwaves > 1 ? (size_t)nwaves * nregs * 64 * sizeof(int) : 0;
     dim3 grid((unsigned)p.npanels), block(nwaves * 64);
@@ -133,13 +135,17 @@ hipError_t launch_skinny(const GemmParams &p, bool requant, hipStream_t st)
     return hipGetLastError();
 }
 
+// Shape heuristic: the 256 x 256 configuration when it fills at least three quarters of the
+// compute units, the 128 x 128 one when every unit still gets two workgroups, else 64 x 64
+// (measured on 1024 x {768, 3072} outputs: the smallest tile wins as long as the larger ones
+// leave units idle).
 int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N)
 {
     if (M <= kSkinnyMaxM) return NGEMM_KERNEL_SKINNY;
     auto tiles = [&](int64_t b) { return ((M + b - 1) / b) * ((N + b - 1) / b); };
     const int64_t cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
     if (tiles(256) * 4 >= cus * 3) return NGEMM_KERNEL_TILE_256;
-    if (tiles(128) * 2 >= cus) return NGEMM_KERNEL_TILE_128;
+    if (tiles(128) >= cus * 2) return NGEMM_KERNEL_TILE_128;
     return NGEMM_KERNEL_TILE_64;
 }
 
@@ -218,16 +224,21 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hip
         p.rowsum = rs;
     }
     hipError_t e;
+    const bool dma_ok = (((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0;
     switch (kernel) {
     case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, st); break;
-    case NGEMM_KERNEL_TILE_64: e = launch_tile<64, 64, 2, 2, 64>(p, a.requant, st); break;
-    case NGEMM_KERNEL_TILE_128: e = launch_tile<128, 128, 2, 2, 64>(p, a.requant, st); break;
+    // direct-to-LDS copies need 16-byte aligned rows of A; the register-staged kernels take the rest
+    case NGEMM_KERNEL_TILE_64:
+        e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st)
+                   : launch_tile<64, 64, 2, 2, 64>(p, a.requant, st);
+        break;
+    case NGEMM_KERNEL_TILE_128:
+        e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st)
+                   : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
+        break;
     case NGEMM_KERNEL_TILE_256:
-        // direct-to-LDS copies need 16-byte aligned rows of A
-        if ((((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0)
-            e = launch_tile_dma<256, 256, 2, 2>(p, a.requant, num_cus, st);
-        else
-            e = launch_tile<256, 256, 2, 2, BK256>(p, a.requant, st);
+        e = dma_ok ? launch_tile_dma<256, 256, 2, 2>(p, a.requant, num_cus, st)
+                   : launch_tile<256, 256, 2, 2, BK256>(p, a.requant, st);
         break;
     default: return NGEMM_ERR_INVALID_ARG;
     }
@@ -288,7 +299,8 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
     {
         DeviceGuard g(device_ordinal);
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
-            allow_big_lds_dma<256, 256, 2, 2>() != hipSuccess) {
+            allow_big_lds_dma<256, 256, 2, 2>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
+            allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess) {
             delete c;
             return NGEMM_ERR_DEVICE;
         }

@@ -826,42 +826,69 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
 }
 
 // ---- skinny-M kernel (M <= 32) --------------------------------------------------------------
-// Bandwidth-bound: one workgroup per 32-column panel; its wavefronts split K, each streaming
-// its fragments of the packed operand straight from memory into registers (no LDS for B) and
-// the few rows of A straight from cache.  Partial 32 x 32 accumulators of the wavefronts are
-// added through LDS as whole vectors (phase 2 of Sec. 3.1: vector adds, no lane tree).
+// Bandwidth-bound: one workgroup per 32-column panel; its wavefronts split K (wavefront v takes
+// fragments v, v + nwaves, ... so that the workgroup sweeps the panel contiguously), each
+// streaming its fragments of the packed operand straight from memory into registers (no LDS for
+// B) and the few rows of A straight from cache.  Loads are issued a batch of kSkinnyBatch
+// fragments ahead of the matrix ops that consume them, so a wavefront always has 4 to 8 KiB in
+// flight.  Partial 32 x 32 accumulators of the wavefronts are added through LDS as whole vectors
+// (phase 2 of Sec. 3.1: vector adds, no lane tree).
+constexpr int kSkinnyBatch = 4;
+
 template <bool REQUANT>
-__global__ __launch_bounds__(1024) void gemm_skinny_kernel(const GemmParams p, int nregs)
+__global__ __launch_bounds__(512) void gemm_skinny_kernel(const GemmParams p, int nregs)
 {
     extern __shared__ int red[];                       // [nwaves][nregs][64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = blockDim.x >> 6;
     const int pnl = blockIdx.x;
     const int nslices = p.Kp / 32;
-    const int per_wave = (nslices + nwaves - 1) / nwaves;
-    const int s0 = wave * per_wave;
-    const int s1 = (s0 + per_wave) < nslices ? (s0 + per_wave) : nslices;
+    const int mine = nslices > wave ? (nslices - wave + nwaves - 1) / nwaves : 0;   // fragments of this wavefront
 
     const int row = lane & 31;
     const bool row_ok = row < p.M;
     const uint8_t *a_row = p.A + (int64_t)(row_ok ? row : 0) * p.lda + (lane >> 5) * 16;
     const uint8_t *b_pan = p.Bp + ((int64_t)pnl * nslices) * kFragBytes + lane * 16;
 
+    auto load_b = [&](int t) { return *(const v4i *)(b_pan + (int64_t)(wave + t * nwaves) * kFragBytes); };
+    auto load_a = [&](int t) {
+        v4i af = {0, 0, 0, 0};
+        if (row_ok) {
+            const int s = wave + t * nwaves;
+            const int valid = p.K - (s * 32 + (lane >> 5) * 16);
+            const uint8_t *src = a_row + s * 32;
+            af = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
+        }
+        return af;
+    };
+
     v16i acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0;
 
-#pragma unroll 4
-    for (int s = s0; s < s1; ++s) {
-        v4i bf = *(const v4i *)(b_pan + (int64_t)s * kFragBytes);
-        v4i af = {0, 0, 0, 0};
-        if (row_ok) {
-            int kk = s * 32 + (lane >> 5) * 16;
-            int valid = p.K - kk;
-            const uint8_t *src = a_row + s * 32;
-            af = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
+    v4i bf[2][kSkinnyBatch], af[2][kSkinnyBatch];
+    const v4i zero = {0, 0, 0, 0};
+    auto load_batch = [&](int slot, int t0) {
+#pragma unroll
+        for (int u = 0; u < kSkinnyBatch; ++u) {
+            const bool ok = t0 + u < mine;
+            bf[slot][u] = ok ? load_b(t0 + u) : zero;
+            af[slot][u] = ok ? load_a(t0 + u) : zero;
         }
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(shift_u8_to_s8(af), bf, acc, 0, 0, 0);
+    };
+    auto mma_batch = [&](int slot) {
+#pragma unroll
+        for (int u = 0; u < kSkinnyBatch; ++u)
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(shift_u8_to_s8(af[slot][u]), bf[slot][u], acc, 0, 0, 0);
+    };
+    if (mine > 0) load_batch(0, 0);
+    for (int t0 = 0; t0 < mine; t0 += 2 * kSkinnyBatch) {
+        if (t0 + kSkinnyBatch < mine) load_batch(1, t0 + kSkinnyBatch);
+        mma_batch(0);          // a padded slot holds zeros for B: adds nothing
+        if (t0 + kSkinnyBatch < mine) {
+            if (t0 + 2 * kSkinnyBatch < mine) load_batch(0, t0 + 2 * kSkinnyBatch);
+            mma_batch(1);
+        }
     }
 
     if (nwaves > 1) {
