@@ -23,9 +23,10 @@ if ROOT not in sys.path:
 INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense INT8 matrix peak, TOP/s (published)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak, GB/s (published)
 
-# HBM bytes per launch of the 8192^3 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM-side bytes per launch of the 8192^3 kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/large_square_8192_hbm_traffic.txt (scaled by the same counters' readings for
+# the 1 GiB copy below).  Valid for --size 8192 only.
+MEASURED_TRAFFIC_BYTES = 1137871865
 
 
 def gpu_time_ms(fn, iters, warmup, torch):
@@ -144,6 +145,13 @@ def main():
     pack_ms = gpu_time_ms(lambda: ng.ngemm_packed_b_free(
         ng.ngemm_pack_b(ctx, n, n, Bd, n, packed, packed.numel())), 5, 1, torch)
 
+    # plain device copy of known size: the achievable-copy ceiling, and the kernel whose
+    # FETCH_SIZE / WRITE_SIZE readings calibrate those counters in the profiles
+    csrc = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cdst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    copy_ms = gpu_time_ms(lambda: cdst.copy_(csrc), 5, 2, torch)
+    del csrc, cdst
+
     result = {
         "metric": "int8 GEMM TOPS (u8 x s8 -> s32, M=N=K=%d)" % n,
         "value": round(tops, 2),
@@ -158,18 +166,19 @@ def main():
         "dtype": "int8 x int8 -> int32 (u8 operand shifted to s8)",
         "data": "synthetic (seeded uniform u8 / s8)",
         "config": {"workload": "large_square_%d" % n, "M": n, "N": n, "K": n, "za": 0, "zb": 0,
-                   "kernel": "gemm_tile_kernel<256,256>", "sampled_outputs_match_oracle": sample_ok},
+                   "kernel": "gemm_tile_dma_kernel<256,256,2,2,4>", "sampled_outputs_match_oracle": sample_ok},
         "roofline": {"bound": "mfma", "achieved": round(kern_tops, 2), "peak": INT8_MFMA_PEAK_TOPS,
                      "unit": "TOP/s", "frac": round(kern_tops / INT8_MFMA_PEAK_TOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES, "kernel_ms": round(kern_ms, 5),
+                     "traffic": MEASURED_TRAFFIC_BYTES if n == 8192 else None, "kernel_ms": round(kern_ms, 5),
                      "algorithmic_ops_per_launch": ops,
                      "algorithmic_bytes_per_launch": 2 * n * n + 4 * n * n},
         "pack_b": {"ms": round(pack_ms, 4), "GBps": round(2.0 * n * n / (pack_ms * 1e-3) / 1e9, 1)},
+        "copy_1GiB": {"ms": round(copy_ms, 4), "GBps_read_plus_write": round(2.0 * (1 << 30) / (copy_ms * 1e-3) / 1e9, 1)},
     }
 
     # ---------------- CPU baseline: the oracle as it stands, bounded sample ----------------
     if not args.no_cpu_baseline:
-        cal_rows = 4
+        cal_rows = 2 * oracle.num_threads()
         t = time.perf_counter()
         oracle.gemm_u8s8s32(np.ascontiguousarray(prob.A[:cal_rows]), prob.B)
         per_row = (time.perf_counter() - t) / cal_rows
@@ -235,6 +244,16 @@ def main():
             ng.ngemm_packed_b_free(hb)
             del pool
             sk["M%d" % M] = entry
+        # launch floor: the smallest possible call through the same entry point, in the same graph
+        tinyB = torch.zeros((32, 64), dtype=torch.int8, device="cuda")
+        tb = ng.ngemm_packed_b_bytes(64, 32)
+        tpk = torch.empty(tb, dtype=torch.uint8, device="cuda")
+        th = ng.ngemm_pack_b(ctx, 64, 32, tinyB, 64, tpk, tb)
+        tA = torch.zeros((1, 64), dtype=torch.uint8, device="cuda")
+        tC = torch.empty((1, 32), dtype=torch.int32, device="cuda")
+        msf = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, 1, tA, 64, 0, th, 0, tC, 32)] * 250, 4, torch)
+        sk["launch_floor_us_1x32x64"] = round(msf * 1e3, 3)
+        ng.ngemm_packed_b_free(th)
         # asymptote: N=16384, K=4096 (64 MiB of weights), 8 rotating copies (512 MiB)
         rngb = wl.rng_for(3, 99)
         Nb, Kb, Mb = 16384, 4096, 16
