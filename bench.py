@@ -74,8 +74,10 @@ def graph_time_ms(fn_seq, replays, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # the clocks of an idle MI355X take some 50 ms of this kernel to settle: the defaults warm up
+    # long enough for the timed steps to see the sustained state (0.2 s in all)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--size", type=int, default=8192, help="square size of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")

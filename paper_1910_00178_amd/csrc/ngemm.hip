@@ -192,11 +192,10 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
 
 size_t rowsum_bytes(int64_t M) { return (size_t)round_up(M * 4, 256); }
 
-// Launches one validated GEMM; `ws` must hold rowsum_bytes(M) when zb != 0.
-ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hipStream_t st)
+// Kernel parameters of one validated GEMM (row sums not yet attached).
+GemmParams make_params(const RunArgs &a)
 {
     const ngemm_packed_b *B = a.B;
-    if (a.M == 0 || B->N == 0) return NGEMM_OK;
     GemmParams p;
     std::memset(&p, 0, sizeof p);
     p.A = a.A;
@@ -216,6 +215,15 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hip
     p.kconst = 0u - (uint32_t)a.zb * (uint32_t)(128 - a.za) * (uint32_t)B->K;
     p.scale = a.scale;
     p.zc = a.zc;
+    return p;
+}
+
+// Launches one validated GEMM; `ws` must hold rowsum_bytes(M) when zb != 0.
+ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hipStream_t st)
+{
+    const ngemm_packed_b *B = a.B;
+    if (a.M == 0 || B->N == 0) return NGEMM_OK;
+    GemmParams p = make_params(a);
     if (a.zb != 0 && B->K > 0) {
         int32_t *rs = (int32_t *)ws;
         hipLaunchKernelGGL(rowsum_a_kernel, dim3((unsigned)((a.M + 3) / 4)), dim3(256), 0, st, a.A, a.lda,
@@ -448,17 +456,80 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
     if (workspace_bytes < need) return NGEMM_ERR_BUFFER_TOO_SMALL;
     DeviceGuard g(ctx->device);
     if (!g.ok) return NGEMM_ERR_DEVICE;
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    // Grouped launches: the members' parameters ride in the kernel argument block, up to
+    // kGroupMax per launch; one grid covers the row-sum units of a group, one the 64 x 64 tiles of
+    // its members with M > 32, one the panels of its skinny members.  Launch count, not
+    // arithmetic, is what a batch of small odd shapes costs.
+    GroupParams rows, tiles, skinny;
+    rows.count = tiles.count = skinny.count = 0;
+    rows.unit_start[0] = tiles.unit_start[0] = skinny.unit_start[0] = 0;
+    using TCfg = TileCfg<64, 64, 2, 2, 64>;
+    auto flush = [&](GroupParams &gp, int which) -> hipError_t {
+        if (gp.count == 0) return hipSuccess;
+        const unsigned grid = (unsigned)gp.unit_start[gp.count];
+        if (grid > 0) {
+            if (which == 0)
+                hipLaunchKernelGGL(rowsum_group_kernel, dim3(grid), dim3(256), 0, st, gp);
+            else if (which == 1)
+                hipLaunchKernelGGL((gemm_group_tile_kernel<64, 64, 2, 2, 64>), dim3(grid), dim3(256),
+                                   (size_t)TCfg::kLdsBytes, st, gp);
+            else
+                hipLaunchKernelGGL(gemm_group_skinny_kernel, dim3(grid), dim3(512), (size_t)(8 * 16 * 64 * 4), st, gp);
+        }
+        gp.count = 0;
+        gp.unit_start[0] = 0;
+        return hipGetLastError();
+    };
+    auto push = [&](GroupParams &gp, const GemmParams &p, int64_t units) {
+        gp.prob[gp.count] = p;
+        gp.unit_start[gp.count + 1] = gp.unit_start[gp.count] + (int)units;
+        ++gp.count;
+    };
+    constexpr int64_t kMaxGrid = 1 << 30;
     size_t off = 0;
+    // pass 1: row sums of every member that needs them (they must precede the GEMMs that read them)
     for (int t = 0; t < count; ++t) {
         const ngemm_problem &q = problems[t];
+        if (!(q.b_zero_point != 0 && q.M > 0 && q.B->N > 0 && q.B->K > 0)) continue;
         RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
-        int kernel;
-        (void)validate_run(ctx, a, &kernel);
-        void *ws = (uint8_t *)workspace_dev + off;
-        if (q.b_zero_point != 0 && q.M > 0 && q.B->N > 0 && q.B->K > 0) off += rowsum_bytes(q.M);
-        ngemm_status s = launch_run(a, kernel, workgroup_budget(ctx), ws, (hipStream_t)hip_stream);
-        if (s != NGEMM_OK) return s;
+        GemmParams p = make_params(a);
+        p.rowsum = (const int32_t *)((uint8_t *)workspace_dev + off);
+        off += rowsum_bytes(q.M);
+        const int64_t units = (q.M + 3) / 4;
+        if (rows.count == kGroupMax || rows.unit_start[rows.count] + units > kMaxGrid)
+            if (flush(rows, 0) != hipSuccess) return NGEMM_ERR_DEVICE;
+        push(rows, p, units);
     }
+    if (flush(rows, 0) != hipSuccess) return NGEMM_ERR_DEVICE;
+    // pass 2: the GEMMs
+    off = 0;
+    for (int t = 0; t < count; ++t) {
+        const ngemm_problem &q = problems[t];
+        if (q.M == 0 || q.B->N == 0) continue;
+        RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
+        GemmParams p = make_params(a);
+        if (q.b_zero_point != 0 && q.B->K > 0) {
+            p.rowsum = (const int32_t *)((uint8_t *)workspace_dev + off);
+            off += rowsum_bytes(q.M);
+        }
+        if (q.M <= kSkinnyMaxM) {
+            const int64_t units = p.npanels;
+            if (skinny.count == kGroupMax || skinny.unit_start[skinny.count] + units > kMaxGrid)
+                if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
+            push(skinny, p, units);
+        } else {
+            p.tiles_m = (p.M + 63) / 64;
+            p.tiles_n = (p.N + 63) / 64;
+            const int64_t units = (int64_t)p.tiles_m * p.tiles_n;
+            if (tiles.count == kGroupMax || tiles.unit_start[tiles.count] + units > kMaxGrid)
+                if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
+            push(tiles, p, units);
+        }
+    }
+    if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
+    if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
     return NGEMM_OK;
 }
 

@@ -356,18 +356,18 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
     }
 }
 
+// One workgroup tile (`tile` in the XCD-aware order of tile_of_block) of the problem `p`.
 template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT>
-__global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmParams p)
+__device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, uint8_t *lds)
 {
     using Cfg = TileCfg<BM, BN, WGM, WGN, BK>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, NT = Cfg::kThreads, KS = Cfg::KS;
     constexpr int CPR = Cfg::CPR, SW = Cfg::SW, AI = Cfg::kAIters, BI = Cfg::kBIters;
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     int tm, tn;
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int nslices = p.Kp / 32;
     const int nfull = p.K / BK;                        // stages that lie completely inside K
@@ -544,6 +544,43 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmPar
     __syncthreads();                                   // every wavefront is done with the stage buffers
     tile_epilogue<TM, TN, BN, REQUANT>(p, acc, m0, n0, wm, wn, lane, tid, NT, lds + wave * kXposeBytes<TN>,
                                        (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>));
+}
+
+template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT>
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    tile_body_staged<BM, BN, WGM, WGN, BK, REQUANT>(p, blockIdx.x, lds);
+}
+
+// ---- grouped launches: several independent problems in one grid -------------------------------
+// The problems' parameters travel in the kernel argument block (at most kGroupMax of them, to
+// stay inside its 4 KiB); unit_start[q] is the first workgroup id of problem q, unit_start[count]
+// the grid size.  What a "unit" is depends on the kernel: a 64 x 64 tile, a 32-column panel, or a
+// group of four rows of A.
+constexpr int kGroupMax = 32;
+struct GroupParams {
+    int count;
+    int unit_start[kGroupMax + 1];
+    GemmParams prob[kGroupMax];
+};
+
+static_assert(sizeof(GroupParams) <= 4096, "kernel argument block");
+
+__device__ __forceinline__ int group_find(const GroupParams &g, int bid)
+{
+    int q = 0;
+    for (int t = 1; t < g.count; ++t)
+        if (bid >= g.unit_start[t]) q = t;
+    return q;
+}
+
+template <int BM, int BN, int WGM, int WGN, int BK>
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_group_tile_kernel(const GroupParams g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int q = group_find(g, blockIdx.x);
+    tile_body_staged<BM, BN, WGM, WGN, BK, false>(g.prob[q], blockIdx.x - g.unit_start[q], lds);
 }
 
 // ---- tiled MFMA kernel, direct-to-LDS variant -------------------------------------------------
@@ -836,12 +873,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
 constexpr int kSkinnyBatch = 4;
 
 template <bool REQUANT>
-__global__ __launch_bounds__(512) void gemm_skinny_kernel(const GemmParams p, int nregs)
+__device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl, int nregs, int *red)
 {
-    extern __shared__ int red[];                       // [nwaves][nregs][64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = blockDim.x >> 6;
-    const int pnl = blockIdx.x;
     const int nslices = p.Kp / 32;
     const int mine = nslices > wave ? (nslices - wave + nwaves - 1) / nwaves : 0;   // fragments of this wavefront
 
@@ -913,6 +948,38 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const GemmParams p, in
         const int orow = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (orow < p.M && col < p.N) store_out<REQUANT>(p, orow, col, v, cs_term);
     }
+}
+
+template <bool REQUANT>
+__global__ __launch_bounds__(512) void gemm_skinny_kernel(const GemmParams p, int nregs)
+{
+    extern __shared__ int red[];                       // [nwaves][nregs][64]
+    skinny_body<REQUANT>(p, blockIdx.x, nregs, red);
+}
+
+// Grouped form: unit = one 32-column panel of one problem; always 8 wavefronts and room for 16
+// accumulator registers per wavefront in LDS.
+__global__ __launch_bounds__(512) void gemm_group_skinny_kernel(const GroupParams g)
+{
+    extern __shared__ int red[];
+    const int q = group_find(g, blockIdx.x);
+    const GemmParams &p = g.prob[q];
+    skinny_body<false>(p, blockIdx.x - g.unit_start[q], 4 * ((p.M + 7) / 8), red);
+}
+
+// Grouped row sums: unit = four rows of A of one problem.
+__global__ __launch_bounds__(256) void rowsum_group_kernel(const GroupParams g)
+{
+    const int q = group_find(g, blockIdx.x);
+    const GemmParams &p = g.prob[q];
+    const int i = (blockIdx.x - g.unit_start[q]) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (i >= p.M) return;
+    const uint8_t *row = p.A + (int64_t)i * p.lda;
+    int s = 0;
+    for (int k = lane; k < p.K; k += 64) s += (int)row[k] - 128;
+    s = wave_sum(s);
+    if (lane == 0) ((int32_t *)p.rowsum)[i] = s;
 }
 
 }  // namespace ngemm

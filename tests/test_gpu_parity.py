@@ -164,6 +164,39 @@ def test_config5_batched_mixed(rt, oracle):
         ng.ngemm_packed_b_free(h)
 
 
+def test_batched_degenerate_members(rt, oracle):
+    """A batch mixing empty members (M = 0, N = 0, K = 0), skinny and tiled members, with and
+    without a weight zero-point, more than one argument block's worth (> 32) of them."""
+    ng = ng_mod()
+    rng = np.random.default_rng(91)
+    shapes = [(0, 5, 7), (5, 0, 7), (5, 7, 0), (1, 1, 1), (33, 65, 129), (32, 64, 64), (70, 3, 300)]
+    shapes += [(int(rng.integers(1, 90)), int(rng.integers(1, 90)), int(rng.integers(1, 200))) for _ in range(40)]
+    items, outs, probs, keep, handles = [], [], [], [], []
+    for t, (M, N, K) in enumerate(shapes):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        za, zb = int(rng.integers(0, 256)), (0 if t % 3 == 0 else int(rng.integers(-128, 128)))
+        h, packed = rt.pack(B)
+        Ad = torch.from_numpy(A).cuda() if A.size else torch.empty(16, dtype=torch.uint8, device="cuda")
+        Cd = torch.full((max(M, 1), max(N, 1)), -9, dtype=torch.int32, device="cuda")
+        handles.append(h); keep.append((packed, Ad)); outs.append(Cd)
+        probs.append((A, B, za, zb))
+        items.append((M, Ad, K, za, zb, h, Cd, max(N, 1)))
+    arr = ng.make_problems(items)
+    wsb = ng.ngemm_batched_workspace_bytes(arr)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    ng.ngemm_run_batched_u8s8s32(rt.ctx, arr, ws, wsb)
+    torch.cuda.synchronize()
+    for (M, N, K), (A, B, za, zb), Cd in zip(shapes, probs, outs):
+        got = Cd.cpu().numpy()
+        if M == 0 or N == 0:
+            assert np.all(got == -9)
+            continue
+        assert np.array_equal(got[:M, :N], oracle.gemm_u8s8s32(A, B, za, zb)), (M, N, K, za, zb)
+    for h in handles:
+        ng.ngemm_packed_b_free(h)
+
+
 EDGE_DIMS = (1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 129, 255, 257)
 
 
