@@ -33,6 +33,10 @@ constexpr uint32_t kCtxMagic = 0x4e47454du;   // "NGEM"
 constexpr uint32_t kPackMagic = 0x4e47504bu;  // "NGPK"
 constexpr int64_t kMaxDim = 0x7fffffff - 4096;
 constexpr int kSkinnyMaxM = 32;
+#ifndef NGEMM_WGM256
+#define NGEMM_WGM256 2
+#define NGEMM_WGN256 2
+#endif
 #ifndef NGEMM_BK256
 #define NGEMM_BK256 64
 #endif
@@ -245,7 +249,7 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hip
                    : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_256:
-        e = dma_ok ? launch_tile_dma<256, 256, 2, 2>(p, a.requant, num_cus, st)
+        e = dma_ok ? launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256>(p, a.requant, num_cus, st)
                    : launch_tile<256, 256, 2, 2, BK256>(p, a.requant, st);
         break;
     default: return NGEMM_ERR_INVALID_ARG;
@@ -307,7 +311,7 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
     {
         DeviceGuard g(device_ordinal);
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
-            allow_big_lds_dma<256, 256, 2, 2>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
+            allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
             allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess) {
             delete c;
             return NGEMM_ERR_DEVICE;

@@ -613,9 +613,9 @@ struct DmaCfg {
     static constexpr int kBIters = kBBlocks / kWaves;
     static constexpr int kABytes = BM * BK;
     static constexpr int kStageBytes = (BM + BN) * BK;
-    static constexpr int kLdsBytes = NSTAGE * kStageBytes;
+    static constexpr int kEpiBytes = kWaves * 32 * (TN * 128 + 16) + BN * 4;   // epilogue patches + column terms
+    static constexpr int kLdsBytes = NSTAGE * kStageBytes > kEpiBytes ? NSTAGE * kStageBytes : kEpiBytes;
     static constexpr int kLoadsPerStage = kAIters + kBIters;   // per thread
-    static_assert(kLdsBytes >= kWaves * 32 * (TN * 128 + 16) + BN * 4, "room for the epilogue patches");
     static_assert(kABlocks % kWaves == 0 && kBBlocks % kWaves == 0, "loader shape");
     static_assert(NSTAGE == 4, "the wait counts below assume a four-stage ring");
     static_assert(2 * kLoadsPerStage <= 63, "vmcnt range");

@@ -297,6 +297,55 @@ def test_persistent_workgroups_many_tiles_each(rt, oracle):
         ng.ngemm_set_max_workgroups(rt.ctx, 0)
 
 
+def test_hip_graph_replays(rt, oracle):
+    """Run calls captured in a HIP graph (the library allocates nothing and records no memset, so
+    it can be captured): several replays with eager work and synchronisation in between, every
+    replay checked against the oracle with fresh input contents."""
+    ng = ng_mod()
+    rng = np.random.default_rng(92)
+    cases = [(4, 4096, 1024, 0, 0), (300, 200, 500, 17, -3), (700, 520, 1024, 128, 0)]
+    bufs = []
+    for (M, N, K, za, zb) in cases:
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        h, packed = rt.pack(B)
+        Ad = torch.zeros((M, K), dtype=torch.uint8, device="cuda")
+        Cd = torch.zeros((M, N), dtype=torch.int32, device="cuda")
+        C8 = torch.zeros((M, N), dtype=torch.uint8, device="cuda")
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        bufs.append((B, h, packed, Ad, Cd, C8, ws, wsb))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+
+    def launch_all():
+        for (M, N, K, za, zb), (B, h, packed, Ad, Cd, C8, ws, wsb) in zip(cases, bufs):
+            ng.ngemm_run_u8s8s32(rt.ctx, M, Ad, K, za, h, zb, Cd, N, ws, wsb)
+            ng.ngemm_run_u8s8u8_requant(rt.ctx, M, Ad, K, za, h, zb, 0.0007, 128, C8, N, ws, wsb)
+
+    with torch.cuda.stream(side):
+        launch_all()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        launch_all()
+    for rep in range(4):
+        As = [rng.integers(0, 256, size=(M, K), dtype=np.uint8) for (M, N, K, za, zb) in cases]
+        for A, b in zip(As, bufs):
+            b[3].copy_(torch.from_numpy(A).cuda())     # eager work between replays
+            b[4].fill_(-1)
+            b[5].fill_(7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for A, (M, N, K, za, zb), b in zip(As, cases, bufs):
+            assert np.array_equal(b[4].cpu().numpy(), oracle.gemm_u8s8s32(A, b[0], za, zb)), (rep, M, N, K)
+            assert np.array_equal(b[5].cpu().numpy(),
+                                  oracle.gemm_u8s8u8_requant(A, b[0], za, zb, np.float32(0.0007), 128)), (rep, M, N, K)
+    for b in bufs:
+        ng.ngemm_packed_b_free(b[1])
+
+
 def test_error_paths_launch_nothing(rt):
     ng = ng_mod()
     B = np.ones((8, 64), np.int8)
