@@ -378,15 +378,17 @@ ngemm_status ngemm_pack_b(ngemm_ctx *ctx, int64_t K, int64_t N, const int8_t *B_
         DeviceGuard g(ctx->device);
         if (!g.ok) { delete d; return NGEMM_ERR_DEVICE; }
         hipStream_t st = (hipStream_t)hip_stream;
-        const int64_t nchunks = Kp * Np / 16;
-        if (nchunks > 0) {
-            hipLaunchKernelGGL(pack_b_kernel, dim3((unsigned)((nchunks + 255) / 256)), dim3(256), 0, st, B_dev,
-                               ldb, (int)K, (int)N, (int)Kp, nchunks, (uint8_t *)packed_dev);
+        int32_t *colsum = (int32_t *)((uint8_t *)packed_dev + Kp * Np);
+        hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((Np + 255) / 256)), dim3(256), 0, st, colsum, (int)Np);
+        if (hipGetLastError() != hipSuccess) { delete d; return NGEMM_ERR_DEVICE; }
+        if (Kp > 0) {
+            const int64_t kblocks = (Kp + kPackKBytes - 1) / kPackKBytes;
+            const int64_t nwg = (Np / 32) * kblocks;
+            if (nwg > 0x7fffffff) { delete d; return NGEMM_ERR_BAD_SHAPE; }
+            hipLaunchKernelGGL(pack_b_kernel, dim3((unsigned)nwg), dim3(256), 0, st, B_dev, ldb, (int)K, (int)N,
+                               (int)Kp, (int)kblocks, (uint8_t *)packed_dev, colsum);
             if (hipGetLastError() != hipSuccess) { delete d; return NGEMM_ERR_DEVICE; }
         }
-        hipLaunchKernelGGL(colsum_b_kernel, dim3((unsigned)((Np + 3) / 4)), dim3(256), 0, st, B_dev, ldb, (int)K,
-                           (int)N, (int)Np, (int32_t *)((uint8_t *)packed_dev + Kp * Np));
-        if (hipGetLastError() != hipSuccess) { delete d; return NGEMM_ERR_DEVICE; }
     }
     *out = d;
     return NGEMM_OK;

@@ -110,56 +110,92 @@ __device__ __forceinline__ int wave_sum(int v)
     return v;
 }
 
-// ---- pack: column-major B -> fragment order, zero padded ------------------------------------
-// One thread per 16-byte chunk of the packed buffer (linear, coalesced writes).
+// ---- pack: column-major B -> fragment order, zero padded, with column sums --------------------
+// One workgroup per (32-column panel, 512 bytes of K = 16 fragments).  Global reads follow the
+// columns (32 consecutive lanes read 512 contiguous bytes of one column), the block is turned
+// in LDS (row pitch 512 + 16 bytes: conflict-free both ways), and the 16 KiB of fragments leave as
+// one contiguous run.  Column sums: every 16-byte chunk is summed with a dot-product-with-ones,
+// the 32 lanes sharing a column are added across lanes (the one horizontal reduction of the
+// path; Sec. 2.1 phase 3) and one integer atomic per column and workgroup goes to colsum, which
+// zero_i32_kernel has cleared beforehand (integer adds: the result does not depend on the order).
+constexpr int kPackKBytes = 512;
+
+__global__ __launch_bounds__(256) void zero_i32_kernel(int32_t *__restrict__ dst, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = 0;
+}
+
 __global__ __launch_bounds__(256) void pack_b_kernel(const int8_t *__restrict__ B, int64_t ldb, int K, int N,
-                                                     int Kp, int64_t nchunks, uint8_t *__restrict__ packed)
+                                                     int Kp, int kblocks, uint8_t *__restrict__ packed,
+                                                     int32_t *__restrict__ colsum)
 {
-    int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c >= nchunks) return;
+    __shared__ __attribute__((aligned(16))) uint8_t turn[32 * (kPackKBytes + 16)];
+    const int tid = threadIdx.x;
+    const int pnl = blockIdx.x / kblocks, kblk = blockIdx.x % kblocks;
     const int nslices = Kp / 32;
-    int64_t frag = c >> 6;
-    int lane = (int)(c & 63);
-    int pnl = (int)(frag / nslices);
-    int s = (int)(frag % nslices);
-    int j = pnl * 32 + (lane & 31);
-    int k0 = s * 32 + (lane >> 5) * 16;
-    v4i v = {0, 0, 0, 0};
-    if (j < N && k0 < K) {
-        const uint8_t *src = (const uint8_t *)B + (int64_t)j * ldb + k0;
-        v = (k0 + 16 <= K) ? load16_any(src) : load16_partial(src, K - k0);
+    const int k_base = kblk * kPackKBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid + 256 * i;                     // chunk: column c/32 of the panel, k-chunk c%32
+        const int jl = c >> 5, kc = c & 31;
+        const int j = pnl * 32 + jl, k0 = k_base + kc * 16;
+        v4i v = {0, 0, 0, 0};
+        if (j < N && k0 < K) {
+            const uint8_t *src = (const uint8_t *)B + (int64_t)j * ldb + k0;
+            v = (k0 + 16 <= K) ? load16_any(src) : load16_partial(src, K - k0);
+        }
+        *(v4i *)(turn + jl * (kPackKBytes + 16) + kc * 16) = v;
+        // column sum of this chunk, then over the 32 lanes that hold the same column
+        int s = __builtin_amdgcn_sdot4(v.x, 0x01010101, 0, false);
+        s = __builtin_amdgcn_sdot4(v.y, 0x01010101, s, false);
+        s = __builtin_amdgcn_sdot4(v.z, 0x01010101, s, false);
+        s = __builtin_amdgcn_sdot4(v.w, 0x01010101, s, false);
+#pragma unroll
+        for (int off = 16; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if ((tid & 31) == 0 && j < N && s != 0) atomicAdd(colsum + j, s);
     }
-    *(v4i *)(packed + c * 16) = v;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int o = tid + 256 * i;                     // output chunk: fragment o/64 of the block, lane o%64
+        const int s = o >> 6, l = o & 63;
+        const int slice = kblk * (kPackKBytes / 32) + s;
+        if (slice < nslices) {
+            const v4i v = *(const v4i *)(turn + (l & 31) * (kPackKBytes + 16) + (2 * s + (l >> 5)) * 16);
+            *(v4i *)(packed + ((int64_t)pnl * nslices + slice) * kFragBytes + l * 16) = v;
+        }
+    }
 }
 
-// colsum[j] = sum_k B[k][j]; one wavefront per column, cross-lane reduction at the end
-// (the only place where a horizontal reduction survives; Sec. 2.1 phase 3).
-__global__ __launch_bounds__(256) void colsum_b_kernel(const int8_t *__restrict__ B, int64_t ldb, int K, int N,
-                                                       int Np, int32_t *__restrict__ colsum)
+// rowsum[i] = sum_k (A[i][k] - 128); needed only when zb != 0.  One wavefront per row, 16 bytes
+// per lane and step: the bytes are shifted to signed (xor 0x80) and summed by a dot product with
+// ones, then across the lanes.
+__device__ __forceinline__ int row_sum_shifted(const uint8_t *row, int K, int lane)
 {
-    int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    int lane = threadIdx.x & 63;
-    if (j >= Np) return;
     int s = 0;
-    if (j < N) {
-        const int8_t *col = B + (int64_t)j * ldb;
-        for (int k = lane; k < K; k += 64) s += col[k];
-        s = wave_sum(s);
+    for (int k = lane * 16; k < K; k += 64 * 16) {
+        v4i v = (k + 16 <= K) ? load16_any(row + k) : load16_partial(row + k, K - k);
+        v = shift_u8_to_s8(v);
+        if (k + 16 > K) {
+            // bytes past K were zero before the shift: take their -128 back out
+            s += 128 * (k + 16 - K);
+        }
+        s = __builtin_amdgcn_sdot4(v.x, 0x01010101, s, false);
+        s = __builtin_amdgcn_sdot4(v.y, 0x01010101, s, false);
+        s = __builtin_amdgcn_sdot4(v.z, 0x01010101, s, false);
+        s = __builtin_amdgcn_sdot4(v.w, 0x01010101, s, false);
     }
-    if (lane == 0) colsum[j] = s;
+    return wave_sum(s);
 }
 
-// rowsum[i] = sum_k (A[i][k] - 128); needed only when zb != 0.
 __global__ __launch_bounds__(256) void rowsum_a_kernel(const uint8_t *__restrict__ A, int64_t lda, int M, int K,
                                                        int32_t *__restrict__ rowsum)
 {
     int i = blockIdx.x * 4 + (threadIdx.x >> 6);
     int lane = threadIdx.x & 63;
     if (i >= M) return;
-    const uint8_t *row = A + (int64_t)i * lda;
-    int s = 0;
-    for (int k = lane; k < K; k += 64) s += (int)row[k] - 128;
-    s = wave_sum(s);
+    const int s = row_sum_shifted(A + (int64_t)i * lda, K, lane);
     if (lane == 0) rowsum[i] = s;
 }
 
@@ -975,10 +1011,7 @@ __global__ __launch_bounds__(256) void rowsum_group_kernel(const GroupParams g)
     const int i = (blockIdx.x - g.unit_start[q]) * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (i >= p.M) return;
-    const uint8_t *row = p.A + (int64_t)i * p.lda;
-    int s = 0;
-    for (int k = lane; k < p.K; k += 64) s += (int)row[k] - 128;
-    s = wave_sum(s);
+    const int s = row_sum_shifted(p.A + (int64_t)i * p.lda, p.K, lane);
     if (lane == 0) ((int32_t *)p.rowsum)[i] = s;
 }
 
