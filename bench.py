@@ -256,26 +256,27 @@ def main():
         msf = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, 1, tA, 64, 0, th, 0, tC, 32)] * 250, 4, torch)
         sk["launch_floor_us_1x32x64"] = round(msf * 1e3, 3)
         ng.ngemm_packed_b_free(th)
-        # asymptote: N=16384, K=4096 (64 MiB of weights), 8 rotating copies (512 MiB)
-        rngb = wl.rng_for(3, 99)
-        Nb, Kb, Mb = 16384, 4096, 16
-        Bbig = wl.uniform_s8(rngb, Nb, Kb)
-        Abig = torch.from_numpy(wl.uniform_u8(rngb, Mb, Kb)).cuda()
-        nb = ng.ngemm_packed_b_bytes(Kb, Nb)
-        pool = torch.empty((8, nb), dtype=torch.uint8, device="cuda")
-        Bd2 = torch.from_numpy(Bbig).cuda()
-        hs = [ng.ngemm_pack_b(ctx, Kb, Nb, Bd2, Kb, pool[c], nb) for c in range(8)]
-        Cb = torch.empty((Mb, Nb), dtype=torch.int32, device="cuda")
-        cnt = [0]
-
-        seq = [(lambda t=t: ng.ngemm_run_u8s8s32(ctx, Mb, Abig, Kb, 0, hs[t % 8], 0, Cb, Nb)) for t in range(16)]
-        ms3 = graph_time_ms(seq, 5, torch)
-        ab = Kb * Nb + Mb * Kb + 4 * Mb * Nb
-        sk["asymptote_M16_N16384_K4096"] = {"us": round(ms3 * 1e3, 2), "GBps": round(ab / (ms3 * 1e-3) / 1e9, 1),
-                                            "frac_of_hbm_peak": round(ab / (ms3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        for x in hs:
-            ng.ngemm_packed_b_free(x)
-        del pool, Bd2
+        # asymptotes: the same kernel on weights large enough to leave launch and latency behind
+        # (rotating copies, 512 MiB or more in all, so that every byte comes from HBM)
+        for (Mb, Nb, Kb, ncp) in ((16, 16384, 4096, 8), (16, 32768, 8192, 3), (1, 32768, 8192, 3)):
+            rngb = wl.rng_for(3, 90 + Mb)
+            Bbig = wl.uniform_s8(rngb, Nb, Kb)
+            Abig = torch.from_numpy(wl.uniform_u8(rngb, Mb, Kb)).cuda()
+            nb = ng.ngemm_packed_b_bytes(Kb, Nb)
+            pool = torch.empty((ncp, nb), dtype=torch.uint8, device="cuda")
+            Bd2 = torch.from_numpy(Bbig).cuda()
+            hs = [ng.ngemm_pack_b(ctx, Kb, Nb, Bd2, Kb, pool[c], nb) for c in range(ncp)]
+            Cb = torch.empty((Mb, Nb), dtype=torch.int32, device="cuda")
+            seq = [(lambda t=t: ng.ngemm_run_u8s8s32(ctx, Mb, Abig, Kb, 0, hs[t % ncp], 0, Cb, Nb))
+                   for t in range(4 * ncp)]
+            ms3 = graph_time_ms(seq, 5, torch)
+            ab = Kb * Nb + Mb * Kb + 4 * Mb * Nb
+            sk["asymptote_M%d_N%d_K%d" % (Mb, Nb, Kb)] = {
+                "us": round(ms3 * 1e3, 2), "GBps": round(ab / (ms3 * 1e-3) / 1e9, 1),
+                "frac_of_hbm_peak": round(ab / (ms3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            for x in hs:
+                ng.ngemm_packed_b_free(x)
+            del pool, Bd2, Bbig
         extras["skinny"] = sk
 
         # transformer FC shapes

@@ -124,18 +124,31 @@ hipError_t allow_big_lds_dma()
                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
 }
 
-hipError_t launch_skinny(const GemmParams &p, bool requant, hipStream_t st)
+template <int P>
+void launch_skinny_p(const GemmParams &p, bool requant, int nwaves, int nregs, size_t smem, hipStream_t st)
+{
+    dim3 grid((unsigned)((p.npanels + P - 1) / P)), block(nwaves * 64);
+    if (requant)
+        hipLaunchKernelGGL((gemm_skinny_kernel<true, P>), grid, block, smem, st, p, nregs);
+    else
+        hipLaunchKernelGGL((gemm_skinny_kernel<false, P>), grid, block, smem, st, p, nregs);
+}
+
+hipError_t launch_skinny(const GemmParams &p, bool requant, int num_cus, hipStream_t st)
 {
     const int nslices = p.Kp / 32;
     int nwaves = 1;
     while (nwaves < 8 && nwaves * 4 <= nslices) nwaves *= 2;    // at least two fragments per wavefront, at most 8 wavefronts
     const int nregs = 4 * ((p.M + 7) / 8);
     const size_t smem = nwaves > 1 ? (size_t)nwaves * nregs * 64 * sizeof(int) : 0;
-    dim3 grid((unsigned)p.npanels), block(nwaves * 64);
-    if (requant)
-        hipLaunchKernelGGL((gemm_skinny_kernel<true>), grid, block, smem, st, p, nregs);
+    // panels per workgroup: share an A fragment between panels when the output is wide enough to
+    // still give every compute unit a workgroup (only worth it once A's rows are many)
+    if (p.M > 4 && p.npanels >= 4 * num_cus)
+        launch_skinny_p<4>(p, requant, nwaves, nregs, smem, st);
+    else if (p.M > 4 && p.npanels >= 2 * num_cus)
+        launch_skinny_p<2>(p, requant, nwaves, nregs, smem, st);
     else
-        hipLaunchKernelGGL((gemm_skinny_kernel<false>), grid, block, smem, st, p, nregs);
+        launch_skinny_p<1>(p, requant, nwaves, nregs, smem, st);
     return hipGetLastError();
 }
 
@@ -238,7 +251,7 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hip
     hipError_t e;
     const bool dma_ok = (((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0;
     switch (kernel) {
-    case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, st); break;
+    case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, num_cus, st); break;
     // direct-to-LDS copies need 16-byte aligned rows of A; the register-staged kernels take the rest
     case NGEMM_KERNEL_TILE_64:
         e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st)

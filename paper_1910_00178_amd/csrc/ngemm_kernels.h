@@ -899,18 +899,20 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
 }
 
 // ---- skinny-M kernel (M <= 32) --------------------------------------------------------------
-// Bandwidth-bound: one workgroup per 32-column panel; its wavefronts split K (wavefront v takes
-// fragments v, v + nwaves, ... so that the workgroup sweeps the panel contiguously), each
-// streaming its fragments of the packed operand straight from memory into registers (no LDS for
-// B) and the few rows of A straight from cache.  Loads are issued a batch of kSkinnyBatch
-// fragments ahead of the matrix ops that consume them, so a wavefront always has 4 to 8 KiB in
-// flight.  Partial 32 x 32 accumulators of the wavefronts are added through LDS as whole vectors
-// (phase 2 of Sec. 3.1: vector adds, no lane tree).
-constexpr int kSkinnyBatch = 4;
-
-template <bool REQUANT>
-__device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl, int nregs, int *red)
+// Bandwidth-bound: one workgroup per P adjacent 32-column panels; its wavefronts split K
+// (wavefront v takes fragments v, v + nwaves, ... so that the workgroup sweeps a panel
+// contiguously), each streaming its fragments of the packed operand straight from memory into
+// registers (no LDS for B) and the few rows of A straight from cache.  An A fragment is loaded
+// once and used against the P panels: with one panel per workgroup the cached reads of A grow to
+// M/32 of the HBM traffic of B and cost 40 % of the bandwidth at M = 32, so wide outputs use
+// P = 2 or 4 as long as that still leaves a workgroup per compute unit.  Loads are issued a
+// batch of fragments ahead of the matrix ops that consume them (double buffered).  The partial
+// 32 x 32 accumulators of the wavefronts are added through LDS as whole vectors (phase 2 of
+// Sec. 3.1: vector adds, no lane tree), one panel after the other.
+template <bool REQUANT, int P>
+__device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl0, int nregs, int *red)
 {
+    constexpr int BATCH = P >= 4 ? 2 : 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = blockDim.x >> 6;
     const int nslices = p.Kp / 32;
@@ -919,9 +921,13 @@ __device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl, int nr
     const int row = lane & 31;
     const bool row_ok = row < p.M;
     const uint8_t *a_row = p.A + (int64_t)(row_ok ? row : 0) * p.lda + (lane >> 5) * 16;
-    const uint8_t *b_pan = p.Bp + ((int64_t)pnl * nslices) * kFragBytes + lane * 16;
-
-    auto load_b = [&](int t) { return *(const v4i *)(b_pan + (int64_t)(wave + t * nwaves) * kFragBytes); };
+    const uint8_t *b_pan[P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        int pn = pnl0 + j;
+        pn = pn < p.npanels ? pn : p.npanels - 1;       // panels past N: read a valid one, never stored
+        b_pan[j] = p.Bp + ((int64_t)pn * nslices) * kFragBytes + lane * 16;
+    }
     auto load_a = [&](int t) {
         v4i af = {0, 0, 0, 0};
         if (row_ok) {
@@ -933,64 +939,75 @@ __device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl, int nr
         return af;
     };
 
-    v16i acc;
+    v16i acc[P];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0;
+    for (int j = 0; j < P; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0;
 
-    v4i bf[2][kSkinnyBatch], af[2][kSkinnyBatch];
+    v4i bf[2][BATCH][P], af[2][BATCH];
     const v4i zero = {0, 0, 0, 0};
     auto load_batch = [&](int slot, int t0) {
 #pragma unroll
-        for (int u = 0; u < kSkinnyBatch; ++u) {
+        for (int u = 0; u < BATCH; ++u) {
             const bool ok = t0 + u < mine;
-            bf[slot][u] = ok ? load_b(t0 + u) : zero;
+#pragma unroll
+            for (int j = 0; j < P; ++j)
+                bf[slot][u][j] = ok ? *(const v4i *)(b_pan[j] + (int64_t)(wave + (t0 + u) * nwaves) * kFragBytes) : zero;
             af[slot][u] = ok ? load_a(t0 + u) : zero;
         }
     };
     auto mma_batch = [&](int slot) {
 #pragma unroll
-        for (int u = 0; u < kSkinnyBatch; ++u)
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(shift_u8_to_s8(af[slot][u]), bf[slot][u], acc, 0, 0, 0);
+        for (int u = 0; u < BATCH; ++u) {
+            const v4i a = shift_u8_to_s8(af[slot][u]);
+#pragma unroll
+            for (int j = 0; j < P; ++j)
+                acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bf[slot][u][j], acc[j], 0, 0, 0);
+        }
     };
     if (mine > 0) load_batch(0, 0);
-    for (int t0 = 0; t0 < mine; t0 += 2 * kSkinnyBatch) {
-        if (t0 + kSkinnyBatch < mine) load_batch(1, t0 + kSkinnyBatch);
+    for (int t0 = 0; t0 < mine; t0 += 2 * BATCH) {
+        if (t0 + BATCH < mine) load_batch(1, t0 + BATCH);
         mma_batch(0);          // a padded slot holds zeros for B: adds nothing
-        if (t0 + kSkinnyBatch < mine) {
-            if (t0 + 2 * kSkinnyBatch < mine) load_batch(0, t0 + 2 * kSkinnyBatch);
+        if (t0 + BATCH < mine) {
+            if (t0 + 2 * BATCH < mine) load_batch(0, t0 + 2 * BATCH);
             mma_batch(1);
         }
     }
 
-    if (nwaves > 1) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-            if (r < nregs) red[(wave * nregs + r) * 64 + lane] = acc[r];
-        __syncthreads();
-    }
-    const int col = pnl * 32 + (lane & 31);
-    const uint32_t cs_term = col < p.N ? p.za_term * (uint32_t)p.colsum[col] : 0u;
-    for (int r = wave; r < nregs; r += nwaves) {
-        int v;
+    for (int j = 0; j < P; ++j) {
+        if (pnl0 + j >= p.npanels) break;
         if (nwaves > 1) {
-            v = 0;
-            for (int w = 0; w < nwaves; ++w) v += red[(w * nregs + r) * 64 + lane];
-        } else {
-            v = 0;
+            if (j > 0) __syncthreads();                 // the previous panel's sums have been read
 #pragma unroll
-            for (int q = 0; q < 16; ++q)
-                if (q == r) v = acc[q];
+            for (int r = 0; r < 16; ++r)
+                if (r < nregs) red[(wave * nregs + r) * 64 + lane] = acc[j][r];
+            __syncthreads();
         }
-        const int orow = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (orow < p.M && col < p.N) store_out<REQUANT>(p, orow, col, v, cs_term);
+        const int col = (pnl0 + j) * 32 + (lane & 31);
+        const uint32_t cs_term = col < p.N ? p.za_term * (uint32_t)p.colsum[col] : 0u;
+        for (int r = wave; r < nregs; r += nwaves) {
+            int v = 0;
+            if (nwaves > 1) {
+                for (int w = 0; w < nwaves; ++w) v += red[(w * nregs + r) * 64 + lane];
+            } else {
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (q == r) v = acc[j][q];
+            }
+            const int orow = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (orow < p.M && col < p.N) store_out<REQUANT>(p, orow, col, v, cs_term);
+        }
     }
 }
 
-template <bool REQUANT>
+template <bool REQUANT, int P>
 __global__ __launch_bounds__(512) void gemm_skinny_kernel(const GemmParams p, int nregs)
 {
     extern __shared__ int red[];                       // [nwaves][nregs][64]
-    skinny_body<REQUANT>(p, blockIdx.x, nregs, red);
+    skinny_body<REQUANT, P>(p, blockIdx.x * P, nregs, red);
 }
 
 // Grouped form: unit = one 32-column panel of one problem; always 8 wavefronts and room for 16
@@ -1000,7 +1017,7 @@ __global__ __launch_bounds__(512) void gemm_group_skinny_kernel(const GroupParam
     extern __shared__ int red[];
     const int q = group_find(g, blockIdx.x);
     const GemmParams &p = g.prob[q];
-    skinny_body<false>(p, blockIdx.x - g.unit_start[q], 4 * ((p.M + 7) / 8), red);
+    skinny_body<false, 1>(p, blockIdx.x - g.unit_start[q], 4 * ((p.M + 7) / 8), red);
 }
 
 // Grouped row sums: unit = four rows of A of one problem.

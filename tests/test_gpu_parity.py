@@ -230,6 +230,18 @@ def test_skinny_all_row_counts(rt, oracle):
         check_problem(rt, oracle, p, (0,))
 
 
+def test_skinny_wide_outputs_share_a_fragments(rt, oracle):
+    """Outputs wide enough for the skinny kernel to give a workgroup 2 or 4 panels (one A
+    fragment used against several panels), with a ragged last workgroup."""
+    rng = np.random.default_rng(93)
+    for (M, N, K) in ((9, 16384 + 40, 200), (17, 32768 + 72, 100), (32, 32768 + 8, 64), (3, 40000, 70)):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        p = wl.Problem(f"wide{M}x{N}x{K}", A, B, za=int(rng.integers(0, 256)), zb=int(rng.integers(-5, 6)),
+                       scale=float(np.float32(0.01)), zc=100)
+        check_problem(rt, oracle, p, (0,))
+
+
 def test_extreme_values_and_wrap(rt, oracle):
     """All-255 x all-(-128)/127 operands: no 16-bit stage, exact at the int32 bound, wraps beyond."""
     for (K, b) in ((64, 127), (64, -128), (65793, -128), (65794, -128), (66311, 127), (66312, 127)):
