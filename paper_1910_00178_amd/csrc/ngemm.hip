@@ -142,10 +142,12 @@ hipError_t launch_skinny(const GemmParams &p, bool requant, int num_cus, hipStre
     const int nregs = 4 * ((p.M + 7) / 8);
     const size_t smem = nwaves > 1 ? (size_t)nwaves * nregs * 64 * sizeof(int) : 0;
     // panels per workgroup: share an A fragment between panels when the output is wide enough to
-    // still give every compute unit a workgroup (only worth it once A's rows are many)
-    if (p.M > 4 && p.npanels >= 4 * num_cus)
+    // still give every compute unit several workgroups (only worth it once A's rows are many)
+    // (measured at N = 32768, K = 8192: M = 32 gains 30 % with four panels, M = 16 12 % with two;
+    // at N = 16384 a workgroup per panel is still the fastest)
+    if (p.M > 16 && p.npanels >= 4 * num_cus)
         launch_skinny_p<4>(p, requant, nwaves, nregs, smem, st);
-    else if (p.M > 4 && p.npanels >= 2 * num_cus)
+    else if (p.M > 4 && p.npanels >= 4 * num_cus)
         launch_skinny_p<2>(p, requant, nwaves, nregs, smem, st);
     else
         launch_skinny_p<1>(p, requant, nwaves, nregs, smem, st);
