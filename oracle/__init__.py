@@ -9,6 +9,7 @@ from .ngemm_oracle import (  # noqa: F401
     gemm_u8s8s64,
     gemm_u8s8s32_sampled,
     gemm_u8s8u8_requant,
+    gemm_u8s8u8_requant_channel,
     num_threads,
     requant_s32u8,
 )

@@ -142,6 +142,38 @@ void oracle_gemm_u8s8u8_requant(int64_t M, int64_t N, int64_t K,
 }
 
 /*
+ * Per-column ("per-channel") form of the fused epilogue -- the realistic shape of the
+ * "operation fusion" the paper names in Sec. 4 without defining it; this build's reading:
+ *     c = wrap32( sum_k (A[i][k]-za) * (B[k][j]-zb_j) )      zb_j = zb_vec[j], or zb when zb_vec is NULL
+ *     t = wrap32( c + bias[j] )                               bias NULL = 0
+ *     g = (float)t * scale[j]                                 one binary32 multiply
+ *     q = (int64)nearbyintf(g) + zc ;  if relu and q < zc: q = zc ;  clamp to [0,255]
+ * (ReLU in the quantised domain: the real value (q - zc) * s_out is >= 0 iff q >= zc.)
+ */
+void oracle_gemm_u8s8u8_requant_channel(int64_t M, int64_t N, int64_t K,
+                                        const uint8_t *A, int64_t lda, int32_t za,
+                                        const int8_t *B, int64_t ldb, int32_t zb, const int32_t *zb_vec,
+                                        const float *scale, const int32_t *bias, int32_t relu, int32_t zc,
+                                        uint8_t *C8, int64_t ldc8)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t zbj = zb_vec ? (int64_t)zb_vec[j] : (int64_t)zb;
+            int32_t c = wrap32(dot_zp(A + i * lda, B + j * ldb, K, za, zbj));
+            int32_t t = wrap32((int64_t)c + (bias ? (int64_t)bias[j] : 0));
+            volatile float f = (float)t;
+            volatile float g = f * scale[j];
+            float r = nearbyintf(g);
+            int64_t q = (int64_t)r + (int64_t)zc;
+            if (relu && q < zc) q = zc;
+            if (q < 0) q = 0;
+            if (q > 255) q = 255;
+            C8[i * ldc8 + j] = (uint8_t)q;
+        }
+}
+
+/*
  * Selected elements only: out[t] = C[rows[t]][cols[t]].  Lets the tests check
  * sampled outputs of shapes whose full product would take minutes here.
  */

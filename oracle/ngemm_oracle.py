@@ -41,6 +41,9 @@ def _load():
         lib.oracle_gemm_u8s8u8_requant.argtypes = [i64, i64, i64, p, i64, i32, p, i64, i32,
                                                    f32, i32, p, i64]
         lib.oracle_gemm_u8s8s32_sampled.argtypes = [i64, p, i64, i32, p, i64, i32, i64, p, p, p]
+        lib.oracle_gemm_u8s8u8_requant_channel.argtypes = [i64, i64, i64, p, i64, i32, p, i64, i32, p, p, p,
+                                                           i32, i32, p, i64]
+        lib.oracle_gemm_u8s8u8_requant_channel.restype = None
         for name in ("oracle_gemm_u8s8s32", "oracle_gemm_u8s8s64", "oracle_requant_s32u8",
                      "oracle_gemm_u8s8u8_requant", "oracle_gemm_u8s8s32_sampled"):
             getattr(lib, name).restype = None
@@ -113,4 +116,22 @@ def gemm_u8s8s32_sampled(A, B, rows, cols, za=0, zb=0):
     out = np.empty(rows.shape, dtype=np.int32)
     _load().oracle_gemm_u8s8s32_sampled(K, _ptr(A), lda, int(za), _ptr(B), ldb, int(zb),
                                         rows.size, _ptr(rows), _ptr(cols), _ptr(out))
+    return out
+
+
+def gemm_u8s8u8_requant_channel(A, B, za, zb, scale, zc, zb_vec=None, bias=None, relu=False):
+    """Per-column scales (float32[N]), optional per-column B zero-points and biases (int32[N]),
+    optional ReLU in the quantised domain."""
+    M, N, K, lda, ldb = _check_ab(A, B)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    assert scale.shape == (N,)
+    zbv = None if zb_vec is None else np.ascontiguousarray(zb_vec, dtype=np.int32)
+    bv = None if bias is None else np.ascontiguousarray(bias, dtype=np.int32)
+    assert zbv is None or zbv.shape == (N,)
+    assert bv is None or bv.shape == (N,)
+    out = np.empty((M, N), dtype=np.uint8)
+    _load().oracle_gemm_u8s8u8_requant_channel(
+        M, N, K, _ptr(A), lda, int(za), _ptr(B), ldb, int(zb),
+        None if zbv is None else _ptr(zbv), _ptr(scale), None if bv is None else _ptr(bv),
+        1 if relu else 0, int(zc), _ptr(out), N)
     return out

@@ -83,3 +83,58 @@ def test_fused_equals_two_step(oracle):
     assert 20 < len(np.unique(one)) and one.min() >= 0      # spreads over the u8 range
     want = [[requant_exact(int(c), np.float32(0.00096), 128) for c in row] for row in C32]
     assert one.tolist() == want
+
+
+# ---- per-column ("per-channel") epilogue ---------------------------------------------------
+
+
+def test_channel_form_reduces_to_per_tensor(oracle):
+    rng = np.random.default_rng(41)
+    A = rng.integers(0, 256, size=(19, 150), dtype=np.uint8)
+    B = rng.integers(-128, 128, size=(23, 150), dtype=np.int8)
+    s = np.float32(0.0021)
+    want = oracle.gemm_u8s8u8_requant(A, B, 77, -4, s, 99)
+    got = oracle.gemm_u8s8u8_requant_channel(A, B, 77, -4, np.full(23, s, np.float32), 99,
+                                             zb_vec=np.full(23, -4, np.int32), bias=np.zeros(23, np.int32))
+    assert np.array_equal(got, want)
+    assert np.array_equal(oracle.gemm_u8s8u8_requant_channel(A, B, 77, -4, np.full(23, s, np.float32), 99), want)
+
+
+def test_channel_form_against_exact_arithmetic(oracle):
+    """Python-integer sums with a different zero-point, scale and bias per column, the exact
+    binary32 rounding helper above, ReLU applied as max(q, zc) before the clamp."""
+    rng = np.random.default_rng(42)
+    M, N, K = 7, 11, 60
+    A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+    za, zc = 131, 20
+    zbv = rng.integers(-128, 128, size=N).astype(np.int32)
+    bias = rng.integers(-50000, 50000, size=N).astype(np.int32)
+    scale = (10.0 ** rng.uniform(-5, -2, size=N)).astype(np.float32)
+    for relu in (False, True):
+        got = oracle.gemm_u8s8u8_requant_channel(A, B, za, 0, scale, zc, zb_vec=zbv, bias=bias, relu=relu)
+        for i in range(M):
+            for j in range(N):
+                c = sum((int(A[i, k]) - za) * (int(B[j, k]) - int(zbv[j])) for k in range(K)) + int(bias[j])
+                f = rne_to_binary32(Fraction(c))
+                g = rne_to_binary32(f * Fraction(float(scale[j])))
+                q = round(g) + zc
+                if relu:
+                    q = max(q, zc)
+                assert int(got[i, j]) == min(255, max(0, q)), (i, j, relu)
+
+
+def test_channel_bias_is_an_accumulator_shift_and_relu_is_a_floor(oracle):
+    rng = np.random.default_rng(43)
+    A = rng.integers(0, 256, size=(9, 80), dtype=np.uint8)
+    B = rng.integers(-100, 100, size=(13, 80), dtype=np.int8)
+    bias = rng.integers(-30000, 30000, size=13).astype(np.int32)
+    scale = np.full(13, 0.0015, np.float32)
+    C32 = oracle.gemm_u8s8s32(A, B, 128, 0)
+    shifted = (C32.astype(np.int64) + bias[None, :]).astype(np.int32)
+    want = oracle.requant_s32u8(shifted, np.float32(0.0015), 128)
+    plain = oracle.gemm_u8s8u8_requant_channel(A, B, 128, 0, scale, 128, bias=bias)
+    assert np.array_equal(plain, want)
+    relu = oracle.gemm_u8s8u8_requant_channel(A, B, 128, 0, scale, 128, bias=bias, relu=True)
+    assert np.array_equal(relu, np.maximum(plain, 128))
+    assert (plain < 128).any() and (plain > 128).any()
