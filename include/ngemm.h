@@ -164,6 +164,31 @@ ngemm_status ngemm_run_u8s8u8_requant(ngemm_ctx *ctx, int64_t M,
                                       void *workspace_dev, size_t workspace_bytes,
                                       void *hip_stream);
 
+/*
+ * Per-column ("per-channel") form of the fused epilogue, the usual shape of a quantised layer:
+ * every output column j has its own scale, optional int32 bias and optional zero-point of B,
+ * and a ReLU can be fused (this library's reading of the "operation fusion" remark of Sec. 4):
+ *     c = sum_k (A[i][k] - a_zero_point) * (B[k][j] - zb_j)      zb_j = b_zero_points_dev[j],
+ *                                                                or b_zero_point when that is NULL
+ *     t = c + bias_dev[j]                  (int32, wrapping; bias_dev NULL = no bias)
+ *     g = (float)t * scales_dev[j]         (one binary32 multiply)
+ *     q = round-half-even(g) + c_zero_point;  if relu: q = max(q, c_zero_point)
+ *     C[i][j] = (uint8) min(255, max(0, q))
+ * scales_dev (N floats), bias_dev and b_zero_points_dev (N int32 each) are device arrays.  The
+ * scales must be finite and in [2^-30, 2^30] and the zero-points in [-128,127]; being device
+ * data they are not checked.  The workspace is needed when b_zero_points_dev is given or
+ * b_zero_point != 0.
+ */
+ngemm_status ngemm_run_u8s8u8_requant_channel(ngemm_ctx *ctx, int64_t M,
+                                              const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                              const ngemm_packed_b *B, int32_t b_zero_point,
+                                              const int32_t *b_zero_points_dev,
+                                              const float *scales_dev, const int32_t *bias_dev,
+                                              int32_t relu, int32_t c_zero_point,
+                                              uint8_t *C_dev, int64_t ldc,
+                                              void *workspace_dev, size_t workspace_bytes,
+                                              void *hip_stream);
+
 /* One member of a batch of independent GEMMs (host struct, device pointers inside). */
 typedef struct ngemm_problem {
     int64_t M;

@@ -29,6 +29,7 @@ EXPORTS = (
     "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_set_max_workgroups",
     "ngemm_packed_b_bytes", "ngemm_pack_b", "ngemm_packed_b_free", "ngemm_packed_b_shape",
     "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_u8s8u8_requant",
+    "ngemm_run_u8s8u8_requant_channel",
     "ngemm_batched_workspace_bytes", "ngemm_run_batched_u8s8s32",
 )
 
@@ -62,6 +63,9 @@ _lib.ngemm_workspace_bytes.argtypes = [_i64, _i64, _i64]
 _lib.ngemm_run_u8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
 _lib.ngemm_run_u8s8u8_requant.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _f32, _i32, _p, _i64,
                                           _p, _sz, _p]
+_lib.ngemm_run_u8s8u8_requant_channel.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _p, _p, _i32, _i32,
+                                                  _p, _i64, _p, _sz, _p]
+_lib.ngemm_run_u8s8u8_requant_channel.restype = _int
 _lib.ngemm_batched_workspace_bytes.restype = _sz
 _lib.ngemm_batched_workspace_bytes.argtypes = [_int, ctypes.POINTER(ngemm_problem)]
 _lib.ngemm_run_batched_u8s8s32.argtypes = [_p, _int, ctypes.POINTER(ngemm_problem), _p, _sz, _p]
@@ -160,6 +164,16 @@ def ngemm_run_u8s8u8_requant(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, 
                                          int(b_zero_point), float(scale), int(c_zero_point), _dev(C_dev),
                                          int(ldc), _dev(workspace_dev), int(workspace_bytes),
                                          _stream(hip_stream)), "ngemm_run_u8s8u8_requant")
+
+
+def ngemm_run_u8s8u8_requant_channel(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, b_zero_points_dev,
+                                     scales_dev, bias_dev, relu, c_zero_point, C_dev, ldc,
+                                     workspace_dev=None, workspace_bytes=0, hip_stream=None):
+    _check(_lib.ngemm_run_u8s8u8_requant_channel(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B,
+                                                 int(b_zero_point), _dev(b_zero_points_dev), _dev(scales_dev),
+                                                 _dev(bias_dev), int(bool(relu)), int(c_zero_point), _dev(C_dev),
+                                                 int(ldc), _dev(workspace_dev), int(workspace_bytes),
+                                                 _stream(hip_stream)), "ngemm_run_u8s8u8_requant_channel")
 
 
 def make_problems(items):

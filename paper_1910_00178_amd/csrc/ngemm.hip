@@ -185,6 +185,12 @@ struct RunArgs {
     bool requant;
     float scale;
     int32_t zc;
+    // per-column epilogue (requantising calls only)
+    const float *scale_vec = nullptr;
+    const int32_t *bias_vec = nullptr;
+    const int32_t *zb_vec = nullptr;
+    int relu = 0;
+    bool needs_rowsum() const { return zb != 0 || zb_vec != nullptr; }
 };
 
 ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_out)
@@ -193,7 +199,7 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
     if (a.B->device != ctx->device) return NGEMM_ERR_INVALID_ARG;
     if (a.M < 0 || a.M > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
     if (a.za < 0 || a.za > 255 || a.zb < -128 || a.zb > 127) return NGEMM_ERR_INVALID_ARG;
-    if (a.requant) {
+    if (a.requant && !a.scale_vec) {
         if (!std::isfinite(a.scale) || a.scale < 0x1p-30f || a.scale > 0x1p30f) return NGEMM_ERR_INVALID_ARG;
     }
     if (a.M == 0 || a.B->N == 0) {
@@ -234,6 +240,11 @@ GemmParams make_params(const RunArgs &a)
     p.kconst = 0u - (uint32_t)a.zb * (uint32_t)(128 - a.za) * (uint32_t)B->K;
     p.scale = a.scale;
     p.zc = a.zc;
+    p.scale_vec = a.scale_vec;
+    p.bias_vec = a.bias_vec;
+    p.zb_vec = a.zb_vec;
+    p.rconst = (uint32_t)(128 - a.za) * (uint32_t)B->K;
+    p.relu = a.relu;
     return p;
 }
 
@@ -243,7 +254,7 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hip
     const ngemm_packed_b *B = a.B;
     if (a.M == 0 || B->N == 0) return NGEMM_OK;
     GemmParams p = make_params(a);
-    if (a.zb != 0 && B->K > 0) {
+    if (a.needs_rowsum() && B->K > 0) {
         int32_t *rs = (int32_t *)ws;
         hipLaunchKernelGGL(rowsum_a_kernel, dim3((unsigned)((a.M + 3) / 4)), dim3(256), 0, st, a.A, a.lda,
                            (int)a.M, (int)B->K, rs);
@@ -278,7 +289,7 @@ ngemm_status run_common(ngemm_ctx *ctx, const RunArgs &a, void *ws, size_t ws_by
     ngemm_status s = validate_run(ctx, a, &kernel);
     if (s != NGEMM_OK) return s;
     if (a.M == 0 || a.B->N == 0) return NGEMM_OK;
-    if (a.zb != 0 && a.B->K > 0) {
+    if (a.needs_rowsum() && a.B->K > 0) {
         if (!ws) return NGEMM_ERR_INVALID_ARG;
         if (ws_bytes < rowsum_bytes(a.M)) return NGEMM_ERR_BUFFER_TOO_SMALL;
     }
@@ -447,6 +458,22 @@ ngemm_status ngemm_run_u8s8u8_requant(ngemm_ctx *ctx, int64_t M, const uint8_t *
                                       void *workspace_dev, size_t workspace_bytes, void *hip_stream)
 {
     RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, true, scale, c_zero_point};
+    return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
+}
+
+ngemm_status ngemm_run_u8s8u8_requant_channel(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, int64_t lda,
+                                              int32_t a_zero_point, const ngemm_packed_b *B, int32_t b_zero_point,
+                                              const int32_t *b_zero_points_dev, const float *scales_dev,
+                                              const int32_t *bias_dev, int32_t relu, int32_t c_zero_point,
+                                              uint8_t *C_dev, int64_t ldc, void *workspace_dev,
+                                              size_t workspace_bytes, void *hip_stream)
+{
+    if (!scales_dev) return NGEMM_ERR_INVALID_ARG;
+    RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, true, 1.0f, c_zero_point};
+    a.scale_vec = scales_dev;
+    a.bias_vec = bias_dev;
+    a.zb_vec = b_zero_points_dev;
+    a.relu = relu ? 1 : 0;
     return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
 }
 

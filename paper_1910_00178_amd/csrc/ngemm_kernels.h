@@ -41,6 +41,12 @@ struct GemmParams {
     uint32_t kconst;        // -zb * (128 - za) * K  (mod 2^32)
     float scale;
     int32_t zc;
+    // per-column form of the requantising epilogue (all nullptr / 0 for the per-tensor form)
+    const float *scale_vec;   // N scales, replaces `scale`
+    const int32_t *bias_vec;  // N int32 biases added to the sum before scaling
+    const int32_t *zb_vec;    // N zero-points of B's columns, replaces `zb`
+    uint32_t rconst;          // (128 - za) * K: sum_k (A[i][k] - za) = rowsum[i] + rconst
+    int relu;                 // clamp from below at zc
 };
 
 // ---- small helpers -------------------------------------------------------------------------
@@ -81,26 +87,38 @@ __device__ __forceinline__ int32_t finish_s32(const GemmParams &p, int32_t acc, 
     return (int32_t)v;
 }
 
-// Requantise-to-u8 sequence of the header: cvt, one multiply, round-half-even, add zc, clamp.
-__device__ __forceinline__ uint8_t requant_u8(int32_t c, float scale, int32_t zc)
+// Requantise-to-u8 sequence of the header: cvt, one multiply, round-half-even, add zc, optional
+// floor at zc (ReLU in the quantised domain), clamp.
+__device__ __forceinline__ uint8_t requant_u8(int32_t c, float scale, int32_t zc, int relu)
 {
     float f = (float)c;
     float g = __fmul_rn(f, scale);
     float r = rintf(g);
     r = fminf(fmaxf(r, -4294967296.0f), 4294967296.0f);   // keeps the clamp below exact, avoids cvt overflow
     long long q = (long long)r + (long long)zc;
+    if (relu && q < (long long)zc) q = zc;
     q = q < 0 ? 0 : (q > 255 ? 255 : q);
     return (uint8_t)q;
+}
+
+// General (per-column capable) value of one requantised element from its shifted-form
+// accumulator: c = acc + (128-za)*colsum_j - zb_j * sum_k(A[i][k]-za), t = c + bias_j.
+__device__ __forceinline__ uint8_t finish_u8(const GemmParams &p, int32_t acc, uint32_t cs_term, int row, int col)
+{
+    const uint32_t zbj = p.zb_vec ? (uint32_t)p.zb_vec[col] : p.zb;
+    const uint32_t rsum = (p.rowsum ? (uint32_t)p.rowsum[row] : 0u) + p.rconst;
+    uint32_t t = (uint32_t)acc + cs_term - zbj * rsum;
+    if (p.bias_vec) t += (uint32_t)p.bias_vec[col];
+    return requant_u8((int32_t)t, p.scale_vec ? p.scale_vec[col] : p.scale, p.zc, p.relu);
 }
 
 template <bool REQUANT>
 __device__ __forceinline__ void store_out(const GemmParams &p, int row, int col, int32_t acc, uint32_t cs_term)
 {
-    int32_t c = finish_s32(p, acc, cs_term, row);
     if (REQUANT)
-        ((uint8_t *)p.C)[(int64_t)row * p.ldc + col] = requant_u8(c, p.scale, p.zc);
+        ((uint8_t *)p.C)[(int64_t)row * p.ldc + col] = finish_u8(p, acc, cs_term, row, col);
     else
-        ((int32_t *)p.C)[(int64_t)row * p.ldc + col] = c;
+        ((int32_t *)p.C)[(int64_t)row * p.ldc + col] = finish_s32(p, acc, cs_term, row);
 }
 
 __device__ __forceinline__ int wave_sum(int v)
@@ -225,7 +243,7 @@ struct TileCfg {
     static constexpr int kBIters = kBChunks / kThreads;
     static constexpr int kABytes = BM * BK;
     static constexpr int kStageBytes = (BM + BN) * BK;
-    static constexpr int kEpiBytes = WGM * WGN * 32 * (TN * 128 + 16) + BN * 4;   // epilogue: transposition patches + column terms
+    static constexpr int kEpiBytes = WGM * WGN * 32 * (TN * 128 + 16) + BN * 12;  // epilogue: transposition patches + three per-column arrays
     static constexpr int kLdsBytes = 2 * kStageBytes > kEpiBytes ? 2 * kStageBytes : kEpiBytes;
     static_assert(BK == 64 || BK == 128, "stage depth");
     static_assert(kAChunks % kThreads == 0 && kBChunks % kThreads == 0, "loader shape");
@@ -278,7 +296,8 @@ __device__ __forceinline__ void lds_barrier()
 // columns for all its stores, so it loads them once, before any store (a load placed between
 // stores to C would be serialised behind them: C may alias anything as far as the compiler
 // knows).  The requantised path stores bytes straight from the accumulator layout and takes its
-// column terms from LDS (`cterm_lds`, BN words) for the same reason.
+// per-column values (column term + bias, zero-point of B, scale: `cterm_lds`, 3 x BN words) from
+// LDS for the same reason.
 // Must be called by all threads of the workgroup; `xpose` and `cterm_lds` must not be in use.
 template <int TN>
 __device__ __forceinline__ int xpose_off(int r, int c)
@@ -299,9 +318,15 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
     const bool interior = m0 + (wm + 1) * TM * 32 <= p.M && n0 + (wn + 1) * TN * 32 <= p.N;   // this wavefront's part
     uint4 ct_back = {0u, 0u, 0u, 0u};
     if (REQUANT) {
+        // per column: (128-za)*colsum + bias, zero-point of B, scale (vectors or the scalars)
         for (int c = tid; c < BN; c += nthreads) {
             const int col = n0 + c;
-            cterm_lds[c] = col < p.N ? p.za_term * (uint32_t)p.colsum[col] : 0u;
+            const bool ok = col < p.N;
+            uint32_t cb = ok ? p.za_term * (uint32_t)p.colsum[col] : 0u;
+            if (ok && p.bias_vec) cb += (uint32_t)p.bias_vec[col];
+            cterm_lds[c] = cb;
+            cterm_lds[BN + c] = (ok && p.zb_vec) ? (uint32_t)p.zb_vec[col] : p.zb;
+            ((float *)cterm_lds)[2 * BN + c] = (ok && p.scale_vec) ? p.scale_vec[col] : p.scale;
         }
         __syncthreads();
     } else if (bcol < p.N) {
@@ -316,6 +341,8 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
         if (REQUANT && row >= p.M) continue;
         uint32_t row_term = p.kconst;
         if (p.rowsum && row < p.M) row_term -= p.zb * (uint32_t)p.rowsum[row];
+        // requantising path: sum_k (A[i][k] - za), multiplied per column by that column's zb
+        const uint32_t rsum = ((p.rowsum && row < p.M) ? (uint32_t)p.rowsum[row] : 0u) + p.rconst;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -323,18 +350,26 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
                 const int lcol = (wn * TN + j) * 32 + 8 * q + 4 * (lane >> 5);
                 const int col = n0 + lcol;
                 if (REQUANT && col >= p.N) continue;
-                uint4 ct = {0u, 0u, 0u, 0u};
-                if (REQUANT) ct = *(const uint4 *)(cterm_lds + lcol);
                 int32_t v[4];
-                v[0] = (int32_t)((uint32_t)acc[i][j][4 * q + 0] + ct.x + row_term);
-                v[1] = (int32_t)((uint32_t)acc[i][j][4 * q + 1] + ct.y + row_term);
-                v[2] = (int32_t)((uint32_t)acc[i][j][4 * q + 2] + ct.z + row_term);
-                v[3] = (int32_t)((uint32_t)acc[i][j][4 * q + 3] + ct.w + row_term);
+                if (REQUANT) {
+                    const uint4 cb = *(const uint4 *)(cterm_lds + lcol);
+                    const uint4 zv = *(const uint4 *)(cterm_lds + BN + lcol);
+                    v[0] = (int32_t)((uint32_t)acc[i][j][4 * q + 0] + cb.x - zv.x * rsum);
+                    v[1] = (int32_t)((uint32_t)acc[i][j][4 * q + 1] + cb.y - zv.y * rsum);
+                    v[2] = (int32_t)((uint32_t)acc[i][j][4 * q + 2] + cb.z - zv.z * rsum);
+                    v[3] = (int32_t)((uint32_t)acc[i][j][4 * q + 3] + cb.w - zv.w * rsum);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) v[t] = (int32_t)((uint32_t)acc[i][j][4 * q + t] + row_term);
+                }
                 if (REQUANT) {
                     uint8_t *dst = (uint8_t *)p.C + (int64_t)row * p.ldc + col;
+                    const float4 sc = *(const float4 *)((const float *)cterm_lds + 2 * BN + lcol);
                     uint8_t b[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) b[t] = requant_u8(v[t], p.scale, p.zc);
+                    b[0] = requant_u8(v[0], sc.x, p.zc, p.relu);
+                    b[1] = requant_u8(v[1], sc.y, p.zc, p.relu);
+                    b[2] = requant_u8(v[2], sc.z, p.zc, p.relu);
+                    b[3] = requant_u8(v[3], sc.w, p.zc, p.relu);
                     if (col + 3 < p.N && c_vec_ok) {
                         *(uint32_t *)dst = (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16) |
                                            ((uint32_t)b[3] << 24);
@@ -594,7 +629,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmPar
 // stay inside its 4 KiB); unit_start[q] is the first workgroup id of problem q, unit_start[count]
 // the grid size.  What a "unit" is depends on the kernel: a 64 x 64 tile, a 32-column panel, or a
 // group of four rows of A.
-constexpr int kGroupMax = 32;
+constexpr int kGroupMax = 28;
 struct GroupParams {
     int count;
     int unit_start[kGroupMax + 1];
@@ -649,7 +684,7 @@ struct DmaCfg {
     static constexpr int kBIters = kBBlocks / kWaves;
     static constexpr int kABytes = BM * BK;
     static constexpr int kStageBytes = (BM + BN) * BK;
-    static constexpr int kEpiBytes = kWaves * 32 * (TN * 128 + 16) + BN * 4;   // epilogue patches + column terms
+    static constexpr int kEpiBytes = kWaves * 32 * (TN * 128 + 16) + BN * 12;  // epilogue patches + three per-column arrays
     static constexpr int kLdsBytes = NSTAGE * kStageBytes > kEpiBytes ? NSTAGE * kStageBytes : kEpiBytes;
     static constexpr int kLoadsPerStage = kAIters + kBIters;   // per thread
     static_assert(kABlocks % kWaves == 0 && kBBlocks % kWaves == 0, "loader shape");

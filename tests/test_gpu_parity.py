@@ -309,6 +309,45 @@ def test_persistent_workgroups_many_tiles_each(rt, oracle):
         ng.ngemm_set_max_workgroups(rt.ctx, 0)
 
 
+def test_per_channel_epilogue(rt, oracle):
+    """Per-column scales, biases and B zero-points with and without the fused ReLU, on every
+    kernel, against the oracle's per-column form; ragged shapes and odd leading dimensions."""
+    ng = ng_mod()
+    rng = np.random.default_rng(94)
+    cases = [(7, 100, 300), (32, 4096, 128), (200, 333, 500), (300, 520, 1008), (64, 64, 64), (33, 1, 17), (260, 300, 1024)]
+    for t, (M, N, K) in enumerate(cases):
+        A = np.clip(np.rint(rng.normal(128, 40, size=(M, K))), 0, 255).astype(np.uint8)
+        B = np.clip(np.rint(rng.normal(0, 30, size=(N, K))), -127, 127).astype(np.int8)
+        za, zc = int(rng.integers(100, 156)), int(rng.integers(0, 200))
+        zbv = rng.integers(-8, 9, size=N).astype(np.int32)
+        bias = rng.integers(-20000, 20000, size=N).astype(np.int32)
+        scale = (10.0 ** rng.uniform(-4, -2.5, size=N)).astype(np.float32)
+        h, packed = rt.pack(B)
+        lda, ldc = K + (t % 3), N + (t % 2) * 3
+        Ah = np.zeros((M, lda), np.uint8)
+        Ah[:, :K] = A
+        Ad = torch.from_numpy(Ah).cuda()
+        sd, bd, zd = torch.from_numpy(scale).cuda(), torch.from_numpy(bias).cuda(), torch.from_numpy(zbv).cuda()
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        kernels = (0,) if M <= 32 else (1, 2, 3)
+        for k in kernels:
+            rt.set_kernel(k)
+            for (use_zbv, use_bias, relu, zb) in ((True, True, True, 0), (False, True, False, 3),
+                                                  (True, False, False, 0), (False, False, True, 0)):
+                Cd = torch.full((M + 1, ldc), 0xA5, dtype=torch.uint8, device="cuda")
+                ng.ngemm_run_u8s8u8_requant_channel(rt.ctx, M, Ad, lda, za, h, zb, zd if use_zbv else None, sd,
+                                                    bd if use_bias else None, relu, zc, Cd, ldc, ws, wsb)
+                torch.cuda.synchronize()
+                got = Cd.cpu().numpy()
+                want = oracle.gemm_u8s8u8_requant_channel(A, B, za, zb, scale, zc, zb_vec=zbv if use_zbv else None,
+                                                          bias=bias if use_bias else None, relu=relu)
+                assert np.array_equal(got[:M, :N], want), (M, N, K, k, use_zbv, use_bias, relu)
+                assert np.all(got[M:, :] == 0xA5) and np.all(got[:M, N:] == 0xA5)
+        rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+        ng.ngemm_packed_b_free(h)
+
+
 def test_hip_graph_replays(rt, oracle):
     """Run calls captured in a HIP graph (the library allocates nothing and records no memset, so
     it can be captured): several replays with eager work and synchronisation in between, every
