@@ -189,6 +189,22 @@ ngemm_status ngemm_run_u8s8u8_requant_channel(ngemm_ctx *ctx, int64_t M,
                                               void *workspace_dev, size_t workspace_bytes,
                                               void *hip_stream);
 
+/*
+ * Online-pack path, for the uncommon case where both operands are inputs of the call
+ * (Sec. 3.1.1: "we can simply perform online packing with extra overhead"): B is given in its
+ * plain column-major form, packed into the workspace on the stream, and multiplied at once.
+ * The workspace must hold ngemm_unpacked_workspace_bytes(M, N, K) bytes (16-byte aligned): the
+ * packed form of B followed by the row sums.  Result identical to ngemm_pack_b followed by
+ * ngemm_run_u8s8s32.
+ */
+size_t ngemm_unpacked_workspace_bytes(int64_t M, int64_t N, int64_t K);
+ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, int64_t K,
+                                        const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                        const int8_t *B_dev, int64_t ldb, int32_t b_zero_point,
+                                        int32_t *C_dev, int64_t ldc,
+                                        void *workspace_dev, size_t workspace_bytes,
+                                        void *hip_stream);
+
 /* One member of a batch of independent GEMMs (host struct, device pointers inside). */
 typedef struct ngemm_problem {
     int64_t M;

@@ -29,7 +29,7 @@ EXPORTS = (
     "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_set_max_workgroups",
     "ngemm_packed_b_bytes", "ngemm_pack_b", "ngemm_packed_b_free", "ngemm_packed_b_shape",
     "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_u8s8u8_requant",
-    "ngemm_run_u8s8u8_requant_channel",
+    "ngemm_run_u8s8u8_requant_channel", "ngemm_unpacked_workspace_bytes", "ngemm_run_u8s8s32_unpacked",
     "ngemm_batched_workspace_bytes", "ngemm_run_batched_u8s8s32",
 )
 
@@ -66,6 +66,11 @@ _lib.ngemm_run_u8s8u8_requant.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _f
 _lib.ngemm_run_u8s8u8_requant_channel.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _p, _p, _i32, _i32,
                                                   _p, _i64, _p, _sz, _p]
 _lib.ngemm_run_u8s8u8_requant_channel.restype = _int
+_lib.ngemm_unpacked_workspace_bytes.restype = _sz
+_lib.ngemm_unpacked_workspace_bytes.argtypes = [_i64, _i64, _i64]
+_lib.ngemm_run_u8s8s32_unpacked.argtypes = [_p, _i64, _i64, _i64, _p, _i64, _i32, _p, _i64, _i32, _p, _i64,
+                                            _p, _sz, _p]
+_lib.ngemm_run_u8s8s32_unpacked.restype = _int
 _lib.ngemm_batched_workspace_bytes.restype = _sz
 _lib.ngemm_batched_workspace_bytes.argtypes = [_int, ctypes.POINTER(ngemm_problem)]
 _lib.ngemm_run_batched_u8s8s32.argtypes = [_p, _int, ctypes.POINTER(ngemm_problem), _p, _sz, _p]
@@ -174,6 +179,18 @@ def ngemm_run_u8s8u8_requant_channel(ctx, M, A_dev, lda, a_zero_point, B, b_zero
                                                  _dev(bias_dev), int(bool(relu)), int(c_zero_point), _dev(C_dev),
                                                  int(ldc), _dev(workspace_dev), int(workspace_bytes),
                                                  _stream(hip_stream)), "ngemm_run_u8s8u8_requant_channel")
+
+
+def ngemm_unpacked_workspace_bytes(M, N, K):
+    return int(_lib.ngemm_unpacked_workspace_bytes(int(M), int(N), int(K)))
+
+
+def ngemm_run_u8s8s32_unpacked(ctx, M, N, K, A_dev, lda, a_zero_point, B_dev, ldb, b_zero_point, C_dev, ldc,
+                               workspace_dev, workspace_bytes, hip_stream=None):
+    _check(_lib.ngemm_run_u8s8s32_unpacked(ctx, int(M), int(N), int(K), _dev(A_dev), int(lda), int(a_zero_point),
+                                           _dev(B_dev), int(ldb), int(b_zero_point), _dev(C_dev), int(ldc),
+                                           _dev(workspace_dev), int(workspace_bytes), _stream(hip_stream)),
+           "ngemm_run_u8s8s32_unpacked")
 
 
 def make_problems(items):

@@ -477,6 +477,36 @@ ngemm_status ngemm_run_u8s8u8_requant_channel(ngemm_ctx *ctx, int64_t M, const u
     return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
 }
 
+size_t ngemm_unpacked_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return 0;
+    return (size_t)round_up((int64_t)ngemm_packed_b_bytes(K, N), 256) + rowsum_bytes(M > 0 ? M : 1);
+}
+
+ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, int64_t K, const uint8_t *A_dev,
+                                        int64_t lda, int32_t a_zero_point, const int8_t *B_dev, int64_t ldb,
+                                        int32_t b_zero_point, int32_t *C_dev, int64_t ldc, void *workspace_dev,
+                                        size_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx_ok(ctx)) return NGEMM_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
+    if (a_zero_point < 0 || a_zero_point > 255 || b_zero_point < -128 || b_zero_point > 127)
+        return NGEMM_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return NGEMM_OK;
+    if (!C_dev || (K > 0 && (!A_dev || !B_dev))) return NGEMM_ERR_INVALID_ARG;
+    if (lda < K || ldb < K || ldc < N) return NGEMM_ERR_BAD_SHAPE;
+    if (!workspace_dev || ((uintptr_t)workspace_dev & 15u) != 0) return NGEMM_ERR_INVALID_ARG;
+    if (workspace_bytes < ngemm_unpacked_workspace_bytes(M, N, K)) return NGEMM_ERR_BUFFER_TOO_SMALL;
+    const size_t pb = (size_t)round_up((int64_t)ngemm_packed_b_bytes(K, N), 256);
+    ngemm_packed_b *h = nullptr;
+    ngemm_status s = ngemm_pack_b(ctx, K, N, B_dev, ldb, workspace_dev, pb, hip_stream, &h);
+    if (s != NGEMM_OK) return s;
+    s = ngemm_run_u8s8s32(ctx, M, A_dev, lda, a_zero_point, h, b_zero_point, C_dev, ldc,
+                          (uint8_t *)workspace_dev + pb, workspace_bytes - pb, hip_stream);
+    ngemm_packed_b_free(h);      // the descriptor only: the kernels already hold the device addresses
+    return s;
+}
+
 size_t ngemm_batched_workspace_bytes(int count, const ngemm_problem *problems)
 {
     if (count <= 0 || !problems) return 0;

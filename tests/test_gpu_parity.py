@@ -348,6 +348,28 @@ def test_per_channel_epilogue(rt, oracle):
         ng.ngemm_packed_b_free(h)
 
 
+def test_online_pack_path(rt, oracle):
+    """Both operands as plain inputs: B is packed into the workspace inside the call."""
+    ng = ng_mod()
+    rng = np.random.default_rng(95)
+    for (M, N, K, za, zb) in ((5, 100, 333, 7, -3), (200, 333, 500, 131, 0), (300, 300, 1024, 0, 9), (40, 64, 0, 3, 3)):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        Ad = torch.from_numpy(A).cuda() if A.size else torch.empty(16, dtype=torch.uint8, device="cuda")
+        Bd = torch.from_numpy(B).cuda() if B.size else torch.empty(16, dtype=torch.int8, device="cuda")
+        Cd = torch.full((M, N), -5, dtype=torch.int32, device="cuda")
+        wsb = ng.ngemm_unpacked_workspace_bytes(M, N, K)
+        ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        ng.ngemm_run_u8s8s32_unpacked(rt.ctx, M, N, K, Ad, K, za, Bd, K, zb, Cd, N, ws, wsb)
+        torch.cuda.synchronize()
+        assert np.array_equal(Cd.cpu().numpy(), oracle.gemm_u8s8s32(A, B, za, zb)), (M, N, K)
+        try:
+            ng.ngemm_run_u8s8s32_unpacked(rt.ctx, M, N, K, Ad, K, za, Bd, K, zb, Cd, N, ws, wsb - 1)
+            assert False, "a short workspace must be refused"
+        except ng.NgemmError as e:
+            assert e.status == ng.NGEMM_ERR_BUFFER_TOO_SMALL
+
+
 def test_hip_graph_replays(rt, oracle):
     """Run calls captured in a HIP graph (the library allocates nothing and records no memset, so
     it can be captured): several replays with eager work and synchronisation in between, every
