@@ -290,13 +290,25 @@ def main():
             ms = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, p.M, A, p.K, p.za, hb, p.zb, C, p.N)] * 50, 4, torch)
             ms8 = graph_time_ms([lambda: ng.ngemm_run_u8s8u8_requant(ctx, p.M, A, p.K, p.za, hb, p.zb, p.scale, p.zc,
                                                                      C8, p.N)] * 50, 4, torch)
+            # per-column scales + bias + ReLU, and the online-pack path (B packed inside the call)
+            sv = torch.full((p.N,), p.scale, dtype=torch.float32, device="cuda")
+            bv = torch.zeros((p.N,), dtype=torch.int32, device="cuda")
+            msc = graph_time_ms([lambda: ng.ngemm_run_u8s8u8_requant_channel(
+                ctx, p.M, A, p.K, p.za, hb, p.zb, None, sv, bv, True, p.zc, C8, p.N)] * 50, 4, torch)
+            Bdev = torch.from_numpy(p.B).cuda()
+            uwb = ng.ngemm_unpacked_workspace_bytes(p.M, p.N, p.K)
+            uws = torch.empty(uwb, dtype=torch.uint8, device="cuda")
+            msu = graph_time_ms([lambda: ng.ngemm_run_u8s8s32_unpacked(
+                ctx, p.M, p.N, p.K, A, p.K, p.za, Bdev, p.K, p.zb, C, p.N, uws, uwb)] * 50, 4, torch)
             o = 2.0 * p.M * p.N * p.K
             b32 = p.M * p.K + p.N * p.K + 4 * p.M * p.N
             b8 = p.M * p.K + p.N * p.K + p.M * p.N
             fc[p.name] = {"s32_us": round(ms * 1e3, 2), "s32_TOPS": round(o / (ms * 1e-3) / 1e12, 1),
                           "s32_GBps": round(b32 / (ms * 1e-3) / 1e9, 1),
                           "u8_us": round(ms8 * 1e3, 2), "u8_TOPS": round(o / (ms8 * 1e-3) / 1e12, 1),
-                          "u8_GBps": round(b8 / (ms8 * 1e-3) / 1e9, 1)}
+                          "u8_GBps": round(b8 / (ms8 * 1e-3) / 1e9, 1),
+                          "u8_per_channel_bias_relu_us": round(msc * 1e3, 2),
+                          "s32_online_pack_us": round(msu * 1e3, 2)}
             ng.ngemm_packed_b_free(hb)
         extras["bert_fc"] = fc
 
