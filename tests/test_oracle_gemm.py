@@ -212,3 +212,23 @@ def test_k_zero_gives_zeros(oracle):
     A = np.zeros((3, 0), np.uint8)
     B = np.zeros((4, 0), np.int8)
     assert np.array_equal(oracle.gemm_u8s8s32(A, B, 9, 9), np.zeros((3, 4), np.int32))
+
+
+def test_signed_variant_brute_force_and_relation_to_unsigned(oracle):
+    """s8 x s8: Python-integer brute force on small shapes, numpy on a larger one, and the
+    identity C_s8(A - 128, za - 128) == C_u8(A, za) that ties it to the unsigned form."""
+    rng = np.random.default_rng(51)
+    for _ in range(30):
+        M, N, K = (int(x) for x in rng.integers(1, 12, size=3))
+        A = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        za, zb = int(rng.integers(-128, 128)), int(rng.integers(-128, 128))
+        want = [[sum((int(A[i, k]) - za) * (int(B[j, k]) - zb) for k in range(K)) for j in range(N)] for i in range(M)]
+        assert oracle.gemm_s8s8s32(A, B, za, zb).tolist() == want
+    A = rng.integers(-128, 128, size=(37, 300), dtype=np.int8)
+    B = rng.integers(-128, 128, size=(29, 300), dtype=np.int8)
+    ref = (A.astype(np.int64) + 7) @ (B.astype(np.int64) - 5).T
+    assert np.array_equal(oracle.gemm_s8s8s32(A, B, -7, 5).astype(np.int64), ref)
+    Au = (A.astype(np.int16) + 128).astype(np.uint8)
+    assert np.array_equal(oracle.gemm_u8s8s32(Au, B, 121, 5), oracle.gemm_s8s8s32(A, B, -7, 5))
+    assert int(oracle.gemm_s8s8s32(np.full((1, 4), -128, np.int8), np.full((1, 4), -128, np.int8))[0, 0]) == 65536
