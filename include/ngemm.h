@@ -147,6 +147,18 @@ ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M,
                                void *hip_stream);
 
 /*
+ * Signed variant, s8 x s8 -> s32 (Sec. 3.1: the method applies to other integer types too): A
+ * holds int8, a_zero_point lies in [-128,127]; everything else as in ngemm_run_u8s8s32.  The
+ * same kernels run without the unsigned-to-signed shift.
+ */
+ngemm_status ngemm_run_s8s8s32(ngemm_ctx *ctx, int64_t M,
+                               const int8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                               const ngemm_packed_b *B, int32_t b_zero_point,
+                               int32_t *C_dev, int64_t ldc,
+                               void *workspace_dev, size_t workspace_bytes,
+                               void *hip_stream);
+
+/*
  * Same sum with the fused requantise-to-u8 epilogue, applied to the int32
  * value c of every element in exactly this order:
  *     f = (float)c            binary32, round to nearest even

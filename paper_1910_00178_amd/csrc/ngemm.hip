@@ -190,6 +190,7 @@ struct RunArgs {
     const int32_t *bias_vec = nullptr;
     const int32_t *zb_vec = nullptr;
     int relu = 0;
+    bool a_signed = false;    // A holds int8 (s8 x s8 variant); za then lies in [-128,127]
     bool needs_rowsum() const { return zb != 0 || zb_vec != nullptr; }
 };
 
@@ -198,7 +199,8 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
     if (!ctx_ok(ctx) || !pack_ok(a.B)) return NGEMM_ERR_INVALID_ARG;
     if (a.B->device != ctx->device) return NGEMM_ERR_INVALID_ARG;
     if (a.M < 0 || a.M > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
-    if (a.za < 0 || a.za > 255 || a.zb < -128 || a.zb > 127) return NGEMM_ERR_INVALID_ARG;
+    if (a.a_signed ? (a.za < -128 || a.za > 127) : (a.za < 0 || a.za > 255)) return NGEMM_ERR_INVALID_ARG;
+    if (a.zb < -128 || a.zb > 127) return NGEMM_ERR_INVALID_ARG;
     if (a.requant && !a.scale_vec) {
         if (!std::isfinite(a.scale) || a.scale < 0x1p-30f || a.scale > 0x1p30f) return NGEMM_ERR_INVALID_ARG;
     }
@@ -235,15 +237,17 @@ GemmParams make_params(const RunArgs &a)
     p.K = (int)B->K;
     p.Kp = (int)B->Kp;
     p.npanels = (int)(B->Np / 32);
-    p.za_term = (uint32_t)(128 - a.za);
+    const int32_t shift = a.a_signed ? 0 : 128;      // A' = A - shift is what the matrix pipe sees
+    p.a_xor = a.a_signed ? 0u : 0x80808080u;
+    p.za_term = (uint32_t)(shift - a.za);
     p.zb = (uint32_t)a.zb;
-    p.kconst = 0u - (uint32_t)a.zb * (uint32_t)(128 - a.za) * (uint32_t)B->K;
+    p.kconst = 0u - (uint32_t)a.zb * (uint32_t)(shift - a.za) * (uint32_t)B->K;
     p.scale = a.scale;
     p.zc = a.zc;
     p.scale_vec = a.scale_vec;
     p.bias_vec = a.bias_vec;
     p.zb_vec = a.zb_vec;
-    p.rconst = (uint32_t)(128 - a.za) * (uint32_t)B->K;
+    p.rconst = (uint32_t)(shift - a.za) * (uint32_t)B->K;
     p.relu = a.relu;
     return p;
 }
@@ -257,7 +261,7 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hip
     if (a.needs_rowsum() && B->K > 0) {
         int32_t *rs = (int32_t *)ws;
         hipLaunchKernelGGL(rowsum_a_kernel, dim3((unsigned)((a.M + 3) / 4)), dim3(256), 0, st, a.A, a.lda,
-                           (int)a.M, (int)B->K, rs);
+                           (int)a.M, (int)B->K, p.a_xor, rs);
         if (hipGetLastError() != hipSuccess) return NGEMM_ERR_DEVICE;
         p.rowsum = rs;
     }
@@ -449,6 +453,15 @@ ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, 
                                void *workspace_dev, size_t workspace_bytes, void *hip_stream)
 {
     RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, false, 1.0f, 0};
+    return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
+}
+
+ngemm_status ngemm_run_s8s8s32(ngemm_ctx *ctx, int64_t M, const int8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                               const ngemm_packed_b *B, int32_t b_zero_point, int32_t *C_dev, int64_t ldc,
+                               void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    RunArgs a{M, (const uint8_t *)A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, false, 1.0f, 0};
+    a.a_signed = true;
     return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
 }
 

@@ -36,17 +36,20 @@ struct GemmParams {
     int M, N, K, Kp;        // Kp = K rounded up to 64
     int npanels;            // Np / 32
     int tiles_m, tiles_n;
-    uint32_t za_term;       // 128 - za
+    uint32_t za_term;       // shift - za, shift = 128 for unsigned A, 0 for signed A
     uint32_t zb;            // zb (two's complement)
-    uint32_t kconst;        // -zb * (128 - za) * K  (mod 2^32)
+    uint32_t kconst;        // -zb * (shift - za) * K  (mod 2^32)
     float scale;
     int32_t zc;
     // per-column form of the requantising epilogue (all nullptr / 0 for the per-tensor form)
     const float *scale_vec;   // N scales, replaces `scale`
     const int32_t *bias_vec;  // N int32 biases added to the sum before scaling
     const int32_t *zb_vec;    // N zero-points of B's columns, replaces `zb`
-    uint32_t rconst;          // (128 - za) * K: sum_k (A[i][k] - za) = rowsum[i] + rconst
+    uint32_t rconst;          // (shift - za) * K: sum_k (A[i][k] - za) = rowsum[i] + rconst
     int relu;                 // clamp from below at zc
+    // operand type of A: 0x80808080 for unsigned bytes (shifted to signed by xor), 0 for signed
+    // bytes (used as they are; za_term and rconst are then -za and -za*K)
+    uint32_t a_xor;
 };
 
 // ---- small helpers -------------------------------------------------------------------------
@@ -71,11 +74,12 @@ __device__ __forceinline__ v4i load16_partial(const uint8_t *p, int valid)
     return v;
 }
 
-// u8 -> s8 shift of 16 packed bytes: a xor 0x80 == a - 128 read as signed.
-__device__ __forceinline__ v4i shift_u8_to_s8(v4i v)
+// u8 -> s8 shift of 16 packed bytes: a xor 0x80 == a - 128 read as signed (mask 0x80808080);
+// a signed A operand passes with mask 0.
+__device__ __forceinline__ v4i shift_u8_to_s8(v4i v, uint32_t mask)
 {
-    v.x ^= (int)0x80808080u; v.y ^= (int)0x80808080u;
-    v.z ^= (int)0x80808080u; v.w ^= (int)0x80808080u;
+    v.x ^= (int)mask; v.y ^= (int)mask;
+    v.z ^= (int)mask; v.w ^= (int)mask;
     return v;
 }
 
@@ -189,13 +193,13 @@ __global__ __launch_bounds__(256) void pack_b_kernel(const int8_t *__restrict__ 
 // rowsum[i] = sum_k (A[i][k] - 128); needed only when zb != 0.  One wavefront per row, 16 bytes
 // per lane and step: the bytes are shifted to signed (xor 0x80) and summed by a dot product with
 // ones, then across the lanes.
-__device__ __forceinline__ int row_sum_shifted(const uint8_t *row, int K, int lane)
+__device__ __forceinline__ int row_sum_shifted(const uint8_t *row, int K, int lane, uint32_t mask)
 {
     int s = 0;
     for (int k = lane * 16; k < K; k += 64 * 16) {
         v4i v = (k + 16 <= K) ? load16_any(row + k) : load16_partial(row + k, K - k);
-        v = shift_u8_to_s8(v);
-        if (k + 16 > K) {
+        v = shift_u8_to_s8(v, mask);
+        if (k + 16 > K && mask) {
             // bytes past K were zero before the shift: take their -128 back out
             s += 128 * (k + 16 - K);
         }
@@ -208,12 +212,12 @@ __device__ __forceinline__ int row_sum_shifted(const uint8_t *row, int K, int la
 }
 
 __global__ __launch_bounds__(256) void rowsum_a_kernel(const uint8_t *__restrict__ A, int64_t lda, int M, int K,
-                                                       int32_t *__restrict__ rowsum)
+                                                       uint32_t mask, int32_t *__restrict__ rowsum)
 {
     int i = blockIdx.x * 4 + (threadIdx.x >> 6);
     int lane = threadIdx.x & 63;
     if (i >= M) return;
-    const int s = row_sum_shifted(A + (int64_t)i * lda, K, lane);
+    const int s = row_sum_shifted(A + (int64_t)i * lda, K, lane, mask);
     if (lane == 0) rowsum[i] = s;
 }
 
@@ -478,7 +482,7 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
     auto gload_a = [&](int i, int kt) { ra[i] = load16_any(a_src[i] + (int64_t)kt * BK); };
     auto gload_b = [&](int i, int kt) { rb[i] = *(const v4i *)(b_src[i] + (int64_t)kt * (KS * kFragBytes)); };
     auto sstore_a = [&](int i, int buf) {
-        *(v4i *)(lds + buf * Cfg::kStageBytes + a_dst[i]) = shift_u8_to_s8(ra[i]);
+        *(v4i *)(lds + buf * Cfg::kStageBytes + a_dst[i]) = shift_u8_to_s8(ra[i], p.a_xor);
     };
     auto sstore_b = [&](int i, int buf) {
         *(v4i *)(lds + buf * Cfg::kStageBytes + Cfg::kABytes + (tid + i * NT) * 16) = rb[i];
@@ -629,7 +633,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmPar
 // stay inside its 4 KiB); unit_start[q] is the first workgroup id of problem q, unit_start[count]
 // the grid size.  What a "unit" is depends on the kernel: a 64 x 64 tile, a 32-column panel, or a
 // group of four rows of A.
-constexpr int kGroupMax = 28;
+constexpr int kGroupMax = 27;
 struct GroupParams {
     int count;
     int unit_start[kGroupMax + 1];
@@ -801,7 +805,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
         };
         auto shift_frags = [&](int slot) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[slot][i] = shift_u8_to_s8(fa[slot][i]);
+            for (int i = 0; i < TM; ++i) fa[slot][i] = shift_u8_to_s8(fa[slot][i], p.a_xor);
         };
         auto xor_gap = [&](int i) { return (NM - 1 - TM + i) > 0 ? (NM - 1 - TM + i) : 0; };
 
@@ -868,7 +872,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
                     }
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
-                        if (xor_gap(i) == m) fa[1][i] = shift_u8_to_s8(fa[1][i]);
+                        if (xor_gap(i) == m) fa[1][i] = shift_u8_to_s8(fa[1][i], p.a_xor);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 // ---- sub-step 1 ----
@@ -889,7 +893,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
                     }
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
-                        if (xor_gap(i) == m) fa[0][i] = shift_u8_to_s8(fa[0][i]);
+                        if (xor_gap(i) == m) fa[0][i] = shift_u8_to_s8(fa[0][i], p.a_xor);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -995,7 +999,7 @@ __device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl0, int n
     auto mma_batch = [&](int slot) {
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
-            const v4i a = shift_u8_to_s8(af[slot][u]);
+            const v4i a = shift_u8_to_s8(af[slot][u], p.a_xor);
 #pragma unroll
             for (int j = 0; j < P; ++j)
                 acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bf[slot][u][j], acc[j], 0, 0, 0);
@@ -1063,7 +1067,7 @@ __global__ __launch_bounds__(256) void rowsum_group_kernel(const GroupParams g)
     const int i = (blockIdx.x - g.unit_start[q]) * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (i >= p.M) return;
-    const int s = row_sum_shifted(p.A + (int64_t)i * p.lda, p.K, lane);
+    const int s = row_sum_shifted(p.A + (int64_t)i * p.lda, p.K, lane, p.a_xor);
     if (lane == 0) ((int32_t *)p.rowsum)[i] = s;
 }
 

@@ -348,6 +348,37 @@ def test_per_channel_epilogue(rt, oracle):
         ng.ngemm_packed_b_free(h)
 
 
+def test_signed_a_variant(rt, oracle):
+    """s8 x s8 -> s32 on every kernel, ragged shapes, zero-points over the signed range."""
+    ng = ng_mod()
+    rng = np.random.default_rng(96)
+    for t, (M, N, K) in enumerate(((3, 70, 333), (32, 96, 64), (100, 200, 300), (300, 333, 1024), (257, 65, 129))):
+        A = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        za = int(rng.integers(-128, 128))
+        zb = 0 if t % 2 else int(rng.integers(-128, 128))
+        want = oracle.gemm_s8s8s32(A, B, za, zb)
+        h, packed = rt.pack(B)
+        Ad = torch.from_numpy(A).cuda()
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        for k in ((0,) if M <= 32 else (1, 2, 3)):
+            rt.set_kernel(k)
+            Cd = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+            ng.ngemm_run_s8s8s32(rt.ctx, M, Ad, K, za, h, zb, Cd, N, ws, wsb)
+            torch.cuda.synchronize()
+            assert np.array_equal(Cd.cpu().numpy(), want), (M, N, K, k)
+        rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+        # zero-point range of the signed operand
+        for bad in (128, -129):
+            try:
+                ng.ngemm_run_s8s8s32(rt.ctx, M, Ad, K, bad, h, 0, Cd, N, ws, wsb)
+                assert False
+            except ng.NgemmError as e:
+                assert e.status == ng.NGEMM_ERR_INVALID_ARG
+        ng.ngemm_packed_b_free(h)
+
+
 def test_online_pack_path(rt, oracle):
     """Both operands as plain inputs: B is packed into the workspace inside the call."""
     ng = ng_mod()
