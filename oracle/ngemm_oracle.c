@@ -107,6 +107,22 @@ void oracle_gemm_s8s8s32(int64_t M, int64_t N, int64_t K,
         }
 }
 
+/* Unsigned-weight variant (Sec. 3.1: other integer types): both operands hold uint8. */
+void oracle_gemm_u8u8s32(int64_t M, int64_t N, int64_t K,
+                         const uint8_t *A, int64_t lda, int32_t za,
+                         const uint8_t *B, int64_t ldb, int32_t zb,
+                         int32_t *C, int64_t ldc)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k)
+                s += ((int64_t)A[i * lda + k] - za) * ((int64_t)B[j * ldb + k] - zb);
+            C[i * ldc + j] = wrap32(s);
+        }
+}
+
 /* Same sum without truncation, for the overflow-bound pins. */
 void oracle_gemm_u8s8s64(int64_t M, int64_t N, int64_t K,
                          const uint8_t *A, int64_t lda, int32_t za,

@@ -232,3 +232,25 @@ def test_signed_variant_brute_force_and_relation_to_unsigned(oracle):
     Au = (A.astype(np.int16) + 128).astype(np.uint8)
     assert np.array_equal(oracle.gemm_u8s8s32(Au, B, 121, 5), oracle.gemm_s8s8s32(A, B, -7, 5))
     assert int(oracle.gemm_s8s8s32(np.full((1, 4), -128, np.int8), np.full((1, 4), -128, np.int8))[0, 0]) == 65536
+
+
+def test_unsigned_weight_variant_brute_force_and_relation_to_signed(oracle):
+    """u8 x u8: Python-integer brute force, a numpy product, the wrap at the largest products
+    (255 * 255 * K passes 2^31 at K = 33026) and C_u8u8(B, zb) == C_u8s8(B - 128, zb - 128)."""
+    rng = np.random.default_rng(52)
+    for _ in range(30):
+        M, N, K = (int(x) for x in rng.integers(1, 12, size=3))
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(0, 256, size=(N, K), dtype=np.uint8)
+        za, zb = int(rng.integers(0, 256)), int(rng.integers(0, 256))
+        want = [[sum((int(A[i, k]) - za) * (int(B[j, k]) - zb) for k in range(K)) for j in range(N)] for i in range(M)]
+        assert oracle.gemm_u8u8s32(A, B, za, zb).tolist() == want
+    A = rng.integers(0, 256, size=(37, 300), dtype=np.uint8)
+    B = rng.integers(0, 256, size=(29, 300), dtype=np.uint8)
+    ref = (A.astype(np.int64) - 7) @ (B.astype(np.int64) - 200).T
+    assert np.array_equal(oracle.gemm_u8u8s32(A, B, 7, 200).astype(np.int64), ref)
+    Bs = (B.astype(np.int16) - 128).astype(np.int8)
+    assert np.array_equal(oracle.gemm_u8u8s32(A, B, 7, 200), oracle.gemm_u8s8s32(A, Bs, 7, 72))
+    full = lambda K: int(oracle.gemm_u8u8s32(np.full((1, K), 255, np.uint8), np.full((1, K), 255, np.uint8))[0, 0])
+    assert full(33025) == 33025 * 65025 == 2147450625
+    assert full(33026) == 33026 * 65025 - 2**32
