@@ -147,6 +147,25 @@ ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M,
                                void *hip_stream);
 
 /*
+ * Unsigned-weight variant, u8 x u8 -> s32 (Sec. 3.1: other integer types).  ngemm_pack_b_u8 is
+ * ngemm_pack_b for a uint8 operand: it stores B - 128 (the same exact shift as for A) in the same
+ * layout and size, with the column sums of the stored bytes.  A descriptor made by it is accepted
+ * only by ngemm_run_u8u8s32, which takes b_zero_point in [0,255] and is otherwise
+ * ngemm_run_u8s8s32; the other run calls return NGEMM_ERR_INVALID_ARG for it, and this one does
+ * for a descriptor made by ngemm_pack_b.
+ */
+ngemm_status ngemm_pack_b_u8(ngemm_ctx *ctx, int64_t K, int64_t N,
+                             const uint8_t *B_dev, int64_t ldb,
+                             void *packed_dev, size_t packed_bytes,
+                             void *hip_stream, ngemm_packed_b **out);
+ngemm_status ngemm_run_u8u8s32(ngemm_ctx *ctx, int64_t M,
+                               const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                               const ngemm_packed_b *B, int32_t b_zero_point,
+                               int32_t *C_dev, int64_t ldc,
+                               void *workspace_dev, size_t workspace_bytes,
+                               void *hip_stream);
+
+/*
  * Signed variant, s8 x s8 -> s32 (Sec. 3.1: the method applies to other integer types too): A
  * holds int8, a_zero_point lies in [-128,127]; everything else as in ngemm_run_u8s8s32.  The
  * same kernels run without the unsigned-to-signed shift.

@@ -27,8 +27,8 @@ NGEMM_KERNEL_TILE_256 = 3
 
 EXPORTS = (
     "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_set_max_workgroups",
-    "ngemm_packed_b_bytes", "ngemm_pack_b", "ngemm_packed_b_free", "ngemm_packed_b_shape",
-    "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_s8s8s32", "ngemm_run_u8s8u8_requant",
+    "ngemm_packed_b_bytes", "ngemm_pack_b", "ngemm_pack_b_u8", "ngemm_packed_b_free", "ngemm_packed_b_shape",
+    "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_s8s8s32", "ngemm_run_u8u8s32", "ngemm_run_u8s8u8_requant",
     "ngemm_run_u8s8u8_requant_channel", "ngemm_unpacked_workspace_bytes", "ngemm_run_u8s8s32_unpacked",
     "ngemm_batched_workspace_bytes", "ngemm_run_batched_u8s8s32",
 )
@@ -56,6 +56,8 @@ _lib.ngemm_set_max_workgroups.argtypes = [_p, _int]
 _lib.ngemm_packed_b_bytes.restype = _sz
 _lib.ngemm_packed_b_bytes.argtypes = [_i64, _i64]
 _lib.ngemm_pack_b.argtypes = [_p, _i64, _i64, _p, _i64, _p, _sz, _p, ctypes.POINTER(_p)]
+_lib.ngemm_pack_b_u8.argtypes = [_p, _i64, _i64, _p, _i64, _p, _sz, _p, ctypes.POINTER(_p)]
+_lib.ngemm_pack_b_u8.restype = _int
 _lib.ngemm_packed_b_free.argtypes = [_p]
 _lib.ngemm_packed_b_shape.argtypes = [_p, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
 _lib.ngemm_workspace_bytes.restype = _sz
@@ -63,6 +65,8 @@ _lib.ngemm_workspace_bytes.argtypes = [_i64, _i64, _i64]
 _lib.ngemm_run_u8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
 _lib.ngemm_run_s8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
 _lib.ngemm_run_s8s8s32.restype = _int
+_lib.ngemm_run_u8u8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
+_lib.ngemm_run_u8u8s32.restype = _int
 _lib.ngemm_run_u8s8u8_requant.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _f32, _i32, _p, _i64,
                                           _p, _sz, _p]
 _lib.ngemm_run_u8s8u8_requant_channel.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _p, _p, _i32, _i32,
@@ -144,6 +148,13 @@ def ngemm_pack_b(ctx, K, N, B_dev, ldb, packed_dev, packed_bytes, hip_stream=Non
     return h
 
 
+def ngemm_pack_b_u8(ctx, K, N, B_dev, ldb, packed_dev, packed_bytes, hip_stream=None):
+    h = _p()
+    _check(_lib.ngemm_pack_b_u8(ctx, int(K), int(N), _dev(B_dev), int(ldb), _dev(packed_dev), int(packed_bytes),
+                                _stream(hip_stream), ctypes.byref(h)), "ngemm_pack_b_u8")
+    return h
+
+
 def ngemm_packed_b_free(b):
     _check(_lib.ngemm_packed_b_free(b), "ngemm_packed_b_free")
 
@@ -170,6 +181,13 @@ def ngemm_run_s8s8s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, 
     _check(_lib.ngemm_run_s8s8s32(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B, int(b_zero_point),
                                   _dev(C_dev), int(ldc), _dev(workspace_dev), int(workspace_bytes),
                                   _stream(hip_stream)), "ngemm_run_s8s8s32")
+
+
+def ngemm_run_u8u8s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, ldc,
+                      workspace_dev=None, workspace_bytes=0, hip_stream=None):
+    _check(_lib.ngemm_run_u8u8s32(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B, int(b_zero_point),
+                                  _dev(C_dev), int(ldc), _dev(workspace_dev), int(workspace_bytes),
+                                  _stream(hip_stream)), "ngemm_run_u8u8s32")
 
 
 def ngemm_run_u8s8u8_requant(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, scale, c_zero_point,

@@ -25,6 +25,7 @@ struct ngemm_packed_b {
     int64_t K, N, Kp, Np;
     const uint8_t *data;     // device, caller-owned
     size_t bytes;
+    int32_t b_shift;         // 0: packed from int8; 128: packed from uint8, stored as B - 128
 };
 
 namespace {
@@ -191,6 +192,7 @@ struct RunArgs {
     const int32_t *zb_vec = nullptr;
     int relu = 0;
     bool a_signed = false;    // A holds int8 (s8 x s8 variant); za then lies in [-128,127]
+    bool b_unsigned = false;  // B was packed from uint8 (u8 x u8 variant); zb is then the caller's zero-point - 128
     bool needs_rowsum() const { return zb != 0 || zb_vec != nullptr; }
 };
 
@@ -200,7 +202,8 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
     if (a.B->device != ctx->device) return NGEMM_ERR_INVALID_ARG;
     if (a.M < 0 || a.M > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
     if (a.a_signed ? (a.za < -128 || a.za > 127) : (a.za < 0 || a.za > 255)) return NGEMM_ERR_INVALID_ARG;
-    if (a.zb < -128 || a.zb > 127) return NGEMM_ERR_INVALID_ARG;
+    if ((a.B->b_shift != 0) != a.b_unsigned) return NGEMM_ERR_INVALID_ARG;   // entry point and pack disagree
+    if (a.zb < -128 || a.zb > 127) return NGEMM_ERR_INVALID_ARG;   // of the packed (signed) bytes
     if (a.requant && !a.scale_vec) {
         if (!std::isfinite(a.scale) || a.scale < 0x1p-30f || a.scale > 0x1p30f) return NGEMM_ERR_INVALID_ARG;
     }
@@ -382,8 +385,9 @@ size_t ngemm_packed_b_bytes(int64_t K, int64_t N)
     return (size_t)(Kp * Np + 4 * Np);
 }
 
-ngemm_status ngemm_pack_b(ngemm_ctx *ctx, int64_t K, int64_t N, const int8_t *B_dev, int64_t ldb,
-                          void *packed_dev, size_t packed_bytes, void *hip_stream, ngemm_packed_b **out)
+static ngemm_status pack_common(ngemm_ctx *ctx, int64_t K, int64_t N, const int8_t *B_dev, int64_t ldb,
+                                void *packed_dev, size_t packed_bytes, void *hip_stream, ngemm_packed_b **out,
+                                int32_t b_shift)
 {
     if (!out) return NGEMM_ERR_INVALID_ARG;
     *out = nullptr;
@@ -403,6 +407,7 @@ ngemm_status ngemm_pack_b(ngemm_ctx *ctx, int64_t K, int64_t N, const int8_t *B_
     d->K = K; d->N = N; d->Kp = Kp; d->Np = Np;
     d->data = (const uint8_t *)packed_dev;
     d->bytes = need;
+    d->b_shift = b_shift;
 
     if (Np > 0) {
         DeviceGuard g(ctx->device);
@@ -416,12 +421,24 @@ ngemm_status ngemm_pack_b(ngemm_ctx *ctx, int64_t K, int64_t N, const int8_t *B_
             const int64_t nwg = (Np / 32) * kblocks;
             if (nwg > 0x7fffffff) { delete d; return NGEMM_ERR_BAD_SHAPE; }
             hipLaunchKernelGGL(pack_b_kernel, dim3((unsigned)nwg), dim3(256), 0, st, B_dev, ldb, (int)K, (int)N,
-                               (int)Kp, (int)kblocks, (uint8_t *)packed_dev, colsum);
+                               (int)Kp, (int)kblocks, b_shift ? 0x80808080u : 0u, (uint8_t *)packed_dev, colsum);
             if (hipGetLastError() != hipSuccess) { delete d; return NGEMM_ERR_DEVICE; }
         }
     }
     *out = d;
     return NGEMM_OK;
+}
+
+ngemm_status ngemm_pack_b(ngemm_ctx *ctx, int64_t K, int64_t N, const int8_t *B_dev, int64_t ldb,
+                          void *packed_dev, size_t packed_bytes, void *hip_stream, ngemm_packed_b **out)
+{
+    return pack_common(ctx, K, N, B_dev, ldb, packed_dev, packed_bytes, hip_stream, out, 0);
+}
+
+ngemm_status ngemm_pack_b_u8(ngemm_ctx *ctx, int64_t K, int64_t N, const uint8_t *B_dev, int64_t ldb,
+                             void *packed_dev, size_t packed_bytes, void *hip_stream, ngemm_packed_b **out)
+{
+    return pack_common(ctx, K, N, (const int8_t *)B_dev, ldb, packed_dev, packed_bytes, hip_stream, out, 128);
 }
 
 ngemm_status ngemm_packed_b_free(ngemm_packed_b *b)
@@ -462,6 +479,17 @@ ngemm_status ngemm_run_s8s8s32(ngemm_ctx *ctx, int64_t M, const int8_t *A_dev, i
 {
     RunArgs a{M, (const uint8_t *)A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, false, 1.0f, 0};
     a.a_signed = true;
+    return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
+}
+
+ngemm_status ngemm_run_u8u8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                               const ngemm_packed_b *B, int32_t b_zero_point, int32_t *C_dev, int64_t ldc,
+                               void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    // (B - zb) == (B - 128) - (zb - 128): the packed bytes are already B - 128
+    if (b_zero_point < 0 || b_zero_point > 255) return NGEMM_ERR_INVALID_ARG;
+    RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point - 128, B, C_dev, ldc, false, 1.0f, 0};
+    a.b_unsigned = true;
     return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
 }
 

@@ -149,8 +149,8 @@ __global__ __launch_bounds__(256) void zero_i32_kernel(int32_t *__restrict__ dst
 }
 
 __global__ __launch_bounds__(256) void pack_b_kernel(const int8_t *__restrict__ B, int64_t ldb, int K, int N,
-                                                     int Kp, int kblocks, uint8_t *__restrict__ packed,
-                                                     int32_t *__restrict__ colsum)
+                                                     int Kp, int kblocks, uint32_t b_xor,
+                                                     uint8_t *__restrict__ packed, int32_t *__restrict__ colsum)
 {
     __shared__ __attribute__((aligned(16))) uint8_t turn[32 * (kPackKBytes + 16)];
     const int tid = threadIdx.x;
@@ -166,6 +166,17 @@ __global__ __launch_bounds__(256) void pack_b_kernel(const int8_t *__restrict__ 
         if (j < N && k0 < K) {
             const uint8_t *src = (const uint8_t *)B + (int64_t)j * ldb + k0;
             v = (k0 + 16 <= K) ? load16_any(src) : load16_partial(src, K - k0);
+            if (b_xor) {
+                // unsigned B: shift the bytes that exist to signed; the padding stays zero
+                const int nb = K - k0;
+                int *w = (int *)&v;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int vb = nb - 4 * q;
+                    const uint32_t m = vb >= 4 ? 0xffffffffu : (vb <= 0 ? 0u : (1u << (8 * vb)) - 1u);
+                    w[q] ^= (int)(b_xor & m);
+                }
+            }
         }
         *(v4i *)(turn + jl * (kPackKBytes + 16) + kc * 16) = v;
         // column sum of this chunk, then over the 32 lanes that hold the same column

@@ -379,6 +379,55 @@ def test_signed_a_variant(rt, oracle):
         ng.ngemm_packed_b_free(h)
 
 
+def test_unsigned_b_variant(rt, oracle):
+    """u8 x u8 -> s32: the pack stores B - 128 with zero padding, every kernel, ragged shapes,
+    zero-points over [0,255]; descriptors and entry points of the other type refuse each other."""
+    from gpu_util import unpack_packed
+    ng = ng_mod()
+    rng = np.random.default_rng(97)
+    for t, (M, N, K) in enumerate(((3, 70, 333), (16, 4096, 61), (100, 200, 300), (300, 333, 1024), (257, 65, 129))):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(0, 256, size=(N, K), dtype=np.uint8)
+        za = int(rng.integers(0, 256))
+        zb = 128 if t == 2 else int(rng.integers(0, 256))       # 128: no row sums needed
+        want = oracle.gemm_u8u8s32(A, B, za, zb)
+        nbytes = ng.ngemm_packed_b_bytes(K, N)
+        packed = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        Bd = torch.from_numpy(B).cuda()
+        h = ng.ngemm_pack_b_u8(rt.ctx, K, N, Bd, K, packed, nbytes)
+        torch.cuda.synchronize()
+        back, pad_zero, colsum = unpack_packed(packed.cpu().numpy(), K, N)
+        assert np.array_equal(back.astype(np.int16) + 128, B.astype(np.int16)) and pad_zero
+        assert np.array_equal(colsum[:N], (B.astype(np.int64) - 128).sum(1).astype(np.int32))
+        Ad = torch.from_numpy(A).cuda()
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        for k in ((0,) if M <= 32 else (1, 2, 3)):
+            rt.set_kernel(k)
+            Cd = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+            ng.ngemm_run_u8u8s32(rt.ctx, M, Ad, K, za, h, zb, Cd, N, ws, wsb)
+            torch.cuda.synchronize()
+            assert np.array_equal(Cd.cpu().numpy(), want), (M, N, K, k)
+        rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+        for call, args in ((ng.ngemm_run_u8s8s32, (za, h, 0)), (ng.ngemm_run_u8u8s32, (za, h, 256)),
+                           (ng.ngemm_run_u8u8s32, (za, h, -1))):
+            try:
+                call(rt.ctx, M, Ad, K, *args, Cd, N, ws, wsb)
+                assert False
+            except ng.NgemmError as e:
+                assert e.status == ng.NGEMM_ERR_INVALID_ARG
+        ng.ngemm_packed_b_free(h)
+    # a signed pack is refused by the unsigned entry point
+    Bs = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+    h, _packed = rt.pack(Bs)
+    try:
+        ng.ngemm_run_u8u8s32(rt.ctx, M, Ad, K, za, h, 128, Cd, N, ws, wsb)
+        assert False
+    except ng.NgemmError as e:
+        assert e.status == ng.NGEMM_ERR_INVALID_ARG
+    ng.ngemm_packed_b_free(h)
+
+
 def test_online_pack_path(rt, oracle):
     """Both operands as plain inputs: B is packed into the workspace inside the call."""
     ng = ng_mod()
