@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak, GB/s (published)
 # HBM-side bytes per launch of the 8192^3 kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/large_square_8192_hbm_traffic.txt (scaled by the same counters' readings for
 # the 1 GiB copy below).  Valid for --size 8192 only.
-MEASURED_TRAFFIC_BYTES = 1137871865
+MEASURED_TRAFFIC_BYTES = 1137810054
 
 
 def gpu_time_ms(fn, iters, warmup, torch):
@@ -332,6 +332,23 @@ def main():
                                            "GBps": round(by / (msb * 1e-3) / 1e9, 1)}
         for x in hs:
             ng.ngemm_packed_b_free(x)
+        del keep, items
+
+        # the other integer types on the headline shape: signed A, and unsigned B (shifted in the pack)
+        rngt = wl.rng_for(4, 50)
+        At = torch.from_numpy(wl.uniform_u8(rngt, n, n)).cuda()
+        Bt = torch.from_numpy(wl.uniform_s8(rngt, n, n)).cuda()
+        Ct = torch.empty((n, n), dtype=torch.int32, device="cuda")
+        nb = ng.ngemm_packed_b_bytes(n, n)
+        pks, pku = (torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(2))
+        hsg = ng.ngemm_pack_b(ctx, n, n, Bt, n, pks, nb)
+        hun = ng.ngemm_pack_b_u8(ctx, n, n, Bt.view(torch.uint8), n, pku, nb)
+        ms_ss = gpu_time_ms(lambda: ng.ngemm_run_s8s8s32(ctx, n, At.view(torch.int8), n, 0, hsg, 0, Ct, n), 100, 100, torch)
+        ms_uu = gpu_time_ms(lambda: ng.ngemm_run_u8u8s32(ctx, n, At, n, 0, hun, 128, Ct, n), 100, 100, torch)
+        extras["other_integer_types_%d" % n] = {"s8s8s32_TOPS": round(ops / (ms_ss * 1e-3) / 1e12, 1),
+                                                "u8u8s32_TOPS": round(ops / (ms_uu * 1e-3) / 1e12, 1)}
+        ng.ngemm_packed_b_free(hsg)
+        ng.ngemm_packed_b_free(hun)
         result["extras"] = extras
 
     ng.ngemm_destroy(ctx)
