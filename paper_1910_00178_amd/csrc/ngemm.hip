@@ -125,6 +125,34 @@ hipError_t allow_big_lds_dma()
                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
 }
 
+// 64 x 64 tiles with the long pipeline: one workgroup per compute unit (its ring takes 128 KiB).
+constexpr int kDeepStages = 4;
+
+hipError_t launch_tile64_deep(const GemmParams &p0, bool requant, int num_cus, hipStream_t st)
+{
+    using Cfg = DeepCfg<kDeepStages>;
+    GemmParams p = p0;
+    p.tiles_m = (p.M + 63) / 64;
+    p.tiles_n = (p.N + 63) / 64;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    dim3 grid((unsigned)(ntiles < num_cus ? ntiles : num_cus)), block(256);
+    if (requant)
+        hipLaunchKernelGGL((gemm_tile64_deep_kernel<kDeepStages, true>), grid, block, Cfg::kLdsBytes, st, p);
+    else
+        hipLaunchKernelGGL((gemm_tile64_deep_kernel<kDeepStages, false>), grid, block, Cfg::kLdsBytes, st, p);
+    return hipGetLastError();
+}
+
+hipError_t allow_big_lds_deep()
+{
+    using Cfg = DeepCfg<kDeepStages>;
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_tile64_deep_kernel<kDeepStages, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)gemm_tile64_deep_kernel<kDeepStages, false>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+}
+
 template <int P>
 void launch_skinny_p(const GemmParams &p, bool requant, int nwaves, int nregs, size_t smem, hipStream_t st)
 {
@@ -256,7 +284,7 @@ GemmParams make_params(const RunArgs &a)
 }
 
 // Launches one validated GEMM; `ws` must hold rowsum_bytes(M) when zb != 0.
-ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hipStream_t st)
+ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cus, void *ws, hipStream_t st)
 {
     const ngemm_packed_b *B = a.B;
     if (a.M == 0 || B->N == 0) return NGEMM_OK;
@@ -274,8 +302,12 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, void *ws, hip
     case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, num_cus, st); break;
     // direct-to-LDS copies need 16-byte aligned rows of A; the register-staged kernels take the rest
     case NGEMM_KERNEL_TILE_64:
-        e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st)
-                   : launch_tile<64, 64, 2, 2, 64>(p, a.requant, st);
+        // at most one tile per compute unit and a K worth pipelining: the long-pipeline variant
+        if (dma_ok && B->K >= 512 && ((a.M + 63) / 64) * ((B->N + 63) / 64) <= (int64_t)device_cus)
+            e = launch_tile64_deep(p, a.requant, num_cus, st);
+        else
+            e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st)
+                       : launch_tile<64, 64, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_128:
         e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st)
@@ -302,7 +334,8 @@ ngemm_status run_common(ngemm_ctx *ctx, const RunArgs &a, void *ws, size_t ws_by
     }
     DeviceGuard g(ctx->device);
     if (!g.ok) return NGEMM_ERR_DEVICE;
-    return launch_run(a, kernel, workgroup_budget(ctx), ws, (hipStream_t)stream);
+    return launch_run(a, kernel, workgroup_budget(ctx), ctx->num_cus > 0 ? ctx->num_cus : 256, ws,
+                      (hipStream_t)stream);
 }
 
 }  // namespace
@@ -345,7 +378,7 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
         DeviceGuard g(device_ordinal);
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
             allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
-            allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess) {
+            allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep() != hipSuccess) {
             delete c;
             return NGEMM_ERR_DEVICE;
         }
