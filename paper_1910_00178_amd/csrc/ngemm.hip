@@ -38,6 +38,9 @@ constexpr int kSkinnyMaxM = 32;
 #define NGEMM_WGM256 2
 #define NGEMM_WGN256 2
 #endif
+#ifndef NGEMM_STAGES256
+#define NGEMM_STAGES256 4
+#endif
 #ifndef NGEMM_BK256
 #define NGEMM_BK256 64
 #endif
@@ -92,10 +95,10 @@ hipError_t allow_big_lds()
                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE = 4>
 hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipStream_t st)
 {
-    using Cfg = DmaCfg<BM, BN, WGM, WGN, 4>;
+    using Cfg = DmaCfg<BM, BN, WGM, WGN, NSTAGE>;
     GemmParams p = p0;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
@@ -107,21 +110,21 @@ hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipS
     dim3 grid((unsigned)nwg), block(WGM * WGN * 64);
     const size_t smem = Cfg::kLdsBytes;
     if (requant)
-        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, 4, true>), grid, block, smem, st, p);
+        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, true>), grid, block, smem, st, p);
     else
-        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, 4, false>), grid, block, smem, st, p);
+        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false>), grid, block, smem, st, p);
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE = 4>
 hipError_t allow_big_lds_dma()
 {
-    using Cfg = DmaCfg<BM, BN, WGM, WGN, 4>;
+    using Cfg = DmaCfg<BM, BN, WGM, WGN, NSTAGE>;
     if (Cfg::kLdsBytes <= 64 * 1024) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, 4, true>,
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, 4, false>,
+    return hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
 }
 
@@ -314,7 +317,7 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
                    : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_256:
-        e = dma_ok ? launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256>(p, a.requant, num_cus, st)
+        e = dma_ok ? launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, a.requant, num_cus, st)
                    : launch_tile<256, 256, 2, 2, BK256>(p, a.requant, st);
         break;
     default: return NGEMM_ERR_INVALID_ARG;
@@ -377,7 +380,7 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
     {
         DeviceGuard g(device_ordinal);
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
-            allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
+            allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
             allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep() != hipSuccess) {
             delete c;
             return NGEMM_ERR_DEVICE;

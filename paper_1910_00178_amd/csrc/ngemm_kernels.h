@@ -703,8 +703,8 @@ struct DmaCfg {
     static constexpr int kLdsBytes = NSTAGE * kStageBytes > kEpiBytes ? NSTAGE * kStageBytes : kEpiBytes;
     static constexpr int kLoadsPerStage = kAIters + kBIters;   // per thread
     static_assert(kABlocks % kWaves == 0 && kBBlocks % kWaves == 0, "loader shape");
-    static_assert(NSTAGE == 4, "the wait counts below assume a four-stage ring");
-    static_assert(2 * kLoadsPerStage <= 63, "vmcnt range");
+    static_assert(NSTAGE >= 4, "ring of at least four stages");
+    static_assert((NSTAGE - 2) * kLoadsPerStage <= 63, "vmcnt range");
 };
 
 // s_waitcnt for the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
@@ -851,7 +851,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
         //       last gaps  : u8 -> s8 shift of slot 1's A fragments (long since returned)
         //   sub-step 1 (slot 1):
         //       first gaps : LDS reads of slot 0 for stage it+1, k-half 0
-        //       then       : copies of stage it+3 into the buffer of stage it-1
+        //       then       : copies of stage it+NSTAGE-1 into the buffer of stage it-1
         //       last gaps  : shift of slot 0's A fragments
         // The barrier of iteration it is what makes the reads of stage it+1 (issued after it) and
         // the overwrite of stage it-1 (whose last reads were consumed in iteration it-1) safe.
@@ -860,15 +860,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
         if (nfull > 0) {
 #pragma unroll
             for (int s = 0; s < NSTAGE - 1; ++s) dma_stage(clampk(s), s);
-            wait_vmcnt<2 * LPS>();                      // stage 0 has landed (this wavefront's part)
+            wait_vmcnt<(NSTAGE - 2) * LPS>();           // stage 0 has landed (this wavefront's part)
             __builtin_amdgcn_s_barrier();               // ... and everybody else's
             read_frags(0, 0, 0);
             shift_frags(0);
             __builtin_amdgcn_sched_barrier(0);
 
             for (int it = 0; it < nfull; ++it) {
-                const int cur = it & (NSTAGE - 1), nxt = (it + 1) & (NSTAGE - 1), fre = (it + 3) & (NSTAGE - 1);
-                const int kload = clampk(it + 3);
+                const int cur = it % NSTAGE, nxt = (it + 1) % NSTAGE, fre = (it + NSTAGE - 1) % NSTAGE;
+                const int kload = clampk(it + NSTAGE - 1);
                 // ---- sub-step 0 ----
 #pragma unroll
                 for (int m = 0; m < NM; ++m) {
@@ -878,7 +878,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
                     for (int r = 0; r < NR; ++r)
                         if (r / 2 == m || (m == NM - 1 && r / 2 > m)) read_one(cur, 1, 1, r);
                     if (m == (NM - 1) / 2) {
-                        wait_vmcnt<LPS>();              // younger: only the copies of stage it+2
+                        wait_vmcnt<(NSTAGE - 3) * LPS>();   // younger: the copies of stages it+2 .. it+NSTAGE-2
                         __builtin_amdgcn_s_barrier();
                     }
 #pragma unroll
