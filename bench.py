@@ -308,7 +308,7 @@ def main():
                           "u8_us": round(ms8 * 1e3, 2), "u8_TOPS": round(o / (ms8 * 1e-3) / 1e12, 1),
                           "u8_GBps": round(b8 / (ms8 * 1e-3) / 1e9, 1),
                           "u8_per_channel_bias_relu_us": round(msc * 1e3, 2),
-                          "s32_online_pack_us": round(msu * 1e3, 2)}
+                          "s32_unpacked_b_us": round(msu * 1e3, 2)}
             ng.ngemm_packed_b_free(hb)
         extras["bert_fc"] = fc
 
@@ -349,6 +349,12 @@ def main():
                                                 "u8u8s32_TOPS": round(ops / (ms_uu * 1e-3) / 1e12, 1)}
         ng.ngemm_packed_b_free(hsg)
         ng.ngemm_packed_b_free(hun)
+        # both operands as inputs: B read from its plain [N x K] storage, nothing packed
+        uwb = ng.ngemm_unpacked_workspace_bytes(n, n, n)
+        uws = torch.empty(uwb, dtype=torch.uint8, device="cuda")
+        ms_un = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32_unpacked(ctx, n, n, n, At, n, 0, Bt, n, 0, Ct, n, uws, uwb),
+                            100, 100, torch)
+        extras["unpacked_b_%d" % n] = {"ms": round(ms_un, 4), "TOPS": round(ops / (ms_un * 1e-3) / 1e12, 1)}
         result["extras"] = extras
 
     ng.ngemm_destroy(ctx)

@@ -221,11 +221,14 @@ ngemm_status ngemm_run_u8s8u8_requant_channel(ngemm_ctx *ctx, int64_t M,
                                               void *hip_stream);
 
 /*
- * Online-pack path, for the uncommon case where both operands are inputs of the call
- * (Sec. 3.1.1: "we can simply perform online packing with extra overhead"): B is given in its
- * plain column-major form, packed into the workspace on the stream, and multiplied at once.
- * The workspace must hold ngemm_unpacked_workspace_bytes(M, N, K) bytes (16-byte aligned): the
- * packed form of B followed by the row sums.  Result identical to ngemm_pack_b followed by
+ * Unpacked-B path, for the uncommon case where both operands are inputs of the call
+ * (Sec. 3.1.1: packing then has to happen online, at a cost): B is given in its plain
+ * column-major form (N rows of K contiguous int8, pitch ldb).  When the rows of A and of B are
+ * 16-byte aligned (pointers and pitches multiples of 16) and M > 32, nothing is packed at all:
+ * the tile kernels copy B's tiles from the caller's storage as they copy A's, and only the
+ * column sums are computed beforehand.  Otherwise B is packed into the workspace on the stream
+ * and multiplied at once.  The workspace must hold ngemm_unpacked_workspace_bytes(M, N, K)
+ * bytes (16-byte aligned) for either way.  Result identical to ngemm_pack_b followed by
  * ngemm_run_u8s8s32.
  */
 size_t ngemm_unpacked_workspace_bytes(int64_t M, int64_t N, int64_t K);

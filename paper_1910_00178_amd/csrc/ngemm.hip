@@ -96,7 +96,8 @@ hipError_t allow_big_lds()
 }
 
 template <int BM, int BN, int WGM, int WGN, int NSTAGE = 4>
-hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipStream_t st)
+hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipStream_t st,
+                           const RawB *rawb = nullptr)
 {
     using Cfg = DmaCfg<BM, BN, WGM, WGN, NSTAGE>;
     GemmParams p = p0;
@@ -109,10 +110,13 @@ hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipS
     const int nwg = ntiles < num_cus * per_cu ? ntiles : num_cus * per_cu;
     dim3 grid((unsigned)nwg), block(WGM * WGN * 64);
     const size_t smem = Cfg::kLdsBytes;
-    if (requant)
-        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, true>), grid, block, smem, st, p);
+    const RawB none{nullptr, 0};
+    if (rawb)        // unpacked B: int32 output only
+        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false, true>), grid, block, smem, st, p, *rawb);
+    else if (requant)
+        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, true>), grid, block, smem, st, p, none);
     else
-        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false>), grid, block, smem, st, p);
+        hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false>), grid, block, smem, st, p, none);
     return hipGetLastError();
 }
 
@@ -123,6 +127,9 @@ hipError_t allow_big_lds_dma()
     if (Cfg::kLdsBytes <= 64 * 1024) return hipSuccess;
     hipError_t e = hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute((const void *)gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
@@ -574,6 +581,42 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
     if (lda < K || ldb < K || ldc < N) return NGEMM_ERR_BAD_SHAPE;
     if (!workspace_dev || ((uintptr_t)workspace_dev & 15u) != 0) return NGEMM_ERR_INVALID_ARG;
     if (workspace_bytes < ngemm_unpacked_workspace_bytes(M, N, K)) return NGEMM_ERR_BUFFER_TOO_SMALL;
+    // Rows of both operands 16-byte aligned and an output that takes a tile kernel: no pack pass.
+    // The tile kernel reads B from the caller's storage with the same copies as A; only the column
+    // sums are computed beforehand (the row-sum kernel applied to B's [N x K] storage).
+    int kernel = ctx->force_kernel == NGEMM_KERNEL_AUTO ? choose_kernel(ctx, M, N) : ctx->force_kernel;
+    const bool aligned = (((uintptr_t)A_dev | (uintptr_t)lda | (uintptr_t)B_dev | (uintptr_t)ldb) & 15) == 0;
+    if (aligned && K > 0 && kernel != NGEMM_KERNEL_SKINNY) {
+        DeviceGuard g(ctx->device);
+        if (!g.ok) return NGEMM_ERR_DEVICE;
+        hipStream_t st = (hipStream_t)hip_stream;
+        ngemm_packed_b shape;                         // sizes only: nothing is packed
+        shape.magic = kPackMagic; shape.device = ctx->device;
+        shape.K = K; shape.N = N; shape.Kp = round_up(K, 64); shape.Np = round_up(N, 32);
+        shape.data = nullptr; shape.bytes = 0; shape.b_shift = 0;
+        RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, &shape, C_dev, ldc, false, 1.0f, 0};
+        GemmParams p = make_params(a);
+        int32_t *colsum = (int32_t *)workspace_dev;
+        int32_t *rowsum = (int32_t *)((uint8_t *)workspace_dev + round_up(shape.Np * 4, 256));
+        p.Bp = nullptr;
+        p.colsum = colsum;
+        hipLaunchKernelGGL(rowsum_a_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st, (const uint8_t *)B_dev,
+                           ldb, (int)N, (int)K, 0u, colsum);
+        if (hipGetLastError() != hipSuccess) return NGEMM_ERR_DEVICE;
+        if (b_zero_point != 0) {
+            hipLaunchKernelGGL(rowsum_a_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, A_dev, lda, (int)M,
+                               (int)K, p.a_xor, rowsum);
+            if (hipGetLastError() != hipSuccess) return NGEMM_ERR_DEVICE;
+            p.rowsum = rowsum;
+        }
+        const RawB rawb{(const uint8_t *)B_dev, ldb};
+        const int budget = workgroup_budget(ctx);
+        hipError_t e;
+        if (kernel == NGEMM_KERNEL_TILE_64) e = launch_tile_dma<64, 64, 2, 2>(p, false, budget, st, &rawb);
+        else if (kernel == NGEMM_KERNEL_TILE_128) e = launch_tile_dma<128, 128, 2, 2>(p, false, budget, st, &rawb);
+        else e = launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, false, budget, st, &rawb);
+        return e == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
+    }
     const size_t pb = (size_t)round_up((int64_t)ngemm_packed_b_bytes(K, N), 256);
     ngemm_packed_b *h = nullptr;
     ngemm_status s = ngemm_pack_b(ctx, K, N, B_dev, ldb, workspace_dev, pb, hip_stream, &h);

@@ -726,8 +726,16 @@ __device__ __forceinline__ void wait_vmcnt_and_lds()
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool REQUANT>
-__global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const GemmParams p)
+// An operand B that was not packed: the caller's int8 [N x K] storage (column j = ldb-strided row of
+// K contiguous bytes), 16-byte aligned.  It has the shape of A, so the BRAW form of the kernel below
+// copies and reads its tiles exactly as it does A's (Sec. 3.1.1: the case where both matrices are inputs).
+struct RawB {
+    const uint8_t *B;
+    int64_t ldb;
+};
+
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool REQUANT, bool BRAW = false>
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const GemmParams p, const RawB rawb)
 {
     using Cfg = DmaCfg<BM, BN, WGM, WGN, NSTAGE>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, KS = Cfg::KS, BK = Cfg::BK;
@@ -763,6 +771,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
         }
     }
     const int b_frag_off = Cfg::kABytes + (wn * TN * KS) * kFragBytes + lane * 16;
+    int b_raw_off[KS];                                  // BRAW: the B tile lies in A's block layout
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        b_raw_off[ks] = Cfg::kABytes + a_frag_off[ks] + (wn * TN - wm * TM) * 2048;
 
     for (int tile = w; tile < ntiles; tile += G) {
         int tm, tn;
@@ -781,9 +793,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
 #pragma unroll
         for (int i = 0; i < BI; ++i) {
             const int q = wave + NW * i;
-            int pnl = n0 / 32 + (q >> 1);
-            pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
-            b_src[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes + lane * 16;
+            if (BRAW) {
+                int gcol = n0 + q * 16 + t16;
+                gcol = gcol < p.N ? gcol : p.N - 1;      // columns past N: read a valid one, never stored
+                b_src[i] = rawb.B + (int64_t)gcol * rawb.ldb + a_chunk * 16;
+            } else {
+                int pnl = n0 / 32 + (q >> 1);
+                pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
+                b_src[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes + lane * 16;
+            }
         }
         auto dma_a = [&](int i, int kt, int buf) {
             __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + (int64_t)kt * BK),
@@ -792,7 +810,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
         };
         auto dma_b = [&](int i, int kt, int buf) {
             __builtin_amdgcn_global_load_lds(
-                (gptr_t)(b_src[i] + (int64_t)kt * (KS * kFragBytes)),
+                (gptr_t)(b_src[i] + (int64_t)kt * (BRAW ? BK : KS * kFragBytes)),
                 (lptr_t)(lds + buf * Cfg::kStageBytes + Cfg::kABytes + (wave + NW * i) * 1024), 16, 0, 0);
         };
         auto dma_stage = [&](int kt, int buf) {
@@ -808,7 +826,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
             if (idx < TM)
                 fa[slot][idx] = *(const v4i *)(base + a_frag_off[ks] + idx * 2048);
             else
-                fb[slot][idx - TM] = *(const v4i *)(base + b_frag_off + ((idx - TM) * KS + ks) * kFragBytes);
+                fb[slot][idx - TM] = BRAW ? *(const v4i *)(base + b_raw_off[ks] + (idx - TM) * 2048)
+                                          : *(const v4i *)(base + b_frag_off + ((idx - TM) * KS + ks) * kFragBytes);
         };
         auto read_frags = [&](int buf, int ks, int slot) {
 #pragma unroll
@@ -926,8 +945,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
             for (int i = 0; i < BI; ++i) {
                 const int q = wave + NW * i;
                 v4i v = {0, 0, 0, 0};
-                if (nfull * KS + (q & 1) < nslices)
+                if (BRAW) {
+                    const int valid = p.K - (kbase + a_chunk * 16);
+                    const uint8_t *src = b_src[i] + kbase;
+                    v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
+                } else if (nfull * KS + (q & 1) < nslices) {
                     v = *(const v4i *)(b_src[i] + (int64_t)nfull * (KS * kFragBytes));
+                }
                 *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) = v;
             }
             __syncthreads();

@@ -451,22 +451,38 @@ def test_unsigned_b_variant(rt, oracle):
 
 
 def test_online_pack_path(rt, oracle):
-    """Both operands as plain inputs: B is packed into the workspace inside the call."""
+    """Both operands as plain inputs.  Unaligned rows or M <= 32: B is packed into the workspace
+    inside the call.  Rows of A and B 16-byte aligned and M > 32: the tile kernels read B from
+    its plain storage (every tile size, K tails, ragged M and N, both zero-points)."""
     ng = ng_mod()
     rng = np.random.default_rng(95)
-    for (M, N, K, za, zb) in ((5, 100, 333, 7, -3), (200, 333, 500, 131, 0), (300, 300, 1024, 0, 9), (40, 64, 0, 3, 3)):
+    cases = [(5, 100, 333, 7, -3, 0), (200, 333, 500, 131, 0, 0), (300, 300, 1024, 0, 9, 0), (40, 64, 0, 3, 3, 0),
+             # (M, N, K, za, zb, pitch padding that makes the rows 16-byte aligned)
+             (300, 300, 1024, 0, 9, 16), (200, 333, 500, 131, 0, 12), (100, 70, 40, 5, -7, 8),
+             (33, 1000, 640, 250, 127, 0), (513, 257, 129, 128, -128, 15), (1024, 768, 768, 128, 0, 0)]
+    for (M, N, K, za, zb, pad) in cases:
         A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
         B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
-        Ad = torch.from_numpy(A).cuda() if A.size else torch.empty(16, dtype=torch.uint8, device="cuda")
-        Bd = torch.from_numpy(B).cuda() if B.size else torch.empty(16, dtype=torch.int8, device="cuda")
-        Cd = torch.full((M, N), -5, dtype=torch.int32, device="cuda")
+        want = oracle.gemm_u8s8s32(A, B, za, zb)
+        ld = K + pad
+        Ah = np.full((M, ld), 99, dtype=np.uint8); Ah[:, :K] = A
+        Bh = np.full((N, ld), 55, dtype=np.int8); Bh[:, :K] = B
+        # the allocations end with the last valid byte of the last row
+        Ad = torch.from_numpy(Ah.reshape(-1)[:(M - 1) * ld + K].copy()).cuda() if K else torch.empty(16, dtype=torch.uint8, device="cuda")
+        Bd = torch.from_numpy(Bh.reshape(-1)[:(N - 1) * ld + K].copy()).cuda() if K else torch.empty(16, dtype=torch.int8, device="cuda")
         wsb = ng.ngemm_unpacked_workspace_bytes(M, N, K)
         ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
-        ng.ngemm_run_u8s8s32_unpacked(rt.ctx, M, N, K, Ad, K, za, Bd, K, zb, Cd, N, ws, wsb)
-        torch.cuda.synchronize()
-        assert np.array_equal(Cd.cpu().numpy(), oracle.gemm_u8s8s32(A, B, za, zb)), (M, N, K)
+        for k in ((-1,) if M <= 32 or pad == 0 and K % 16 else (-1, 1, 2, 3)):
+            rt.set_kernel(k)
+            Cd = torch.full((M + 1, N + 3), -5, dtype=torch.int32, device="cuda")
+            ng.ngemm_run_u8s8s32_unpacked(rt.ctx, M, N, K, Ad, ld, za, Bd, ld, zb, Cd, N + 3, ws, wsb)
+            torch.cuda.synchronize()
+            got = Cd.cpu().numpy()
+            assert np.array_equal(got[:M, :N], want), (M, N, K, pad, k)
+            assert (got[M:, :] == -5).all() and (got[:, N:] == -5).all()
+        rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
         try:
-            ng.ngemm_run_u8s8s32_unpacked(rt.ctx, M, N, K, Ad, K, za, Bd, K, zb, Cd, N, ws, wsb - 1)
+            ng.ngemm_run_u8s8s32_unpacked(rt.ctx, M, N, K, Ad, ld, za, Bd, ld, zb, Cd, N + 3, ws, wsb - 1)
             assert False, "a short workspace must be refused"
         except ng.NgemmError as e:
             assert e.status == ng.NGEMM_ERR_BUFFER_TOO_SMALL
