@@ -79,6 +79,26 @@ ngemm_status ngemm_destroy(ngemm_ctx *ctx);
  * call return NGEMM_ERR_INVALID_ARG. */
 ngemm_status ngemm_set_kernel(ngemm_ctx *ctx, int kernel);
 
+/*
+ * Shape-driven tuning (the method searches its tiling per problem size, Sec. 3.1.1 and Sec. 4):
+ * run every kernel that can serve this call's shape on the caller's own operands (C is
+ * overwritten with the same, correct result each time), time them with events on the stream,
+ * and remember the fastest for later run calls of any entry point with the same (M, N, K) on
+ * this context while the kernel choice is NGEMM_KERNEL_AUTO.  Arguments as for
+ * ngemm_run_u8s8s32.  The call waits for the stream; it belongs to set-up, next to the pack.
+ * *best_kernel (may be NULL) receives the NGEMM_KERNEL_* value.  A context is not meant to be
+ * tuned and used from several threads at once.
+ */
+ngemm_status ngemm_tune_u8s8s32(ngemm_ctx *ctx, int64_t M,
+                                const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                const ngemm_packed_b *B, int32_t b_zero_point,
+                                int32_t *C_dev, int64_t ldc,
+                                void *workspace_dev, size_t workspace_bytes,
+                                void *hip_stream, int *best_kernel);
+
+/* The kernel remembered for a shape by ngemm_tune_u8s8s32, or NGEMM_KERNEL_AUTO if none. */
+ngemm_status ngemm_tuned_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N, int64_t K, int *kernel);
+
 /* Cap the number of persistent workgroups the large-tile kernel launches (0 = one per compute
  * unit, the default).  For sharing the device with other work, and for tests that want many
  * tiles per workgroup on a small problem. */

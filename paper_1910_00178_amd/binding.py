@@ -26,7 +26,7 @@ NGEMM_KERNEL_TILE_128 = 2
 NGEMM_KERNEL_TILE_256 = 3
 
 EXPORTS = (
-    "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_set_max_workgroups",
+    "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_tune_u8s8s32", "ngemm_tuned_kernel", "ngemm_set_max_workgroups",
     "ngemm_packed_b_bytes", "ngemm_pack_b", "ngemm_pack_b_u8", "ngemm_packed_b_free", "ngemm_packed_b_shape",
     "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_s8s8s32", "ngemm_run_u8u8s32", "ngemm_run_u8s8u8_requant",
     "ngemm_run_u8s8u8_requant_channel", "ngemm_unpacked_workspace_bytes", "ngemm_run_u8s8s32_unpacked",
@@ -63,6 +63,10 @@ _lib.ngemm_packed_b_shape.argtypes = [_p, ctypes.POINTER(_i64), ctypes.POINTER(_
 _lib.ngemm_workspace_bytes.restype = _sz
 _lib.ngemm_workspace_bytes.argtypes = [_i64, _i64, _i64]
 _lib.ngemm_run_u8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
+_lib.ngemm_tune_u8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p, ctypes.POINTER(_int)]
+_lib.ngemm_tune_u8s8s32.restype = _int
+_lib.ngemm_tuned_kernel.argtypes = [_p, _i64, _i64, _i64, ctypes.POINTER(_int)]
+_lib.ngemm_tuned_kernel.restype = _int
 _lib.ngemm_run_s8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
 _lib.ngemm_run_s8s8s32.restype = _int
 _lib.ngemm_run_u8u8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
@@ -174,6 +178,22 @@ def ngemm_run_u8s8s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, 
     _check(_lib.ngemm_run_u8s8s32(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B, int(b_zero_point),
                                   _dev(C_dev), int(ldc), _dev(workspace_dev), int(workspace_bytes),
                                   _stream(hip_stream)), "ngemm_run_u8s8s32")
+
+
+def ngemm_tune_u8s8s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, ldc,
+                       workspace_dev=None, workspace_bytes=0, hip_stream=None):
+    """Returns the NGEMM_KERNEL_* value found fastest (and remembered) for this shape."""
+    best = _int(-1)
+    _check(_lib.ngemm_tune_u8s8s32(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B, int(b_zero_point),
+                                   _dev(C_dev), int(ldc), _dev(workspace_dev), int(workspace_bytes),
+                                   _stream(hip_stream), ctypes.byref(best)), "ngemm_tune_u8s8s32")
+    return best.value
+
+
+def ngemm_tuned_kernel(ctx, M, N, K):
+    k = _int(-1)
+    _check(_lib.ngemm_tuned_kernel(ctx, int(M), int(N), int(K), ctypes.byref(k)), "ngemm_tuned_kernel")
+    return k.value
 
 
 def ngemm_run_s8s8s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, ldc,

@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <vector>
 
 using namespace ngemm;
 
@@ -17,6 +18,12 @@ struct ngemm_ctx {
     int num_cus;
     int force_kernel;
     int max_workgroups;      // 0 = one per compute unit
+    // kernels found fastest by ngemm_tune_u8s8s32, by shape; consulted before the shape heuristic
+    struct Tuned {
+        int64_t M, N, K;
+        int kernel;
+    };
+    std::vector<Tuned> tuned;
 };
 
 struct ngemm_packed_b {
@@ -203,7 +210,7 @@ int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N)
     auto tiles = [&](int64_t b) { return ((M + b - 1) / b) * ((N + b - 1) / b); };
     const int64_t cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
     if (tiles(256) * 4 >= cus * 3) return NGEMM_KERNEL_TILE_256;
-    if (tiles(128) >= cus * 2) return NGEMM_KERNEL_TILE_128;
+    if (tiles(128) >= cus) return NGEMM_KERNEL_TILE_128;
     return NGEMM_KERNEL_TILE_64;
 }
 
@@ -252,7 +259,11 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
     if (!a.C || (!a.A && a.B->K > 0)) return NGEMM_ERR_INVALID_ARG;
     if (a.lda < a.B->K || a.ldc < a.B->N) return NGEMM_ERR_BAD_SHAPE;
     int k = ctx->force_kernel;
-    if (k == NGEMM_KERNEL_AUTO) k = choose_kernel(ctx, a.M, a.B->N);
+    if (k == NGEMM_KERNEL_AUTO) {
+        for (const ngemm_ctx::Tuned &t : ctx->tuned)
+            if (t.M == a.M && t.N == a.B->N && t.K == a.B->K) k = t.kernel;
+        if (k == NGEMM_KERNEL_AUTO) k = choose_kernel(ctx, a.M, a.B->N);
+    }
     if (k == NGEMM_KERNEL_SKINNY && a.M > kSkinnyMaxM) return NGEMM_ERR_INVALID_ARG;
     *kernel_out = k;
     return NGEMM_OK;
@@ -411,6 +422,80 @@ ngemm_status ngemm_set_kernel(ngemm_ctx *ctx, int kernel)
     if (!ctx_ok(ctx)) return NGEMM_ERR_INVALID_ARG;
     if (kernel < NGEMM_KERNEL_AUTO || kernel >= NGEMM_KERNEL_COUNT) return NGEMM_ERR_INVALID_ARG;
     ctx->force_kernel = kernel;
+    return NGEMM_OK;
+}
+
+ngemm_status ngemm_tune_u8s8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                const ngemm_packed_b *B, int32_t b_zero_point, int32_t *C_dev, int64_t ldc,
+                                void *workspace_dev, size_t workspace_bytes, void *hip_stream, int *best_kernel)
+{
+    if (best_kernel) *best_kernel = NGEMM_KERNEL_AUTO;
+    if (!ctx_ok(ctx) || !pack_ok(B)) return NGEMM_ERR_INVALID_ARG;
+    RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, false, 1.0f, 0};
+    const int saved = ctx->force_kernel;
+    int dummy;
+    ctx->force_kernel = NGEMM_KERNEL_TILE_64;         // valid for every shape: checks the arguments
+    ngemm_status s = validate_run(ctx, a, &dummy);
+    ctx->force_kernel = saved;
+    if (s != NGEMM_OK) return s;
+    if (M == 0 || B->N == 0 || B->K == 0) return NGEMM_OK;   // nothing to measure
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return NGEMM_ERR_DEVICE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return NGEMM_ERR_DEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return NGEMM_ERR_DEVICE;
+    }
+    const int candidates[4] = {NGEMM_KERNEL_SKINNY, NGEMM_KERNEL_TILE_64, NGEMM_KERNEL_TILE_128, NGEMM_KERNEL_TILE_256};
+    int best = NGEMM_KERNEL_AUTO;
+    float best_ms = 0.0f;
+    s = NGEMM_OK;
+    for (int c = 0; c < 4 && s == NGEMM_OK; ++c) {
+        const int k = candidates[c];
+        if (k == NGEMM_KERNEL_SKINNY && M > kSkinnyMaxM) continue;
+        // a tile far larger than the output cannot win: skip what would leave most of it empty
+        if (k == NGEMM_KERNEL_TILE_256 && (M <= 64 || B->N <= 64)) continue;
+        ctx->force_kernel = k;
+        const int warm = 3, reps = 20;
+        for (int r = 0; r < warm + reps && s == NGEMM_OK; ++r) {
+            if (r == warm && hipEventRecord(e0, st) != hipSuccess) s = NGEMM_ERR_DEVICE;
+            if (s == NGEMM_OK) s = run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
+        }
+        float ms = 0.0f;
+        if (s == NGEMM_OK && (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                              hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+            s = NGEMM_ERR_DEVICE;
+        if (s == NGEMM_OK && (best == NGEMM_KERNEL_AUTO || ms < best_ms)) {
+            best = k;
+            best_ms = ms;
+        }
+    }
+    ctx->force_kernel = saved;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (s != NGEMM_OK) return s;
+    bool found = false;
+    for (ngemm_ctx::Tuned &t : ctx->tuned)
+        if (t.M == M && t.N == B->N && t.K == B->K) {
+            t.kernel = best;
+            found = true;
+        }
+    if (!found) {
+        if (ctx->tuned.size() >= 4096) ctx->tuned.erase(ctx->tuned.begin());
+        ctx->tuned.push_back(ngemm_ctx::Tuned{M, B->N, B->K, best});
+    }
+    if (best_kernel) *best_kernel = best;
+    return NGEMM_OK;
+}
+
+ngemm_status ngemm_tuned_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N, int64_t K, int *kernel)
+{
+    if (!ctx_ok(ctx) || !kernel) return NGEMM_ERR_INVALID_ARG;
+    *kernel = NGEMM_KERNEL_AUTO;
+    for (const ngemm_ctx::Tuned &t : ctx->tuned)
+        if (t.M == M && t.N == N && t.K == K) *kernel = t.kernel;
     return NGEMM_OK;
 }
 

@@ -488,6 +488,39 @@ def test_online_pack_path(rt, oracle):
             assert e.status == ng.NGEMM_ERR_BUFFER_TOO_SMALL
 
 
+def test_shape_tuning(rt, oracle):
+    """ngemm_tune_u8s8s32 measures the kernels that can serve a shape, remembers the fastest for
+    that (M, N, K), and later run calls with the automatic choice take it; results stay exact."""
+    ng = ng_mod()
+    rng = np.random.default_rng(99)
+    for (M, N, K) in ((16, 512, 256), (300, 500, 700), (2048, 2048, 512), (40, 3000, 64)):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        za, zb = 3, -2
+        want = oracle.gemm_u8s8s32(A, B, za, zb)
+        h, packed = rt.pack(B)
+        Ad = torch.from_numpy(A).cuda()
+        Cd = torch.full((M, N), -9, dtype=torch.int32, device="cuda")
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        assert ng.ngemm_tuned_kernel(rt.ctx, M, N, K) == ng.NGEMM_KERNEL_AUTO
+        best = ng.ngemm_tune_u8s8s32(rt.ctx, M, Ad, K, za, h, zb, Cd, N, ws, wsb)
+        allowed = (0, 1) if M <= 32 else (1, 2, 3)
+        assert best in allowed, (M, N, K, best)
+        assert ng.ngemm_tuned_kernel(rt.ctx, M, N, K) == best
+        assert np.array_equal(Cd.cpu().numpy(), want)          # the tuning runs leave the result in C
+        Cd.fill_(-9)
+        ng.ngemm_run_u8s8s32(rt.ctx, M, Ad, K, za, h, zb, Cd, N, ws, wsb)
+        torch.cuda.synchronize()
+        assert np.array_equal(Cd.cpu().numpy(), want)
+        try:
+            ng.ngemm_tune_u8s8s32(rt.ctx, M, Ad, K, 256, h, zb, Cd, N, ws, wsb)
+            assert False
+        except ng.NgemmError as e:
+            assert e.status == ng.NGEMM_ERR_INVALID_ARG
+        ng.ngemm_packed_b_free(h)
+
+
 def test_hip_graph_replays(rt, oracle):
     """Run calls captured in a HIP graph (the library allocates nothing and records no memset, so
     it can be captured): several replays with eager work and synchronisation in between, every
