@@ -142,31 +142,36 @@ hipError_t allow_big_lds_dma()
                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
 }
 
-// 64 x 64 tiles with the long pipeline: one workgroup per compute unit (its ring takes 128 KiB).
+// Small tiles with the long pipeline: one workgroup per compute unit (the ring takes 128 KiB).
+// T = 1: 64 x 64 tiles, stages of 256 bytes of K; T = 2: 128 x 128 tiles, stages of 128 bytes.
 constexpr int kDeepStages = 4;
+template <int T>
+constexpr int kDeepSub = T == 1 ? 4 : 2;
 
-hipError_t launch_tile64_deep(const GemmParams &p0, bool requant, int num_cus, hipStream_t st)
+template <int T>
+hipError_t launch_tile_deep(const GemmParams &p0, bool requant, int num_cus, hipStream_t st)
 {
-    using Cfg = DeepCfg<kDeepStages>;
+    using Cfg = DeepCfg<T, kDeepSub<T>, kDeepStages>;
     GemmParams p = p0;
-    p.tiles_m = (p.M + 63) / 64;
-    p.tiles_n = (p.N + 63) / 64;
+    p.tiles_m = (p.M + Cfg::BMN - 1) / Cfg::BMN;
+    p.tiles_n = (p.N + Cfg::BMN - 1) / Cfg::BMN;
     const int ntiles = p.tiles_m * p.tiles_n;
     dim3 grid((unsigned)(ntiles < num_cus ? ntiles : num_cus)), block(256);
     if (requant)
-        hipLaunchKernelGGL((gemm_tile64_deep_kernel<kDeepStages, true>), grid, block, Cfg::kLdsBytes, st, p);
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true>), grid, block, Cfg::kLdsBytes, st, p);
     else
-        hipLaunchKernelGGL((gemm_tile64_deep_kernel<kDeepStages, false>), grid, block, Cfg::kLdsBytes, st, p);
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false>), grid, block, Cfg::kLdsBytes, st, p);
     return hipGetLastError();
 }
 
+template <int T>
 hipError_t allow_big_lds_deep()
 {
-    using Cfg = DeepCfg<kDeepStages>;
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_tile64_deep_kernel<kDeepStages, true>,
+    using Cfg = DeepCfg<T, kDeepSub<T>, kDeepStages>;
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)gemm_tile64_deep_kernel<kDeepStages, false>,
+    return hipFuncSetAttribute((const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
 }
 
@@ -325,14 +330,17 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
     case NGEMM_KERNEL_TILE_64:
         // at most one tile per compute unit and a K worth pipelining: the long-pipeline variant
         if (dma_ok && B->K >= 512 && ((a.M + 63) / 64) * ((B->N + 63) / 64) <= (int64_t)device_cus)
-            e = launch_tile64_deep(p, a.requant, num_cus, st);
+            e = launch_tile_deep<1>(p, a.requant, num_cus, st);
         else
             e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st)
                        : launch_tile<64, 64, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_128:
-        e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st)
-                   : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
+        if (dma_ok && B->K >= 512 && ((a.M + 127) / 128) * ((B->N + 127) / 128) <= (int64_t)device_cus)
+            e = launch_tile_deep<2>(p, a.requant, num_cus, st);
+        else
+            e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st)
+                       : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_256:
         e = dma_ok ? launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, a.requant, num_cus, st)
@@ -399,7 +407,7 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
         DeviceGuard g(device_ordinal);
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
             allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
-            allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep() != hipSuccess) {
+            allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep<1>() != hipSuccess || allow_big_lds_deep<2>() != hipSuccess) {
             delete c;
             return NGEMM_ERR_DEVICE;
         }

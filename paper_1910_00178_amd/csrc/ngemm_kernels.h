@@ -972,25 +972,27 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
     }
 }
 
-// ---- 64 x 64 tiles with a long pipeline -------------------------------------------------------
-// For outputs with at most one 64 x 64 tile per compute unit.  There a workgroup is alone on its
-// compute unit, one wavefront per SIMD, and the kernel above spends its time waiting for LDS: a
-// wavefront has two matrix ops per 64 bytes of K and one barrier, with fragment reads issued one
-// matrix op ahead.  Here a stage is 256 bytes of K (four sub-blocks in the layout above, 32 KiB),
-// so a barrier pays for eight matrix ops per wavefront, and all sixteen fragments of stage it+1
-// are read into a second register set while the matrix ops of stage it run: the LDS latency has
-// half a stage (128 matrix-pipe cycles) to pass.  Ring of NSTAGE stage buffers, copies
-// memory -> LDS as above; the sub-blocks of the last, partial stage and the K tail are consumed
-// without pipelining.
-template <int NSTAGE>
+// ---- small tiles with a long pipeline ---------------------------------------------------------
+// For outputs with at most one 64 x 64 (T = 1) or 128 x 128 (T = 2) tile per compute unit.  There
+// a workgroup is alone on its compute unit, one wavefront per SIMD, and the kernel above spends
+// its time waiting for LDS: with T = 1 a wavefront has two matrix ops per 64 bytes of K and one
+// barrier, with fragment reads issued one matrix op ahead.  Here a stage is SUB sub-blocks of
+// 64 bytes of K in the layout above (32 KiB per stage), so one barrier pays for 2 * SUB * T * T
+// matrix ops per wavefront, and all fragments of stage it+1 are read into a second register set
+// while the matrix ops of stage it run: the LDS latency has half a stage to pass.  Ring of NSTAGE
+// stage buffers, copies memory -> LDS as above; the sub-blocks of the last, partial stage and
+// the K tail are consumed without pipelining.
+template <int T, int SUB, int NSTAGE>
 struct DeepCfg {
-    static constexpr int SUB = 4;                          // 64-byte sub-blocks of K per stage
-    static constexpr int kSubBytes = 2 * 64 * 64;          // A 64 x 64 + B 64 x 64
+    static constexpr int BMN = 64 * T;                     // tile edge
+    static constexpr int kABytes = BMN * 64;               // A part of a sub-block
+    static constexpr int kSubBytes = 2 * kABytes;          // A BMN x 64 + B BMN x 64
     static constexpr int kStageBytes = SUB * kSubBytes;
-    static constexpr int kLoadsPerStage = 2 * SUB;         // per lane: one A block, one B fragment per sub-block
-    static constexpr int kEpiBytes = 4 * kXposeBytes<1> + 64 * 12;
+    static constexpr int kLoadsPerStage = 2 * T * SUB;     // per lane: T blocks of A, T of B per sub-block
+    static constexpr int kEpiBytes = 4 * kXposeBytes<T> + BMN * 12;
     static constexpr int kLdsBytes = NSTAGE * kStageBytes > kEpiBytes ? NSTAGE * kStageBytes : kEpiBytes;
-    static_assert(NSTAGE >= 3 && NSTAGE <= 5, "ring depth");
+    static_assert(T == 1 || T == 2, "wavefront tile of 32 x 32 or 64 x 64");
+    static_assert(NSTAGE >= 3 && NSTAGE * kStageBytes <= 160 * 1024, "ring depth");
     static_assert((NSTAGE - 2) * kLoadsPerStage <= 63, "vmcnt range");
 };
 
@@ -999,11 +1001,17 @@ struct IntC {
     static constexpr int value = V;
 };
 
-template <int NSTAGE, bool REQUANT>
-__global__ __launch_bounds__(256) void gemm_tile64_deep_kernel(const GemmParams p)
+template <int T, int SUB, int NSTAGE, bool REQUANT>
+__global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
 {
-    using Cfg = DeepCfg<NSTAGE>;
-    constexpr int SUB = Cfg::SUB, LPS = Cfg::kLoadsPerStage, NF = 2 * SUB;   // NF fragments pairs per stage
+    using Cfg = DeepCfg<T, SUB, NSTAGE>;
+    constexpr int BMN = Cfg::BMN, LPS = Cfg::kLoadsPerStage;
+    constexpr int NF = 2 * SUB;                          // 32-byte steps of K per stage
+    constexpr int NM = T * T;                            // matrix ops per such step
+    constexpr int G = (NF / 2) * NM;                     // matrix ops (= gaps) in the second half of a stage
+    constexpr int NREADS = NF * 2 * T;                   // fragment reads per stage
+    constexpr int RPG = (NREADS + G / 2 - 1) / (G / 2);  // reads per gap: all in the first half of the gaps
+    constexpr int DPG = (LPS + G - 1) / G;               // copies per gap
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1015,7 +1023,7 @@ __global__ __launch_bounds__(256) void gemm_tile64_deep_kernel(const GemmParams 
     const int nstages = nst + (rem > 0 ? 1 : 0);
     const bool has_tail = nsub * 64 < p.Kp;
     const int ntiles = p.tiles_m * p.tiles_n;
-    const int G = gridDim.x, w = blockIdx.x;
+    const int gsz = gridDim.x, w = blockIdx.x;
 
     const int t16 = lane >> 2;
     const int a_chunk = ((lane & 3) - (t16 >> 2)) & 3;
@@ -1025,51 +1033,70 @@ __global__ __launch_bounds__(256) void gemm_tile64_deep_kernel(const GemmParams 
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const int c = 2 * ks + (lane >> 5);
-            a_frag_off[ks] = (wm * 2 + (r >> 4)) * 1024 + (4 * t + ((c + (t >> 2)) & 3)) * 16;
+            a_frag_off[ks] = (wm * T * 2 + (r >> 4)) * 1024 + (4 * t + ((c + (t >> 2)) & 3)) * 16;
         }
     }
-    const int b_frag_off = 4096 + (wn * 2) * kFragBytes + lane * 16;
+    const int b_frag_off = Cfg::kABytes + (wn * T * 2) * kFragBytes + lane * 16;
 
-    for (int tile = w; tile < ntiles; tile += G) {
+    for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
         tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
-        const int m0 = tm * 64, n0 = tn * 64;
+        const int m0 = tm * BMN, n0 = tn * BMN;
 
-        // Loader: wavefront v copies rows 16v..16v+15 of the A tile and fragment v (panel v/2,
-        // k-half v%2) of the B tile, for every sub-block.
-        int grow = m0 + wave * 16 + t16;
-        grow = grow < p.M ? grow : p.M - 1;              // rows past M: read a valid row, never stored
-        const uint8_t *a_src = p.A + (int64_t)grow * p.lda + a_chunk * 16;
-        int pnl = n0 / 32 + (wave >> 1);
-        pnl = pnl < p.npanels ? pnl : p.npanels - 1;     // panels past N: read a valid panel, never stored
-        const uint8_t *b_src = p.Bp + ((int64_t)pnl * nslices + (wave & 1)) * kFragBytes + lane * 16;
-
-        auto dma_sub = [&](int s, int q, int buf) {      // sub-block q of stage s into ring buffer buf
+        // Loader: wavefront v copies, for every sub-block, the 16-row blocks v, v+4, ... of the A
+        // tile and the fragments v, v+4, ... (panel q/2, k-half q%2) of the B tile.
+        const uint8_t *a_src[T], *b_src[T];
+#pragma unroll
+        for (int i = 0; i < T; ++i) {
+            int grow = m0 + (wave + 4 * i) * 16 + t16;
+            grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
+            a_src[i] = p.A + (int64_t)grow * p.lda + a_chunk * 16;
+            const int q = wave + 4 * i;
+            int pnl = n0 / 32 + (q >> 1);
+            pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
+            b_src[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes + lane * 16;
+        }
+        // copy number d of stage s into ring buffer buf: sub-block d / 2T, then T blocks of A, T of B
+        auto dma_one = [&](int s, int d, int buf) {
+            const int q = d / (2 * T), e = d % (2 * T);
             int g = s * SUB + q;
             g = g < nsub ? g : nsub - 1;                 // past the end: a copy nobody reads
-            uint8_t *dst = lds + buf * Cfg::kStageBytes + q * Cfg::kSubBytes + wave * 1024;
-            __builtin_amdgcn_global_load_lds((gptr_t)(a_src + (int64_t)g * 64), (lptr_t)dst, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(b_src + (int64_t)g * (2 * kFragBytes)), (lptr_t)(dst + 4096),
-                                             16, 0, 0);
+            uint8_t *dst = lds + buf * Cfg::kStageBytes + q * Cfg::kSubBytes;
+            if (e < T)
+                __builtin_amdgcn_global_load_lds((gptr_t)(a_src[e] + (int64_t)g * 64),
+                                                 (lptr_t)(dst + (wave + 4 * e) * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((gptr_t)(b_src[e - T] + (int64_t)g * (2 * kFragBytes)),
+                                                 (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (e - T)) * 1024), 16, 0, 0);
         };
         auto clamps = [&](int s) { return s < nstages ? s : nstages - 1; };
 
-        v4i fa[2][NF], fb[2][NF];                        // [register set][2 * sub-block + k-half]
-        auto read_pair = [&](auto set, int buf, int idx) {
+        v4i fa[2][NF][T], fb[2][NF][T];                  // [register set][32-byte step of the stage][block]
+        // fragment read number r of a stage: step r / 2T, then T fragments of A, T of B
+        auto read_one = [&](auto set, int buf, int r) {
             constexpr int S = decltype(set)::value;
+            const int idx = r / (2 * T), e = r % (2 * T);
             const uint8_t *base = lds + buf * Cfg::kStageBytes + (idx >> 1) * Cfg::kSubBytes;
-            fa[S][idx] = *(const v4i *)(base + a_frag_off[idx & 1]);
-            fb[S][idx] = *(const v4i *)(base + b_frag_off + (idx & 1) * kFragBytes);
+            if (e < T)
+                fa[S][idx][e] = *(const v4i *)(base + a_frag_off[idx & 1] + e * 2048);
+            else
+                fb[S][idx][e - T] = *(const v4i *)(base + b_frag_off + ((e - T) * 2 + (idx & 1)) * kFragBytes);
         };
 
-        v16i acc[1][1];
+        v16i acc[T][T];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[0][0][r] = 0;
-        // Packed operand first, as in the kernels above (the epilogue expects that register layout).
-        auto mma = [&](auto set, int idx) {
+        for (int i = 0; i < T; ++i)
+#pragma unroll
+            for (int j = 0; j < T; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+        // matrix op m of step idx; packed operand first, as in the kernels above (the epilogue
+        // expects that register layout).  The u8 -> s8 shift of an A fragment precedes its first use.
+        auto mma = [&](auto set, int idx, int m) {
             constexpr int S = decltype(set)::value;
-            const v4i a = shift_u8_to_s8(fa[S][idx], p.a_xor);
-            acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[S][idx], a, acc[0][0], 0, 0, 0);
+            const int i = m / T, j = m % T;
+            if (j == 0) fa[S][idx][i] = shift_u8_to_s8(fa[S][idx][i], p.a_xor);
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[S][idx][j], fa[S][idx][i], acc[i][j], 0, 0, 0);
         };
 
         if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
@@ -1078,39 +1105,40 @@ __global__ __launch_bounds__(256) void gemm_tile64_deep_kernel(const GemmParams 
 #pragma unroll
             for (int s = 0; s < NSTAGE - 1; ++s)
 #pragma unroll
-                for (int q = 0; q < SUB; ++q) dma_sub(clamps(s), q, s);
+                for (int d = 0; d < LPS; ++d) dma_one(clamps(s), d, s);
             wait_vmcnt<(NSTAGE - 2) * LPS>();            // stage 0 has landed (this wavefront's part)
             __builtin_amdgcn_s_barrier();                // ... and everybody else's
 #pragma unroll
-            for (int idx = 0; idx < NF; ++idx) read_pair(IntC<0>{}, 0, idx);
+            for (int r = 0; r < NREADS; ++r) read_one(IntC<0>{}, 0, r);
             __builtin_amdgcn_sched_barrier(0);
 
             // One full stage: register set S holds its fragments, the other set receives those of
-            // stage it+1.  First half: four matrix ops, then the wait for this wavefront's copies
-            // of stage it+1 and the barrier (=> stage it+1 is complete for everybody, and
+            // stage it+1.  First half: half of the matrix ops, then the wait for this wavefront's
+            // copies of stage it+1 and the barrier (=> stage it+1 is complete for everybody, and
             // everybody's reads of stage it-1 were consumed long ago, so its buffer is free).
-            // Second half: reads of stage it+1 and copies of stage it+NSTAGE-1 in the gaps
-            // between the other four matrix ops.
+            // Second half: reads of stage it+1 (all in the early gaps: they have the longest way)
+            // and copies of stage it+NSTAGE-1 in the gaps between the other matrix ops.
             auto body = [&](auto set, auto other, int it) {
                 const int buf_n = (it + 1) % NSTAGE, buf_f = (it + NSTAGE - 1) % NSTAGE;
                 const int sload = clamps(it + NSTAGE - 1);
 #pragma unroll
-                for (int idx = 0; idx < NF / 2; ++idx) {
-                    mma(set, idx);
+                for (int g = 0; g < G; ++g) {
+                    mma(set, g / NM, g % NM);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 wait_vmcnt<(NSTAGE - 3) * LPS>();
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int j = 0; j < NF / 2; ++j) {
-                    if (j < 2) {                         // all reads early: they have the longest way
+                for (int g = 0; g < G; ++g) {
 #pragma unroll
-                        for (int r = 0; r < NF / 2; ++r) read_pair(other, buf_n, j * (NF / 2) + r);
-                    }
-                    dma_sub(sload, j, buf_f);
+                    for (int r = g * RPG; r < (g + 1) * RPG; ++r)
+                        if (r < NREADS) read_one(other, buf_n, r);
+#pragma unroll
+                    for (int d = g * DPG; d < (g + 1) * DPG; ++d)
+                        if (d < LPS) dma_one(sload, d, buf_f);
                     __builtin_amdgcn_sched_barrier(0);
-                    mma(set, NF / 2 + j);
+                    mma(set, NF / 2 + g / NM, g % NM);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
@@ -1119,8 +1147,8 @@ __global__ __launch_bounds__(256) void gemm_tile64_deep_kernel(const GemmParams 
 #pragma unroll
                 for (int q = 0; q < SUB - 1; ++q)
                     if (q < rem) {
-                        mma(set, 2 * q);
-                        mma(set, 2 * q + 1);
+#pragma unroll
+                        for (int m = 0; m < 2 * NM; ++m) mma(set, 2 * q + m / NM, m % NM);
                     }
             };
             int it = 0;
@@ -1141,25 +1169,27 @@ __global__ __launch_bounds__(256) void gemm_tile64_deep_kernel(const GemmParams 
         if (has_tail) {
             const int kbase = nsub * 64;
             __syncthreads();
-            {
+#pragma unroll
+            for (int i = 0; i < T; ++i) {
+                const int q = wave + 4 * i;
                 const int valid = p.K - (kbase + a_chunk * 16);
-                const uint8_t *src = a_src + kbase;
+                const uint8_t *src = a_src[i] + kbase;
                 v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
-                *(v4i *)(lds + wave * 1024 + lane * 16) = v;
+                *(v4i *)(lds + q * 1024 + lane * 16) = v;
                 v4i z = {0, 0, 0, 0};
-                if (nsub * 2 + (wave & 1) < nslices) z = *(const v4i *)(b_src + (int64_t)nsub * (2 * kFragBytes));
-                *(v4i *)(lds + 4096 + wave * 1024 + lane * 16) = z;
+                if (nsub * 2 + (q & 1) < nslices) z = *(const v4i *)(b_src[i] + (int64_t)nsub * (2 * kFragBytes));
+                *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) = z;
             }
             __syncthreads();
-            read_pair(IntC<0>{}, 0, 0);
-            read_pair(IntC<0>{}, 0, 1);
-            mma(IntC<0>{}, 0);
-            mma(IntC<0>{}, 1);
+#pragma unroll
+            for (int r = 0; r < 2 * 2 * T; ++r) read_one(IntC<0>{}, 0, r);
+#pragma unroll
+            for (int m = 0; m < 2 * NM; ++m) mma(IntC<0>{}, m / NM, m % NM);
         }
 
         __syncthreads();                                 // every wavefront is done with the stage buffers
-        tile_epilogue<1, 1, 64, REQUANT>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<1>,
-                                         (uint32_t *)(lds + 4 * kXposeBytes<1>));
+        tile_epilogue<T, T, BMN, REQUANT>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
+                                          (uint32_t *)(lds + 4 * kXposeBytes<T>));
     }
 }
 

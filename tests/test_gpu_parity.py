@@ -310,23 +310,25 @@ def test_persistent_workgroups_many_tiles_each(rt, oracle):
 
 
 def test_long_pipeline_small_tile_kernel(rt, oracle):
-    """Outputs with at most one 64 x 64 tile per compute unit and K >= 512 take the long-pipeline
-    variant of the small-tile kernel: even and odd numbers of 256-byte stages, 0..3 sub-blocks in
-    the partial stage, K tails, ragged M and N, several tiles per workgroup, both epilogues."""
+    """Outputs with at most one 64 x 64 (128 x 128) tile per compute unit and K >= 512 take the
+    long-pipeline variant of the small-tile kernels: even and odd numbers of stages, every count
+    of sub-blocks in the partial stage, K tails, ragged M and N, several tiles per workgroup,
+    both epilogues."""
     ng = ng_mod()
     rng = np.random.default_rng(98)
     shapes = ((64, 64, 512), (100, 130, 768), (130, 70, 1000), (65, 65, 576), (200, 300, 1300), (64, 128, 4096),
-              (33, 1000, 640), (1024, 768, 1793))
+              (33, 1000, 640), (1024, 768, 1793), (129, 257, 704), (500, 640, 2048))
     for t, (M, N, K) in enumerate(shapes):
         A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
         B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
         za, zb = int(rng.integers(0, 256)), (0 if t % 2 else int(rng.integers(-128, 128)))
         lda = (K + 15) // 16 * 16                      # 16-byte aligned rows: the direct-to-LDS kernels
         prob = wl.Problem("deep%d" % t, A, B, za, zb, 0.0003, 77)
-        check_problem(rt, oracle, prob, (ng.NGEMM_KERNEL_TILE_64,), lda_pad=lda - K)
+        both = (ng.NGEMM_KERNEL_TILE_64, ng.NGEMM_KERNEL_TILE_128)     # 64 x 64 and 128 x 128 forms
+        check_problem(rt, oracle, prob, both, lda_pad=lda - K)
         ng.ngemm_set_max_workgroups(rt.ctx, 3)
         try:
-            check_problem(rt, oracle, prob, (ng.NGEMM_KERNEL_TILE_64,), lda_pad=lda - K)
+            check_problem(rt, oracle, prob, both, lda_pad=lda - K)
         finally:
             ng.ngemm_set_max_workgroups(rt.ctx, 0)
 
