@@ -8,6 +8,7 @@ from .ngemm_oracle import (  # noqa: F401
     gemm_u8s8s32,
     gemm_s8s8s32,
     gemm_u8u8s32,
+    gemm_s16s16s32,
     gemm_u8s8s64,
     gemm_u8s8s32_sampled,
     gemm_u8s8u8_requant,

@@ -123,6 +123,25 @@ void oracle_gemm_u8u8s32(int64_t M, int64_t N, int64_t K,
         }
 }
 
+/* 16-bit variant (Sec. 3.1 names s16 x s16 -> s32 among the types the method covers): the same
+ * definition on int16 operands, zero-points in the int16 range, low 32 bits of the exact sum. */
+void oracle_gemm_s16s16s32(int64_t M, int64_t N, int64_t K,
+                           const int16_t *A, int64_t lda, int32_t za,
+                           const int16_t *B, int64_t ldb, int32_t zb,
+                           int32_t *C, int64_t ldc)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            /* |a - za| and |b - zb| stay below 2^16, so a product stays below 2^32 and the sum of
+             * fewer than 2^31 of them below 2^63: int64 holds it exactly */
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k)
+                s += ((int64_t)A[i * lda + k] - za) * ((int64_t)B[j * ldb + k] - zb);
+            C[i * ldc + j] = wrap32(s);
+        }
+}
+
 /* Same sum without truncation, for the overflow-bound pins. */
 void oracle_gemm_u8s8s64(int64_t M, int64_t N, int64_t K,
                          const uint8_t *A, int64_t lda, int32_t za,

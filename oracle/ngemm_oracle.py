@@ -48,6 +48,8 @@ def _load():
         lib.oracle_gemm_s8s8s32.restype = None
         lib.oracle_gemm_u8u8s32.argtypes = [i64, i64, i64, p, i64, i32, p, i64, i32, p, i64]
         lib.oracle_gemm_u8u8s32.restype = None
+        lib.oracle_gemm_s16s16s32.argtypes = [i64, i64, i64, p, i64, i32, p, i64, i32, p, i64]
+        lib.oracle_gemm_s16s16s32.restype = None
         for name in ("oracle_gemm_u8s8s32", "oracle_gemm_u8s8s64", "oracle_requant_s32u8",
                      "oracle_gemm_u8s8u8_requant", "oracle_gemm_u8s8s32_sampled"):
             getattr(lib, name).restype = None
@@ -166,4 +168,18 @@ def gemm_u8u8s32(A, B, za=0, zb=0):
     ldb = B.strides[0] if N > 1 and K > 0 else K
     C = np.empty((M, N), dtype=np.int32)
     _load().oracle_gemm_u8u8s32(M, N, K, _ptr(A), lda, int(za), _ptr(B), ldb, int(zb), _ptr(C), N)
+    return C
+
+
+def gemm_s16s16s32(A, B, za=0, zb=0):
+    """16-bit variant: A int16 (M,K), B int16 (N,K); leading dimensions in elements."""
+    assert A.dtype == np.int16 and A.ndim == 2 and (A.size == 0 or A.strides[1] == 2)
+    assert B.dtype == np.int16 and B.ndim == 2 and (B.size == 0 or B.strides[1] == 2)
+    M, K = A.shape
+    N, Kb = B.shape
+    assert K == Kb
+    lda = A.strides[0] // 2 if M > 1 and K > 0 else K
+    ldb = B.strides[0] // 2 if N > 1 and K > 0 else K
+    C = np.empty((M, N), dtype=np.int32)
+    _load().oracle_gemm_s16s16s32(M, N, K, _ptr(A), lda, int(za), _ptr(B), ldb, int(zb), _ptr(C), N)
     return C

@@ -254,3 +254,37 @@ def test_unsigned_weight_variant_brute_force_and_relation_to_signed(oracle):
     full = lambda K: int(oracle.gemm_u8u8s32(np.full((1, K), 255, np.uint8), np.full((1, K), 255, np.uint8))[0, 0])
     assert full(33025) == 33025 * 65025 == 2147450625
     assert full(33026) == 33026 * 65025 - 2**32
+
+
+def test_16bit_variant(oracle):
+    """s16 x s16: Python-integer brute force with zero-points over the int16 range, a numpy product,
+    wrap at the extremes (32768^2 * 2 = 2^31 wraps to -2^31), leading dimensions, and agreement
+    with the 8-bit sum when the values fit 8 bits."""
+    rng = np.random.default_rng(53)
+    for _ in range(30):
+        M, N, K = (int(x) for x in rng.integers(1, 12, size=3))
+        A = rng.integers(-32768, 32768, size=(M, K), dtype=np.int16)
+        B = rng.integers(-32768, 32768, size=(N, K), dtype=np.int16)
+        za, zb = int(rng.integers(-32768, 32768)), int(rng.integers(-32768, 32768))
+        want = [[((sum((int(A[i, k]) - za) * (int(B[j, k]) - zb) for k in range(K)) + 2**31) % 2**32) - 2**31
+                 for j in range(N)] for i in range(M)]
+        assert oracle.gemm_s16s16s32(A, B, za, zb).tolist() == want
+    A = rng.integers(-3000, 3000, size=(37, 300), dtype=np.int16)
+    B = rng.integers(-200, 200, size=(29, 300), dtype=np.int16)
+    ref = (A.astype(np.int64) - 11) @ (B.astype(np.int64) + 7).T          # fits int32: no wrap
+    assert np.array_equal(oracle.gemm_s16s16s32(A, B, 11, -7).astype(np.int64), ref)
+    lo = np.full((1, 2), -32768, np.int16)
+    assert int(oracle.gemm_s16s16s32(lo, lo)[0, 0]) == -2**31            # 2 * 2^30 = 2^31 wraps
+    assert int(oracle.gemm_s16s16s32(lo[:, :1], lo[:, :1])[0, 0]) == 2**30
+    hi = np.full((1, 3), 32767, np.int16)
+    assert int(oracle.gemm_s16s16s32(hi, hi)[0, 0]) == (3 * 32767 * 32767 + 2**31) % 2**32 - 2**31
+    # padded rows (leading dimension > K) are not read
+    Ap = np.full((5, 40), 12345, np.int16); Ap[:, :33] = rng.integers(-32768, 32768, size=(5, 33))
+    Bp = np.full((4, 50), -321, np.int16); Bp[:, :33] = rng.integers(-32768, 32768, size=(4, 33))
+    assert np.array_equal(oracle.gemm_s16s16s32(Ap[:, :33], Bp[:, :33], 5, 6),
+                          oracle.gemm_s16s16s32(np.ascontiguousarray(Ap[:, :33]), np.ascontiguousarray(Bp[:, :33]), 5, 6))
+    # 8-bit values: the same sum as the signed 8-bit variant
+    A8 = rng.integers(-128, 128, size=(9, 70), dtype=np.int8)
+    B8 = rng.integers(-128, 128, size=(6, 70), dtype=np.int8)
+    assert np.array_equal(oracle.gemm_s16s16s32(A8.astype(np.int16), B8.astype(np.int16), -3, 9),
+                          oracle.gemm_s8s8s32(A8, B8, -3, 9))
