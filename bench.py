@@ -353,6 +353,18 @@ def main():
                                                 "u8u8s32_TOPS": round(ops / (ms_uu * 1e-3) / 1e12, 1)}
         ng.ngemm_packed_b_free(hsg)
         ng.ngemm_packed_b_free(hun)
+        # 16-bit operands through byte planes (four 8-bit matrix ops per block)
+        A16 = torch.from_numpy(rngt.integers(-32768, 32768, size=(n, n), dtype=np.int16)).cuda()
+        B16 = torch.from_numpy(rngt.integers(-32768, 32768, size=(n, n), dtype=np.int16)).cuda()
+        nb16 = ng.ngemm_packed_b_bytes_s16(n, n)
+        pk16 = torch.empty(nb16, dtype=torch.uint8, device="cuda")
+        h16 = ng.ngemm_pack_b_s16(ctx, n, n, B16, n, pk16, nb16)
+        wsb16 = ng.ngemm_workspace_bytes(n, n, n)
+        ws16 = torch.empty(wsb16, dtype=torch.uint8, device="cuda")
+        ms_16 = gpu_time_ms(lambda: ng.ngemm_run_s16s16s32(ctx, n, A16, n, 0, h16, 0, Ct, n, ws16, wsb16), 30, 30, torch)
+        extras["other_integer_types_%d" % n]["s16s16s32_TOPS"] = round(ops / (ms_16 * 1e-3) / 1e12, 1)
+        ng.ngemm_packed_b_free(h16)
+        del A16, B16, pk16
         # both operands as inputs: B read from its plain [N x K] storage, nothing packed
         uwb = ng.ngemm_unpacked_workspace_bytes(n, n, n)
         uws = torch.empty(uwb, dtype=torch.uint8, device="cuda")

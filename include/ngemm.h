@@ -241,6 +241,32 @@ ngemm_status ngemm_run_u8s8u8_requant_channel(ngemm_ctx *ctx, int64_t M,
                                               void *hip_stream);
 
 /*
+ * 16-bit variant, s16 x s16 -> s32 (Sec. 3.1 lists it among the types the method covers):
+ * C[i][j] = low 32 bits of sum_k (A[i][k] - a_zero_point) * (B[k][j] - b_zero_point) on int16
+ * operands, zero-points in [-32768, 32767].  The target has no 16-bit integer matrix
+ * instruction: the operands are split into byte planes and multiplied by four 8-bit matrix
+ * ops per block, exactly (mod 2^32).
+ *   ngemm_packed_b_bytes_s16 / ngemm_pack_b_s16: as ngemm_packed_b_bytes / ngemm_pack_b for an
+ *     int16 operand (ldb in elements, B_dev 2-byte aligned); the packed form takes
+ *     2 * (K rounded up to 32) * (N rounded up to 32) + 4 * (N rounded up to 32) bytes.
+ *   ngemm_run_s16s16s32: as ngemm_run_u8s8s32 (lda in elements).  Rows of A must be 16-byte
+ *     aligned (A_dev and 2 * lda multiples of 16), else NGEMM_ERR_INVALID_ARG; the workspace
+ *     (ngemm_workspace_bytes) is always needed.  A descriptor from ngemm_pack_b_s16 is accepted
+ *     by this call only, and this call accepts no other.
+ */
+size_t ngemm_packed_b_bytes_s16(int64_t K, int64_t N);
+ngemm_status ngemm_pack_b_s16(ngemm_ctx *ctx, int64_t K, int64_t N,
+                              const int16_t *B_dev, int64_t ldb,
+                              void *packed_dev, size_t packed_bytes,
+                              void *hip_stream, ngemm_packed_b **out);
+ngemm_status ngemm_run_s16s16s32(ngemm_ctx *ctx, int64_t M,
+                                 const int16_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                 const ngemm_packed_b *B, int32_t b_zero_point,
+                                 int32_t *C_dev, int64_t ldc,
+                                 void *workspace_dev, size_t workspace_bytes,
+                                 void *hip_stream);
+
+/*
  * Unpacked-B path, for the uncommon case where both operands are inputs of the call
  * (Sec. 3.1.1: packing then has to happen online, at a cost): B is given in its plain
  * column-major form (N rows of K contiguous int8, pitch ldb).  When the rows of A and of B are

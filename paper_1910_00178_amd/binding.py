@@ -28,7 +28,7 @@ NGEMM_KERNEL_TILE_256 = 3
 EXPORTS = (
     "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_tune_u8s8s32", "ngemm_tuned_kernel", "ngemm_set_max_workgroups",
     "ngemm_packed_b_bytes", "ngemm_pack_b", "ngemm_pack_b_u8", "ngemm_packed_b_free", "ngemm_packed_b_shape",
-    "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_s8s8s32", "ngemm_run_u8u8s32", "ngemm_run_u8s8u8_requant",
+    "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_s8s8s32", "ngemm_run_u8u8s32", "ngemm_packed_b_bytes_s16", "ngemm_pack_b_s16", "ngemm_run_s16s16s32", "ngemm_run_u8s8u8_requant",
     "ngemm_run_u8s8u8_requant_channel", "ngemm_unpacked_workspace_bytes", "ngemm_run_u8s8s32_unpacked",
     "ngemm_batched_workspace_bytes", "ngemm_run_batched_u8s8s32",
 )
@@ -71,6 +71,12 @@ _lib.ngemm_run_s8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64,
 _lib.ngemm_run_s8s8s32.restype = _int
 _lib.ngemm_run_u8u8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
 _lib.ngemm_run_u8u8s32.restype = _int
+_lib.ngemm_packed_b_bytes_s16.restype = _sz
+_lib.ngemm_packed_b_bytes_s16.argtypes = [_i64, _i64]
+_lib.ngemm_pack_b_s16.argtypes = [_p, _i64, _i64, _p, _i64, _p, _sz, _p, ctypes.POINTER(_p)]
+_lib.ngemm_pack_b_s16.restype = _int
+_lib.ngemm_run_s16s16s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
+_lib.ngemm_run_s16s16s32.restype = _int
 _lib.ngemm_run_u8s8u8_requant.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _f32, _i32, _p, _i64,
                                           _p, _sz, _p]
 _lib.ngemm_run_u8s8u8_requant_channel.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _p, _p, _i32, _i32,
@@ -208,6 +214,24 @@ def ngemm_run_u8u8s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, 
     _check(_lib.ngemm_run_u8u8s32(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B, int(b_zero_point),
                                   _dev(C_dev), int(ldc), _dev(workspace_dev), int(workspace_bytes),
                                   _stream(hip_stream)), "ngemm_run_u8u8s32")
+
+
+def ngemm_packed_b_bytes_s16(K, N):
+    return int(_lib.ngemm_packed_b_bytes_s16(int(K), int(N)))
+
+
+def ngemm_pack_b_s16(ctx, K, N, B_dev, ldb, packed_dev, packed_bytes, hip_stream=None):
+    h = _p()
+    _check(_lib.ngemm_pack_b_s16(ctx, int(K), int(N), _dev(B_dev), int(ldb), _dev(packed_dev), int(packed_bytes),
+                                 _stream(hip_stream), ctypes.byref(h)), "ngemm_pack_b_s16")
+    return h
+
+
+def ngemm_run_s16s16s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, ldc,
+                        workspace_dev=None, workspace_bytes=0, hip_stream=None):
+    _check(_lib.ngemm_run_s16s16s32(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B, int(b_zero_point),
+                                    _dev(C_dev), int(ldc), _dev(workspace_dev), int(workspace_bytes),
+                                    _stream(hip_stream)), "ngemm_run_s16s16s32")
 
 
 def ngemm_run_u8s8u8_requant(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, scale, c_zero_point,

@@ -33,6 +33,7 @@ struct ngemm_packed_b {
     const uint8_t *data;     // device, caller-owned
     size_t bytes;
     int32_t b_shift;         // 0: packed from int8; 128: packed from uint8, stored as B - 128
+    int32_t elem_bytes;      // 1: 8-bit operand; 2: int16 operand packed as two byte planes
 };
 
 namespace {
@@ -253,6 +254,7 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
     if (a.M < 0 || a.M > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
     if (a.a_signed ? (a.za < -128 || a.za > 127) : (a.za < 0 || a.za > 255)) return NGEMM_ERR_INVALID_ARG;
     if ((a.B->b_shift != 0) != a.b_unsigned) return NGEMM_ERR_INVALID_ARG;   // entry point and pack disagree
+    if (a.B->elem_bytes != 1) return NGEMM_ERR_INVALID_ARG;                  // a 16-bit pack: ngemm_run_s16s16s32 only
     if (a.zb < -128 || a.zb > 127) return NGEMM_ERR_INVALID_ARG;   // of the packed (signed) bytes
     if (a.requant && !a.scale_vec) {
         if (!std::isfinite(a.scale) || a.scale < 0x1p-30f || a.scale > 0x1p30f) return NGEMM_ERR_INVALID_ARG;
@@ -407,7 +409,9 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
         DeviceGuard g(device_ordinal);
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
             allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
-            allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep<1>() != hipSuccess || allow_big_lds_deep<2>() != hipSuccess) {
+            allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep<1>() != hipSuccess || allow_big_lds_deep<2>() != hipSuccess ||
+            hipFuncSetAttribute((const void *)gemm_s16_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                S16Cfg::kLdsBytes) != hipSuccess) {
             delete c;
             return NGEMM_ERR_DEVICE;
         }
@@ -544,6 +548,7 @@ static ngemm_status pack_common(ngemm_ctx *ctx, int64_t K, int64_t N, const int8
     d->data = (const uint8_t *)packed_dev;
     d->bytes = need;
     d->b_shift = b_shift;
+    d->elem_bytes = 1;
 
     if (Np > 0) {
         DeviceGuard g(ctx->device);
@@ -654,6 +659,107 @@ ngemm_status ngemm_run_u8s8u8_requant_channel(ngemm_ctx *ctx, int64_t M, const u
     return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
 }
 
+size_t ngemm_packed_b_bytes_s16(int64_t K, int64_t N)
+{
+    if (K < 0 || N < 0 || K > kMaxDim / 2 || N > kMaxDim) return 0;
+    const int64_t Kp = 2 * round_up(K, 32), Np = round_up(N, 32);
+    return (size_t)(Kp * Np + 4 * Np);
+}
+
+ngemm_status ngemm_pack_b_s16(ngemm_ctx *ctx, int64_t K, int64_t N, const int16_t *B_dev, int64_t ldb,
+                              void *packed_dev, size_t packed_bytes, void *hip_stream, ngemm_packed_b **out)
+{
+    if (!out) return NGEMM_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!ctx_ok(ctx)) return NGEMM_ERR_INVALID_ARG;
+    if (K < 0 || N < 0 || K > kMaxDim / 2 || N > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
+    if (K > 0 && N > 0 && (!B_dev || ldb < K)) return B_dev ? NGEMM_ERR_BAD_SHAPE : NGEMM_ERR_INVALID_ARG;
+    if (((uintptr_t)B_dev & 1u) != 0) return NGEMM_ERR_INVALID_ARG;
+    const size_t need = ngemm_packed_b_bytes_s16(K, N);
+    if (need > 0 && !packed_dev) return NGEMM_ERR_INVALID_ARG;
+    if (packed_bytes < need) return NGEMM_ERR_BUFFER_TOO_SMALL;
+    if (((uintptr_t)packed_dev & 15u) != 0) return NGEMM_ERR_INVALID_ARG;
+    const int64_t Kp = 2 * round_up(K, 32), Np = round_up(N, 32);
+    ngemm_packed_b *d = new (std::nothrow) ngemm_packed_b;
+    if (!d) return NGEMM_ERR_DEVICE;
+    d->magic = kPackMagic;
+    d->device = ctx->device;
+    d->K = K; d->N = N; d->Kp = Kp; d->Np = Np;
+    d->data = (const uint8_t *)packed_dev;
+    d->bytes = need;
+    d->b_shift = 0;
+    d->elem_bytes = 2;
+    if (Np > 0) {
+        DeviceGuard g(ctx->device);
+        if (!g.ok) { delete d; return NGEMM_ERR_DEVICE; }
+        hipStream_t st = (hipStream_t)hip_stream;
+        int32_t *colsum = (int32_t *)((uint8_t *)packed_dev + Kp * Np);
+        hipLaunchKernelGGL(rowsum_s16_kernel, dim3((unsigned)((Np + 3) / 4)), dim3(256), 0, st, B_dev, ldb, (int)N,
+                           (int)Np, (int)K, colsum);
+        if (hipGetLastError() != hipSuccess) { delete d; return NGEMM_ERR_DEVICE; }
+        if (Kp > 0) {
+            const int64_t nslices = Kp / 64;                       // 32-element slices
+            const int64_t nchunks = (Np / 32) * nslices * 64;
+            const int64_t nwg = (nchunks + 255) / 256;
+            if (nwg > 0x7fffffff) { delete d; return NGEMM_ERR_BAD_SHAPE; }
+            hipLaunchKernelGGL(pack_b_s16_kernel, dim3((unsigned)nwg), dim3(256), 0, st, B_dev, ldb, (int)K, (int)N,
+                               (int)nslices, nchunks, (uint8_t *)packed_dev);
+            if (hipGetLastError() != hipSuccess) { delete d; return NGEMM_ERR_DEVICE; }
+        }
+    }
+    *out = d;
+    return NGEMM_OK;
+}
+
+ngemm_status ngemm_run_s16s16s32(ngemm_ctx *ctx, int64_t M, const int16_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                 const ngemm_packed_b *B, int32_t b_zero_point, int32_t *C_dev, int64_t ldc,
+                                 void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx_ok(ctx) || !pack_ok(B) || B->elem_bytes != 2 || B->device != ctx->device) return NGEMM_ERR_INVALID_ARG;
+    if (M < 0 || M > kMaxDim) return NGEMM_ERR_BAD_SHAPE;
+    if (a_zero_point < -32768 || a_zero_point > 32767 || b_zero_point < -32768 || b_zero_point > 32767)
+        return NGEMM_ERR_INVALID_ARG;
+    if (M == 0 || B->N == 0) return NGEMM_OK;
+    if (!C_dev || (!A_dev && B->K > 0)) return NGEMM_ERR_INVALID_ARG;
+    if (lda < B->K || ldc < B->N) return NGEMM_ERR_BAD_SHAPE;
+    // the kernel copies rows of A straight into LDS in 16-byte pieces
+    if ((((uintptr_t)A_dev | (uintptr_t)(lda * 2)) & 15) != 0) return NGEMM_ERR_INVALID_ARG;
+    if (B->K > 0) {
+        if (!workspace_dev) return NGEMM_ERR_INVALID_ARG;
+        if (workspace_bytes < rowsum_bytes(M)) return NGEMM_ERR_BUFFER_TOO_SMALL;
+    }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return NGEMM_ERR_DEVICE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    GemmParams p;
+    std::memset(&p, 0, sizeof p);
+    p.A = (const uint8_t *)A_dev;
+    p.lda = lda * 2;
+    p.Bp = B->data;
+    p.colsum = (const int32_t *)(B->data + B->Kp * B->Np);
+    p.C = C_dev;
+    p.ldc = ldc;
+    p.M = (int)M; p.N = (int)B->N; p.K = (int)B->K; p.Kp = (int)B->Kp;
+    p.npanels = (int)(B->Np / 32);
+    p.tiles_m = (int)((M + 127) / 128);
+    p.tiles_n = (int)((B->N + 127) / 128);
+    // sum (a-za)(b-zb) = sum (a-128)(b-128) + (128-za) colsum'[j] - (zb-128) rowsum'[i] - (zb-128)(128-za) K
+    p.za_term = (uint32_t)(128 - a_zero_point);
+    p.zb = (uint32_t)(b_zero_point - 128);
+    p.kconst = 0u - (uint32_t)(b_zero_point - 128) * (uint32_t)(128 - a_zero_point) * (uint32_t)B->K;
+    if (B->K > 0) {
+        int32_t *rs = (int32_t *)workspace_dev;
+        hipLaunchKernelGGL(rowsum_s16_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, A_dev, lda, (int)M,
+                           (int)M, (int)B->K, rs);
+        if (hipGetLastError() != hipSuccess) return NGEMM_ERR_DEVICE;
+        p.rowsum = rs;
+    }
+    const int ntiles = p.tiles_m * p.tiles_n, budget = workgroup_budget(ctx);
+    hipLaunchKernelGGL(gemm_s16_tile_kernel, dim3((unsigned)(ntiles < budget ? ntiles : budget)), dim3(256),
+                       S16Cfg::kLdsBytes, st, p);
+    return hipGetLastError() == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
+}
+
 size_t ngemm_unpacked_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return 0;
@@ -686,7 +792,7 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
         ngemm_packed_b shape;                         // sizes only: nothing is packed
         shape.magic = kPackMagic; shape.device = ctx->device;
         shape.K = K; shape.N = N; shape.Kp = round_up(K, 64); shape.Np = round_up(N, 32);
-        shape.data = nullptr; shape.bytes = 0; shape.b_shift = 0;
+        shape.data = nullptr; shape.bytes = 0; shape.b_shift = 0; shape.elem_bytes = 1;
         RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, &shape, C_dev, ldc, false, 1.0f, 0};
         GemmParams p = make_params(a);
         int32_t *colsum = (int32_t *)workspace_dev;

@@ -1193,6 +1193,286 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
     }
 }
 
+// ---- 16-bit operands: s16 x s16 -> s32 on the 8-bit matrix pipe -------------------------------
+// There is no 16-bit integer matrix instruction; a 16-bit value is split into its bytes,
+//     a - 128 = 256 * ah + al',   ah = a >> 8 (signed),   al' = (a & 255) - 128 = (a & 255) xor 0x80,
+// and likewise for b, so that
+//     sum (a-128)(b-128) = 65536 * sum ah*bh + 256 * (sum ah*bl' + sum al'*bh) + sum al'*bl'   (mod 2^32)
+// is three int32 accumulators fed by four 8-bit matrix ops per 32 x 32 x 32 block; every step is
+// exact in the ring of integers mod 2^32.  The zero-points enter as for the unsigned 8-bit operand:
+//     sum (a-za)(b-zb) = sum (a-128)(b-128) + (128-zb) * rowsum'[i] + (128-za) * colsum'[j] + K (128-za)(128-zb)
+// with rowsum'[i] = sum_k (a[i][k] - 128), colsum'[j] = sum_k (b[k][j] - 128): the epilogue above with
+// zb - 128 in the place of zb.
+//
+// Packed B: per 32-column panel and 32 elements of K two fragments, the ah-plane and the al'-plane, in
+// the fragment layout of the 8-bit pack (byte n of lane l = element 16 * (l / 32) + n of column l % 32),
+// panel contiguous over K; zero padded to (K rounded up to 32) x (N rounded up to 32).  A stage of the
+// kernel is 32 elements of K: 64 bytes per row of A in the block layout of the 8-bit kernel, and the
+// two planes of B, which have exactly the shape of the two k-halves there, so the copies are the same.
+// A's bytes are separated after the LDS read by byte permutes.
+
+// Row sums of an int16 matrix minus 128 per element: out[i] = sum_k (X[i][k] - 128), rows >= rows_valid
+// give 0.  One wavefront per row.
+__global__ __launch_bounds__(256) void rowsum_s16_kernel(const int16_t *__restrict__ X, int64_t ldx, int rows_valid,
+                                                         int rows_out, int K, int32_t *__restrict__ out)
+{
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (i >= rows_out) return;
+    int s = 0;
+    if (i < rows_valid) {
+        const int16_t *row = X + (int64_t)i * ldx;
+        for (int k = lane * 8; k < K; k += 64 * 8) {
+            if (k + 8 <= K) {
+                int16_t v[8];
+                __builtin_memcpy(v, row + k, 16);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) s += (int)v[t] - 128;
+            } else {
+                for (int t = 0; k + t < K; ++t) s += (int)row[k + t] - 128;
+            }
+        }
+    }
+    s = wave_sum(s);
+    if (lane == 0) out[i] = s;
+}
+
+// Pack of the int16 operand.  One thread per (panel, 32-element slice, lane of the fragment): it reads
+// its 16 elements and writes 16 bytes into each plane.
+__global__ __launch_bounds__(256) void pack_b_s16_kernel(const int16_t *__restrict__ B, int64_t ldb, int K, int N,
+                                                         int nslices, int64_t nchunks, uint8_t *__restrict__ packed)
+{
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= nchunks) return;
+    const int l = (int)(id & 63);
+    const int64_t f = id >> 6;                           // (panel, slice)
+    const int s = (int)(f % nslices);
+    const int64_t pnl = f / nslices;
+    const int64_t j = pnl * 32 + (l & 31);
+    const int k0 = s * 32 + (l >> 5) * 16;
+    uint32_t hi[4] = {0u, 0u, 0u, 0u}, lo[4] = {0u, 0u, 0u, 0u};
+    if (j < N) {
+        const int16_t *src = B + j * ldb + k0;
+#pragma unroll
+        for (int n = 0; n < 16; ++n)
+            if (k0 + n < K) {
+                const uint32_t v = (uint32_t)(uint16_t)src[n];
+                hi[n >> 2] |= (v >> 8) << (8 * (n & 3));
+                lo[n >> 2] |= ((v & 255u) ^ 0x80u) << (8 * (n & 3));
+            }
+    }
+    v4i h, w;
+    h.x = (int)hi[0]; h.y = (int)hi[1]; h.z = (int)hi[2]; h.w = (int)hi[3];
+    w.x = (int)lo[0]; w.y = (int)lo[1]; w.z = (int)lo[2]; w.w = (int)lo[3];
+    uint8_t *dst = packed + (f * 2) * kFragBytes + l * 16;
+    *(v4i *)dst = h;
+    *(v4i *)(dst + kFragBytes) = w;
+}
+
+struct S16Cfg {
+    static constexpr int NSTAGE = 8;
+    static constexpr int kABytes = 128 * 64;               // 128 rows x 32 elements
+    static constexpr int kStageBytes = 2 * kABytes;        // + 4 panels x 2 planes x 1 KiB
+    static constexpr int kLoadsPerStage = 4;               // per lane: 2 blocks of A, 2 fragments of B
+    static constexpr int kEpiBytes = 4 * kXposeBytes<2> + 128 * 12;
+    static constexpr int kLdsBytes = NSTAGE * kStageBytes > kEpiBytes ? NSTAGE * kStageBytes : kEpiBytes;
+};
+
+// p.A / p.lda: the int16 matrix as bytes (lda in bytes, a multiple of 16, rows 16-byte aligned);
+// p.K: elements; p.Kp: bytes of one packed column (2 * K rounded up to 32 elements); p.zb: zb - 128;
+// p.rowsum / p.colsum: the sums above.  128 x 128 tiles, four wavefronts of 64 x 64.
+__global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
+{
+    using Cfg = S16Cfg;
+    constexpr int NSTAGE = Cfg::NSTAGE, LPS = Cfg::kLoadsPerStage;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int nfrag = p.Kp / 32;                         // fragments per panel (two per 32 elements)
+    const int nst = p.K / 32;                            // full stages
+    const bool has_tail = nst * 32 < p.K;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int gsz = gridDim.x, w = blockIdx.x;
+
+    const int t16 = lane >> 2;
+    const int a_chunk = ((lane & 3) - (t16 >> 2)) & 3;
+    int a_off[2];                                        // this lane's two 16-byte chunks (8 elements each)
+    {
+        const int r = lane & 31, t = r & 15;
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2) {
+            const int c = 2 * (lane >> 5) + c2;
+            a_off[c2] = (wm * 4 + (r >> 4)) * 1024 + (4 * t + ((c + (t >> 2)) & 3)) * 16;
+        }
+    }
+    const int b_off = Cfg::kABytes + (wn * 4) * kFragBytes + lane * 16;
+
+    for (int tile = w; tile < ntiles; tile += gsz) {
+        int tm, tn;
+        tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
+        const int m0 = tm * 128, n0 = tn * 128;
+
+        const uint8_t *a_src[2], *b_src[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            int grow = m0 + (wave + 4 * i) * 16 + t16;
+            grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
+            a_src[i] = p.A + (int64_t)grow * p.lda + a_chunk * 16;
+            const int q = wave + 4 * i;                  // panel q / 2, plane q % 2
+            int pnl = n0 / 32 + (q >> 1);
+            pnl = pnl < p.npanels ? pnl : p.npanels - 1;
+            b_src[i] = p.Bp + ((int64_t)pnl * nfrag + (q & 1)) * kFragBytes + lane * 16;
+        }
+        auto dma_one = [&](int s, int d, int buf) {      // copy d (0..3) of stage s
+            const int g = s < nst ? s : nst - 1;         // past the end: a copy nobody reads
+            uint8_t *dst = lds + buf * Cfg::kStageBytes;
+            if (d < 2)
+                __builtin_amdgcn_global_load_lds((gptr_t)(a_src[d] + (int64_t)g * 64),
+                                                 (lptr_t)(dst + (wave + 4 * d) * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((gptr_t)(b_src[d - 2] + (int64_t)g * (2 * kFragBytes)),
+                                                 (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (d - 2)) * 1024), 16, 0, 0);
+        };
+
+        v4i ar[2][2][2], br[2][2][2];                    // [register set][block][chunk | plane]
+        auto read_one = [&](auto set, int buf, int r) {  // fragment read r (0..7) of a stage
+            constexpr int S = decltype(set)::value;
+            const uint8_t *base = lds + buf * Cfg::kStageBytes;
+            const int blk = (r >> 1) & 1, x = r & 1;
+            if (r < 4)
+                ar[S][blk][x] = *(const v4i *)(base + a_off[x] + blk * 2048);
+            else
+                br[S][blk][x] = *(const v4i *)(base + b_off + (blk * 2 + x) * kFragBytes);
+        };
+
+        v16i hh[2][2], xx[2][2], ll[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    hh[i][j][r] = 0;
+                    xx[i][j][r] = 0;
+                    ll[i][j][r] = 0;
+                }
+        v4i ah[2], al[2];
+        // bytes of 16 consecutive elements (two chunks) -> the high bytes and the shifted low bytes
+        auto split = [&](auto set, int i) {
+            constexpr int S = decltype(set)::value;
+            const v4i c0 = ar[S][i][0], c1 = ar[S][i][1];
+            ah[i].x = (int)__builtin_amdgcn_perm((uint32_t)c0.y, (uint32_t)c0.x, 0x07050301u);
+            ah[i].y = (int)__builtin_amdgcn_perm((uint32_t)c0.w, (uint32_t)c0.z, 0x07050301u);
+            ah[i].z = (int)__builtin_amdgcn_perm((uint32_t)c1.y, (uint32_t)c1.x, 0x07050301u);
+            ah[i].w = (int)__builtin_amdgcn_perm((uint32_t)c1.w, (uint32_t)c1.z, 0x07050301u);
+            al[i].x = (int)(__builtin_amdgcn_perm((uint32_t)c0.y, (uint32_t)c0.x, 0x06040200u) ^ 0x80808080u);
+            al[i].y = (int)(__builtin_amdgcn_perm((uint32_t)c0.w, (uint32_t)c0.z, 0x06040200u) ^ 0x80808080u);
+            al[i].z = (int)(__builtin_amdgcn_perm((uint32_t)c1.y, (uint32_t)c1.x, 0x06040200u) ^ 0x80808080u);
+            al[i].w = (int)(__builtin_amdgcn_perm((uint32_t)c1.w, (uint32_t)c1.z, 0x06040200u) ^ 0x80808080u);
+        };
+        // matrix op m (0..15) of a stage; the two ops that share an accumulator are eight apart.
+        // Packed operand first, as in the 8-bit kernels (the epilogue expects that register layout).
+        auto mma = [&](auto set, int m) {
+            constexpr int S = decltype(set)::value;
+            const int i = (m >> 1) & 1, j = m & 1;
+            switch (m >> 2) {
+            case 0: hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(br[S][j][0], ah[i], hh[i][j], 0, 0, 0); break;
+            case 1: xx[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(br[S][j][1], ah[i], xx[i][j], 0, 0, 0); break;
+            case 2: ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(br[S][j][1], al[i], ll[i][j], 0, 0, 0); break;
+            default: xx[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(br[S][j][0], al[i], xx[i][j], 0, 0, 0); break;
+            }
+        };
+
+        if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
+
+        if (nst > 0) {
+#pragma unroll
+            for (int s = 0; s < NSTAGE - 1; ++s)
+#pragma unroll
+                for (int d = 0; d < LPS; ++d) dma_one(s, d, s);
+            wait_vmcnt<(NSTAGE - 2) * LPS>();            // stage 0 has landed (this wavefront's part)
+            __builtin_amdgcn_s_barrier();
+#pragma unroll
+            for (int r = 0; r < 8; ++r) read_one(IntC<0>{}, 0, r);
+            __builtin_amdgcn_sched_barrier(0);
+
+            // One stage: set S holds its raw fragments, the other set receives those of stage it+1
+            // in the gaps of the second half, behind the barrier that makes stage it+1 complete and
+            // the buffer of stage it-1 free; the copies of stage it+NSTAGE-1 follow into that buffer.
+            auto body = [&](auto set, auto other, int it) {
+                const int buf_n = (it + 1) % NSTAGE, buf_f = (it + NSTAGE - 1) % NSTAGE;
+                split(set, 0);
+                split(set, 1);
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    mma(set, m);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                wait_vmcnt<(NSTAGE - 3) * LPS>();
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int m = 8; m < 16; ++m) {
+                    if (m < 12) {
+                        read_one(other, buf_n, 2 * (m - 8));
+                        read_one(other, buf_n, 2 * (m - 8) + 1);
+                    } else {
+                        dma_one(it + NSTAGE - 1, m - 12, buf_f);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma(set, m);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            int it = 0;
+            for (; it + 1 < nst; it += 2) {
+                body(IntC<0>{}, IntC<1>{}, it);
+                body(IntC<1>{}, IntC<0>{}, it + 1);
+            }
+            if (it < nst) body(IntC<0>{}, IntC<1>{}, it);
+            wait_vmcnt<0>();                             // drain the copies nobody reads
+        }
+
+        // K tail: fewer than 32 elements.  Guarded register loads of A, the zero-padded planes of B.
+        if (has_tail) {
+            const int kbase = nst * 64;                  // bytes into a row of A
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int q = wave + 4 * i;
+                const int valid = 2 * p.K - (kbase + a_chunk * 16);
+                const uint8_t *src = a_src[i] + kbase;
+                v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
+                *(v4i *)(lds + q * 1024 + lane * 16) = v;
+                *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) =
+                    *(const v4i *)(b_src[i] + (int64_t)nst * (2 * kFragBytes));
+            }
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < 8; ++r) read_one(IntC<0>{}, 0, r);
+            split(IntC<0>{}, 0);
+            split(IntC<0>{}, 1);
+#pragma unroll
+            for (int m = 0; m < 16; ++m) mma(IntC<0>{}, m);
+        }
+
+        // (a-128)(b-128) sums: 65536 * hh + 256 * xx + ll, wrapping
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    hh[i][j][r] = (int)(((uint32_t)hh[i][j][r] << 16) + ((uint32_t)xx[i][j][r] << 8) +
+                                        (uint32_t)ll[i][j][r]);
+
+        __syncthreads();                                 // every wavefront is done with the stage buffers
+        tile_epilogue<2, 2, 128, false>(p, hh, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<2>,
+                                        (uint32_t *)(lds + 4 * kXposeBytes<2>));
+    }
+}
+
 // ---- skinny-M kernel (M <= 32) --------------------------------------------------------------
 // Bandwidth-bound: one workgroup per P adjacent 32-column panels; its wavefronts split K
 // (wavefront v takes fragments v, v + nwaves, ... so that the workgroup sweeps a panel

@@ -452,6 +452,80 @@ def test_unsigned_b_variant(rt, oracle):
     ng.ngemm_packed_b_free(h)
 
 
+def test_16bit_variant(rt, oracle):
+    """s16 x s16 -> s32 through byte planes on the 8-bit matrix pipe: pack layout (two planes per
+    32-element slice, zero padded, column sums of b - 128), parity on ragged shapes with K tails,
+    zero-points over the int16 range, extreme values (wrap), several tiles per workgroup, and the
+    refusals between descriptor types."""
+    ng = ng_mod()
+    rng = np.random.default_rng(101)
+    shapes = ((1, 1, 1), (5, 7, 31), (64, 64, 32), (100, 130, 100), (130, 257, 320), (300, 200, 1000), (128, 128, 2048),
+              (257, 129, 65))
+    for t, (M, N, K) in enumerate(shapes):
+        if t == 3:      # extremes: every product near 2^30, sums wrap
+            A = rng.choice(np.array([-32768, 32767], dtype=np.int16), size=(M, K))
+            B = rng.choice(np.array([-32768, 32767], dtype=np.int16), size=(N, K))
+        else:
+            A = rng.integers(-32768, 32768, size=(M, K), dtype=np.int16)
+            B = rng.integers(-32768, 32768, size=(N, K), dtype=np.int16)
+        za = int(rng.integers(-32768, 32768)) if t % 3 else 0
+        zb = 128 if t == 2 else (int(rng.integers(-32768, 32768)) if t % 2 else 0)
+        want = oracle.gemm_s16s16s32(A, B, za, zb)
+        lda = (K + 7) // 8 * 8
+        Ah = np.full((M, lda), 1234, dtype=np.int16); Ah[:, :K] = A
+        Ad = torch.from_numpy(Ah.reshape(-1)[:(M - 1) * lda + K].copy()).cuda()     # ends with the last valid element
+        Bh = np.full((N, K + 3), -77, dtype=np.int16); Bh[:, :K] = B
+        Bd = torch.from_numpy(Bh).cuda()
+        nbytes = ng.ngemm_packed_b_bytes_s16(K, N)
+        Kp, Np = (K + 31) // 32 * 32, (N + 31) // 32 * 32
+        assert nbytes == 2 * Kp * Np + 4 * Np
+        packed = torch.full((nbytes,), 0x5a, dtype=torch.uint8, device="cuda")
+        h = ng.ngemm_pack_b_s16(rt.ctx, K, N, Bd, K + 3, packed, nbytes)
+        torch.cuda.synchronize()
+        # layout: fragment (panel, slice, plane) at 1024 * ((panel * nslices + slice) * 2 + plane),
+        # byte 16 * (32 * ((k % 32) / 16) + j % 32) + k % 16 inside it
+        raw = packed.cpu().numpy()
+        frag = raw[:2 * Kp * Np].reshape(Np // 32, Kp // 32, 2, 2, 32, 16)      # panel, slice, plane, k-half, column, byte
+        planes = frag.transpose(2, 0, 4, 1, 3, 5).reshape(2, Np, Kp)            # plane, column, k
+        Bpad = np.zeros((Np, Kp), dtype=np.int16); Bpad[:N, :K] = B
+        hi = ((Bpad.astype(np.int32) >> 8) & 255).astype(np.uint8)
+        lo = ((Bpad.astype(np.int32) & 255) ^ 0x80).astype(np.uint8)
+        mask = np.zeros((Np, Kp), dtype=bool); mask[:N, :K] = True
+        assert np.array_equal(planes[0], np.where(mask, hi, 0)) and np.array_equal(planes[1], np.where(mask, lo, 0))
+        colsum = raw[2 * Kp * Np:].view(np.int32)
+        assert np.array_equal(colsum[:N], (B.astype(np.int64) - 128).sum(1).astype(np.int32)) and not colsum[N:].any()
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        for cap in (0, 2):
+            ng.ngemm_set_max_workgroups(rt.ctx, cap)
+            Cd = torch.full((M + 1, N + 2), -3, dtype=torch.int32, device="cuda")
+            ng.ngemm_run_s16s16s32(rt.ctx, M, Ad, lda, za, h, zb, Cd, N + 2, ws, wsb)
+            torch.cuda.synchronize()
+            got = Cd.cpu().numpy()
+            assert np.array_equal(got[:M, :N], want), (M, N, K, cap, np.count_nonzero(got[:M, :N] != want))
+            assert (got[M:, :] == -3).all() and (got[:, N:] == -3).all()
+        ng.ngemm_set_max_workgroups(rt.ctx, 0)
+        # refusals: a 16-bit pack in an 8-bit call, zero-points out of range, unaligned rows
+        for call, args in ((ng.ngemm_run_u8s8s32, (rt.ctx, M, Ad, lda, 0, h, 0, Cd, N + 2, ws, wsb)),
+                           (ng.ngemm_run_s16s16s32, (rt.ctx, M, Ad, lda, 32768, h, 0, Cd, N + 2, ws, wsb)),
+                           (ng.ngemm_run_s16s16s32, (rt.ctx, M, Ad, lda, 0, h, -32769, Cd, N + 2, ws, wsb)),
+                           (ng.ngemm_run_s16s16s32, (rt.ctx, M, Ad, lda + 1, 0, h, 0, Cd, N + 2, ws, wsb))):
+            try:
+                call(*args)
+                assert False
+            except ng.NgemmError as e:
+                assert e.status == ng.NGEMM_ERR_INVALID_ARG
+        ng.ngemm_packed_b_free(h)
+    # an 8-bit pack is refused by the 16-bit call
+    h8, _pk = rt.pack(rng.integers(-128, 128, size=(N, K), dtype=np.int8))
+    try:
+        ng.ngemm_run_s16s16s32(rt.ctx, M, Ad, lda, 0, h8, 0, Cd, N + 2, ws, wsb)
+        assert False
+    except ng.NgemmError as e:
+        assert e.status == ng.NGEMM_ERR_INVALID_ARG
+    ng.ngemm_packed_b_free(h8)
+
+
 def test_online_pack_path(rt, oracle):
     """Both operands as plain inputs.  Unaligned rows or M <= 32: B is packed into the workspace
     inside the call.  Rows of A and B 16-byte aligned and M > 32: the tile kernels read B from
