@@ -168,7 +168,7 @@ def main():
         "dtype": "int8 x int8 -> int32 (u8 operand shifted to s8)",
         "data": "synthetic (seeded uniform u8 / s8)",
         "config": {"workload": "large_square_%d" % n, "M": n, "N": n, "K": n, "za": 0, "zb": 0,
-                   "kernel": "gemm_tile_dma_kernel<256,256,2,2,4>", "sampled_outputs_match_oracle": sample_ok},
+                   "kernel": "gemm_tile_x64_kernel (256 x 256 tiles, v_mfma_i32_16x16x64_i8)", "sampled_outputs_match_oracle": sample_ok},
         "roofline": {"bound": "mfma", "achieved": round(kern_tops, 2), "peak": INT8_MFMA_PEAK_TOPS,
                      "unit": "TOP/s", "frac": round(kern_tops / INT8_MFMA_PEAK_TOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES if n == 8192 else None, "kernel_ms": round(kern_ms, 5),

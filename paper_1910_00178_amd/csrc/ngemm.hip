@@ -345,8 +345,18 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
                        : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_256:
-        e = dma_ok ? launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, a.requant, num_cus, st)
-                   : launch_tile<256, 256, 2, 2, BK256>(p, a.requant, st);
+        if (dma_ok && !a.requant && (uint64_t)a.lda * 16 < (1ull << 32)) {
+            // int32 output: the 16 x 16 x 64 form of the matrix instruction
+            p.tiles_m = (p.M + 255) / 256;
+            p.tiles_n = (p.N + 255) / 256;
+            const int ntiles = p.tiles_m * p.tiles_n;
+            hipLaunchKernelGGL(gemm_tile_x64_kernel, dim3((unsigned)(ntiles < num_cus ? ntiles : num_cus)), dim3(256),
+                               X64Cfg::kLdsBytes, st, p);
+            e = hipGetLastError();
+        } else {
+            e = dma_ok ? launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, a.requant, num_cus, st)
+                       : launch_tile<256, 256, 2, 2, BK256>(p, a.requant, st);
+        }
         break;
     default: return NGEMM_ERR_INVALID_ARG;
     }
@@ -410,6 +420,8 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
             allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
             allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep<1>() != hipSuccess || allow_big_lds_deep<2>() != hipSuccess ||
+            hipFuncSetAttribute((const void *)gemm_tile_x64_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                X64Cfg::kLdsBytes) != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_s16_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S16Cfg::kLdsBytes) != hipSuccess) {
             delete c;

@@ -972,6 +972,260 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
     }
 }
 
+// compile-time integer as a function argument (register-set selectors of the kernels below)
+template <int V>
+struct IntC {
+    static constexpr int value = V;
+};
+
+// ---- 256 x 256 tiles on the 16 x 16 x 64 matrix instruction ------------------------------------
+// The same tiling, ring and copies as gemm_tile_dma_kernel<256,256,2,2,4>, for int32 output.  On
+// operands that change with every instruction the chip is limited by power, not by issue slots, and
+// v_mfma_i32_16x16x64_i8 does the same work for less of it than the 32 x 32 x 32 form (a quarter of
+// the accumulator traffic per instruction, half per multiply-add): a register-only loop of the one
+// sustains 3.9 POP/s on random data, of the other 3.5.  A stage of 64 bytes of K is exactly one such
+// instruction deep:
+//   A operand of block i (16 rows): lane l holds row l%16, bytes 16*(l/16) .. +15 of the stage; in the
+//     block layout of the copies that is one conflict-free 16-byte read per lane from one 1 KiB block;
+//   B operand of block j (16 columns): lane l holds column l%16, the same bytes; in the packed layout
+//     (32-column panels, two 32-byte k-halves per stage) that is fragment l/32 of the panel, lane slot
+//     32*((l/16)%2) + 16*(j%2) + l%16: each group of 16 lanes reads 256 contiguous bytes.
+// With the packed operand first, lane l of the result holds, for row l%16 of A's block, the four
+// consecutive columns 4*(l/16) .. +3 of B's block.
+// A wavefront owns 128 x 128 of C as 8 x 8 blocks (256 accumulator registers) and keeps the sixteen
+// operand fragments of two stages in registers: those of stage it+1 are read from LDS while the 64
+// matrix ops of stage it run.
+struct X64Cfg {
+    static constexpr int NSTAGE = 4;
+    static constexpr int kABytes = 256 * 64;
+    static constexpr int kStageBytes = 2 * kABytes;
+    static constexpr int kLoadsPerStage = 8;               // per lane: 4 blocks of A, 4 fragments of B
+    static constexpr int kPatchRow = 128 * 4 + 16;         // epilogue patch: 16 rows of 128 int32, padded
+    static constexpr int kPatchBytes = 16 * kPatchRow;     // per wavefront
+    static constexpr int kLdsBytes = NSTAGE * kStageBytes;
+    static_assert(4 * kPatchBytes <= kLdsBytes, "epilogue patches fit the ring");
+};
+
+__global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
+{
+    using Cfg = X64Cfg;
+    constexpr int NSTAGE = Cfg::NSTAGE, LPS = Cfg::kLoadsPerStage;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int nslices = p.Kp / 32;
+    const int nfull = p.K / 64;
+    const bool has_tail = nfull * 64 < p.Kp;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int gsz = gridDim.x, w = blockIdx.x;
+
+    const int t16 = lane >> 2;                           // loader: row of the 16-row block
+    const int a_chunk = ((lane & 3) - (t16 >> 2)) & 3;
+    const int ft = lane & 15, fc = lane >> 4;            // fragments: row / column of the block, 16-byte chunk
+    const int a_off = (wm * 8) * 1024 + (4 * ft + ((fc + (ft >> 2)) & 3)) * 16;
+    const int b_off = Cfg::kABytes + (wn * 8 + (fc >> 1)) * 1024 + (32 * (fc & 1) + ft) * 16;
+
+    for (int tile = w; tile < ntiles; tile += gsz) {
+        int tm, tn;
+        tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
+        const int m0 = tm * 256, n0 = tn * 256;
+
+        // Loader addresses as a wavefront-uniform base plus a 32-bit lane offset: the advance along K
+        // is then scalar arithmetic (the host checks that 16 rows of A span less than 4 GiB).
+        const uint8_t *a_base[4], *b_base[4];
+        uint32_t a_lane[4];
+        const uint32_t b_lane = (uint32_t)lane * 16u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int row0 = m0 + (wave + 4 * i) * 16;
+            row0 = row0 < p.M ? row0 : p.M - 1;          // rows past M: read a valid row, never stored
+            int grow = row0 + t16;
+            grow = grow < p.M ? grow : p.M - 1;
+            a_base[i] = p.A + (int64_t)row0 * p.lda;
+            a_lane[i] = (uint32_t)(grow - row0) * (uint32_t)p.lda + (uint32_t)a_chunk * 16u;
+            const int q = wave + 4 * i;                  // panel q / 2, k-half q % 2
+            int pnl = n0 / 32 + (q >> 1);
+            pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
+            b_base[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes;
+        }
+        auto dma_one = [&](int s, int d, int buf) {      // copy d (0..7) of stage s into ring buffer buf
+            const int g = s < nfull ? s : nfull - 1;     // past the end: a copy nobody reads
+            uint8_t *dst = lds + buf * Cfg::kStageBytes;
+            if (d < 4)
+                __builtin_amdgcn_global_load_lds((gptr_t)(a_base[d] + (int64_t)g * 64 + a_lane[d]),
+                                                 (lptr_t)(dst + (wave + 4 * d) * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((gptr_t)(b_base[d - 4] + (int64_t)g * (2 * kFragBytes) + b_lane),
+                                                 (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (d - 4)) * 1024), 16, 0, 0);
+        };
+
+        // B fragments of a stage serve all 64 of its matrix ops: two register sets, the one of stage
+        // it+1 filled while stage it runs.  An A fragment serves eight: a rolling window of four.
+        v4i fb[2][8], fa[4];
+        auto read_b = [&](auto set, int buf, int j) {
+            constexpr int S = decltype(set)::value;
+            fb[S][j] = *(const v4i *)(lds + buf * Cfg::kStageBytes + b_off + (j >> 1) * 2048 + (j & 1) * 256);
+        };
+        auto read_a = [&](int buf, int i) {
+            fa[i & 3] = *(const v4i *)(lds + buf * Cfg::kStageBytes + a_off + i * 1024);
+        };
+
+        v4i acc[8][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+        // matrix op m (0..63) of a stage: row block m / 8, column block m % 8
+        auto mma = [&](auto set, int m) {
+            constexpr int S = decltype(set)::value;
+            const int i = m >> 3, j = m & 7;
+            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[S][j], fa[i & 3], acc[i][j], 0, 0, 0);
+        };
+        auto shift_a = [&](int i) { fa[i & 3] = shift_u8_to_s8(fa[i & 3], p.a_xor); };   // u8 -> s8
+        auto shift_a_word = [&](int i, int wd) { fa[i & 3][wd] ^= (int)p.a_xor; };      // one dword of it
+
+        if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
+
+        if (nfull > 0) {
+#pragma unroll
+            for (int s = 0; s < NSTAGE - 1; ++s)
+#pragma unroll
+                for (int d = 0; d < LPS; ++d) dma_one(s, d, s);
+            wait_vmcnt<(NSTAGE - 2) * LPS>();            // stage 0 has landed (this wavefront's part)
+            __builtin_amdgcn_s_barrier();
+#pragma unroll
+            for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, 0, j);
+            read_a(0, 0);
+            read_a(0, 1);
+            shift_a(0);
+            __builtin_amdgcn_sched_barrier(0);
+
+            // One stage: 64 matrix ops, row block by row block (eight ops each, gaps j = 0..7).
+            //   j = 4..7 of row i: the u8 -> s8 shift of A fragment i+1, one dword per gap (a gap has
+            //     room for about three vector instructions before the next matrix op is due).  The
+            //     compiler waits for every outstanding LDS read at j = 4, so the reads follow it and
+            //     have until the next row's shift to return:
+            //   j = 5 of row i: the read of A fragment i+2 (rows 6, 7: fragments 0, 1 of stage it+1);
+            //   j = 6, 7 of rows 2..5: the B fragments of stage it+1 into the other register set;
+            //   j = 0..3 of rows 3, 4: the copies of stage it+NSTAGE-1.
+            // Before row 2: wait for this wavefront's copies of stage it+1, barrier (=> stage it+1 is
+            // complete for everybody, and everybody's reads of stage it-1 were consumed a stage ago, so
+            // its buffer is free).
+            auto body = [&](auto set, auto other, int it) {
+                const int buf_c = it % NSTAGE, buf_n = (it + 1) % NSTAGE, buf_f = (it + NSTAGE - 1) % NSTAGE;
+#pragma unroll
+                for (int m = 0; m < 64; ++m) {
+                    const int i = m >> 3, j = m & 7;
+                    if (m == 16) {
+                        wait_vmcnt<(NSTAGE - 3) * LPS>();
+                        __builtin_amdgcn_s_barrier();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (j >= 4) shift_a_word(i + 1, j - 4);
+                    if (j == 5) {
+                        if (i < 6) read_a(buf_c, i + 2);
+                        else read_a(buf_n, i - 6);
+                    }
+                    if (j >= 6 && i >= 2 && i < 6) read_b(other, buf_n, 2 * (i - 2) + (j - 6));
+                    if (j < 4 && (i == 3 || i == 4)) dma_one(it + NSTAGE - 1, 4 * (i - 3) + j, buf_f);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma(set, m);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            int it = 0;
+            for (; it + 1 < nfull; it += 2) {
+                body(IntC<0>{}, IntC<1>{}, it);
+                body(IntC<1>{}, IntC<0>{}, it + 1);
+            }
+            if (it < nfull) body(IntC<0>{}, IntC<1>{}, it);
+            wait_vmcnt<0>();                             // drain the copies nobody reads
+        }
+
+        // K tail: the last, partial stage.  Guarded register loads into buffer 0, same layout.
+        if (has_tail) {
+            const int kbase = nfull * 64;
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int q = wave + 4 * i;
+                const int valid = p.K - (kbase + a_chunk * 16);
+                const uint8_t *src = a_base[i] + a_lane[i] + kbase;
+                v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
+                *(v4i *)(lds + q * 1024 + lane * 16) = v;
+                v4i z = {0, 0, 0, 0};
+                if (nfull * 2 + (q & 1) < nslices) z = *(const v4i *)(b_base[i] + b_lane + (int64_t)nfull * (2 * kFragBytes));
+                *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) = z;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, 0, j);
+#pragma unroll
+            for (int m = 0; m < 64; ++m) {
+                if ((m & 7) == 0) {
+                    read_a(0, m >> 3);
+                    shift_a(m >> 3);
+                }
+                mma(IntC<0>{}, m);
+            }
+        }
+
+        __syncthreads();                                 // every wavefront is done with the stage buffers
+
+        // Epilogue.  Per 16-row block: row terms added, the 16 x 128 block written to an LDS patch as
+        // it lies in the accumulators, read back two rows per instruction, column terms added, stored
+        // as full 512-byte row pieces.
+        uint8_t *patch = lds + wave * Cfg::kPatchBytes;
+        const int cg = lane & 31, r2 = lane >> 5;
+        const int bcol = n0 + wn * 128 + 4 * cg;
+        uint4 ct = {0u, 0u, 0u, 0u};
+        if (bcol < p.N) {
+            const int4 cs = *(const int4 *)(p.colsum + bcol);        // colsum is padded to 32 columns
+            ct.x = p.za_term * (uint32_t)cs.x; ct.y = p.za_term * (uint32_t)cs.y;
+            ct.z = p.za_term * (uint32_t)cs.z; ct.w = p.za_term * (uint32_t)cs.w;
+        }
+        const bool interior = m0 + (wm + 1) * 128 <= p.M && n0 + (wn + 1) * 128 <= p.N;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int brow0 = m0 + wm * 128 + 16 * i;
+            const int row = brow0 + ft;
+            uint32_t row_term = p.kconst;
+            if (p.rowsum && row < p.M) row_term -= p.zb * (uint32_t)p.rowsum[row];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                v4i v = acc[i][j];
+                v.x = (int)((uint32_t)v.x + row_term); v.y = (int)((uint32_t)v.y + row_term);
+                v.z = (int)((uint32_t)v.z + row_term); v.w = (int)((uint32_t)v.w + row_term);
+                *(v4i *)(patch + ft * Cfg::kPatchRow + (16 * j + 4 * fc) * 4) = v;
+            }
+            v4i o[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) o[q] = *(const v4i *)(patch + (2 * q + r2) * Cfg::kPatchRow + cg * 16);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                v4i v = o[q];
+                v.x = (int)((uint32_t)v.x + ct.x); v.y = (int)((uint32_t)v.y + ct.y);
+                v.z = (int)((uint32_t)v.z + ct.z); v.w = (int)((uint32_t)v.w + ct.w);
+                const int orow = brow0 + 2 * q + r2;
+                int32_t *dst = (int32_t *)p.C + (int64_t)orow * p.ldc + bcol;
+                if (interior) {
+                    __builtin_memcpy(dst, &v, 16);       // 4-byte aligned is enough
+                } else if (orow < p.M && bcol < p.N) {
+                    if (bcol + 3 < p.N) {
+                        __builtin_memcpy(dst, &v, 16);
+                    } else {
+                        dst[0] = v.x;
+                        if (bcol + 1 < p.N) dst[1] = v.y;
+                        if (bcol + 2 < p.N) dst[2] = v.z;
+                    }
+                }
+            }
+        }
+    }
+}
+
 // ---- small tiles with a long pipeline ---------------------------------------------------------
 // For outputs with at most one 64 x 64 (T = 1) or 128 x 128 (T = 2) tile per compute unit.  There
 // a workgroup is alone on its compute unit, one wavefront per SIMD, and the kernel above spends
@@ -994,11 +1248,6 @@ struct DeepCfg {
     static_assert(T == 1 || T == 2, "wavefront tile of 32 x 32 or 64 x 64");
     static_assert(NSTAGE >= 3 && NSTAGE * kStageBytes <= 160 * 1024, "ring depth");
     static_assert((NSTAGE - 2) * kLoadsPerStage <= 63, "vmcnt range");
-};
-
-template <int V>
-struct IntC {
-    static constexpr int value = V;
 };
 
 template <int T, int SUB, int NSTAGE, bool REQUANT>
