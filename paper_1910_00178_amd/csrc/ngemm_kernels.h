@@ -985,11 +985,12 @@ struct IntC {
 // the accumulator traffic per instruction, half per multiply-add): a register-only loop of the one
 // sustains 3.9 POP/s on random data, of the other 3.5.  A stage of 64 bytes of K is exactly one such
 // instruction deep:
-//   A operand of block i (16 rows): lane l holds row l%16, bytes 16*(l/16) .. +15 of the stage; in the
-//     block layout of the copies that is one conflict-free 16-byte read per lane from one 1 KiB block;
-//   B operand of block j (16 columns): lane l holds column l%16, the same bytes; in the packed layout
-//     (32-column panels, two 32-byte k-halves per stage) that is fragment l/32 of the panel, lane slot
-//     32*((l/16)%2) + 16*(j%2) + l%16: each group of 16 lanes reads 256 contiguous bytes.
+//   A operand of block i (16 rows): lane l holds row l%16, bytes 16*(l/16) .. +15 of the stage: one
+//     16-byte read per lane from one 1 KiB block of the copies (with its own chunk rotation, below);
+//   B operand of block j (16 columns): lane l holds column l%16, the same bytes; they lie in the two
+//     packed fragments (32-byte k-halves) of the block's panel.  A copy's lanes may fetch any 16 bytes
+//     each, so the chunks of a fragment are permuted on the way into LDS (still one contiguous KiB
+//     per copy): the two 16-byte halves a lane pair l, l+16 needs lie 256 bytes apart.
 // With the packed operand first, lane l of the result holds, for row l%16 of A's block, the four
 // consecutive columns 4*(l/16) .. +3 of B's block.
 // A wavefront owns 128 x 128 of C as 8 x 8 blocks (256 accumulator registers) and keeps the sixteen
@@ -1022,10 +1023,14 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
     const int gsz = gridDim.x, w = blockIdx.x;
 
     const int t16 = lane >> 2;                           // loader: row of the 16-row block
-    const int a_chunk = ((lane & 3) - (t16 >> 2)) & 3;
+    const int a_chunk = ((lane & 3) - (t16 >> 1)) & 3;   // chunks of row t rotated by t/2: see a_off
     const int ft = lane & 15, fc = lane >> 4;            // fragments: row / column of the block, 16-byte chunk
-    const int a_off = (wm * 8) * 1024 + (4 * ft + ((fc + (ft >> 2)) & 3)) * 16;
-    const int b_off = Cfg::kABytes + (wn * 8 + (fc >> 1)) * 1024 + (32 * (fc & 1) + ft) * 16;
+    // A block in LDS: row t at 64 * t, its four chunks rotated by t / 2.  (Measured with the bank
+    // conflict counter: this read pattern -- lane l takes row l % 16, chunk l / 16 -- is free of
+    // conflicts with a rotation by t / 2 and takes twice as long with the rotation by t / 4 that
+    // serves the 32 x 32 x 32 kernels' pattern.)
+    const int a_off = (wm * 8) * 1024 + (4 * ft + ((fc + (ft >> 1)) & 3)) * 16;
+    const int b_off = Cfg::kABytes + (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16;
 
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
@@ -1036,7 +1041,10 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
         // is then scalar arithmetic (the host checks that 16 rows of A span less than 4 GiB).
         const uint8_t *a_base[4], *b_base[4];
         uint32_t a_lane[4];
-        const uint32_t b_lane = (uint32_t)lane * 16u;
+        // A B fragment (32 columns x 32 bytes of K, 1 KiB) is copied with its 16-byte chunks permuted:
+        // LDS slot 16 * (2 * h + khalf) + t takes column 16 * h + t, k-half khalf (packed slot
+        // 32 * khalf + 16 * h + t), so that the two k-halves of a 16-column block lie side by side
+        const uint32_t b_lane = (uint32_t)((32 * ((lane >> 4) & 1) + 16 * (lane >> 5) + (lane & 15)) * 16);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             int row0 = m0 + (wave + 4 * i) * 16;
@@ -1066,7 +1074,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
         v4i fb[2][8], fa[4];
         auto read_b = [&](auto set, int buf, int j) {
             constexpr int S = decltype(set)::value;
-            fb[S][j] = *(const v4i *)(lds + buf * Cfg::kStageBytes + b_off + (j >> 1) * 2048 + (j & 1) * 256);
+            fb[S][j] = *(const v4i *)(lds + buf * Cfg::kStageBytes + b_off + (j >> 1) * 2048 + (j & 1) * 512);
         };
         auto read_a = [&](int buf, int i) {
             fa[i & 3] = *(const v4i *)(lds + buf * Cfg::kStageBytes + a_off + i * 1024);
