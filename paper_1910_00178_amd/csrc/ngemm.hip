@@ -350,8 +350,8 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
             p.tiles_m = (p.M + 255) / 256;
             p.tiles_n = (p.N + 255) / 256;
             const int ntiles = p.tiles_m * p.tiles_n;
-            hipLaunchKernelGGL(gemm_tile_x64_kernel, dim3((unsigned)(ntiles < num_cus ? ntiles : num_cus)), dim3(256),
-                               X64Cfg::kLdsBytes, st, p);
+            hipLaunchKernelGGL(gemm_tile_x64_kernel<false>, dim3((unsigned)(ntiles < num_cus ? ntiles : num_cus)),
+                               dim3(256), X64Cfg::kLdsBytes, st, p, RawB{nullptr, 0});
             e = hipGetLastError();
         } else {
             e = dma_ok ? launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, a.requant, num_cus, st)
@@ -420,7 +420,9 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
             allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
             allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep<1>() != hipSuccess || allow_big_lds_deep<2>() != hipSuccess ||
-            hipFuncSetAttribute((const void *)gemm_tile_x64_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+            hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                X64Cfg::kLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 X64Cfg::kLdsBytes) != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_s16_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S16Cfg::kLdsBytes) != hipSuccess) {
@@ -825,7 +827,14 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
         hipError_t e;
         if (kernel == NGEMM_KERNEL_TILE_64) e = launch_tile_dma<64, 64, 2, 2>(p, false, budget, st, &rawb);
         else if (kernel == NGEMM_KERNEL_TILE_128) e = launch_tile_dma<128, 128, 2, 2>(p, false, budget, st, &rawb);
-        else e = launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, false, budget, st, &rawb);
+        else if (((uint64_t)lda | (uint64_t)ldb) * 16 < (1ull << 32)) {
+            p.tiles_m = (int)((M + 255) / 256);
+            p.tiles_n = (int)((N + 255) / 256);
+            const int ntiles = p.tiles_m * p.tiles_n;
+            hipLaunchKernelGGL(gemm_tile_x64_kernel<true>, dim3((unsigned)(ntiles < budget ? ntiles : budget)), dim3(256),
+                               X64Cfg::kLdsBytes, st, p, rawb);
+            e = hipGetLastError();
+        } else e = launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, false, budget, st, &rawb);
         return e == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
     }
     const size_t pb = (size_t)round_up((int64_t)ngemm_packed_b_bytes(K, N), 256);

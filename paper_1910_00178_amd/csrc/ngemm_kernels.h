@@ -1007,7 +1007,10 @@ struct X64Cfg {
     static_assert(4 * kPatchBytes <= kLdsBytes, "epilogue patches fit the ring");
 };
 
-__global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
+// BRAW: B is the caller's plain [N x K] int8 storage (struct RawB); its tiles are then copied and read
+// exactly as A's.
+template <bool BRAW>
+__global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, const RawB rawb)
 {
     using Cfg = X64Cfg;
     constexpr int NSTAGE = Cfg::NSTAGE, LPS = Cfg::kLoadsPerStage;
@@ -1030,7 +1033,8 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
     // conflicts with a rotation by t / 2 and takes twice as long with the rotation by t / 4 that
     // serves the 32 x 32 x 32 kernels' pattern.)
     const int a_off = (wm * 8) * 1024 + (4 * ft + ((fc + (ft >> 1)) & 3)) * 16;
-    const int b_off = Cfg::kABytes + (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16;
+    const int b_off = BRAW ? Cfg::kABytes + a_off + (wn - wm) * 8192
+                           : Cfg::kABytes + (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16;
 
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
@@ -1040,7 +1044,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
         // Loader addresses as a wavefront-uniform base plus a 32-bit lane offset: the advance along K
         // is then scalar arithmetic (the host checks that 16 rows of A span less than 4 GiB).
         const uint8_t *a_base[4], *b_base[4];
-        uint32_t a_lane[4];
+        uint32_t a_lane[4], b_lane_raw[4];
         // A B fragment (32 columns x 32 bytes of K, 1 KiB) is copied with its 16-byte chunks permuted:
         // LDS slot 16 * (2 * h + khalf) + t takes column 16 * h + t, k-half khalf (packed slot
         // 32 * khalf + 16 * h + t), so that the two k-halves of a 16-column block lie side by side
@@ -1053,10 +1057,20 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
             grow = grow < p.M ? grow : p.M - 1;
             a_base[i] = p.A + (int64_t)row0 * p.lda;
             a_lane[i] = (uint32_t)(grow - row0) * (uint32_t)p.lda + (uint32_t)a_chunk * 16u;
-            const int q = wave + 4 * i;                  // panel q / 2, k-half q % 2
-            int pnl = n0 / 32 + (q >> 1);
-            pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
-            b_base[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes;
+            const int q = wave + 4 * i;                  // panel q / 2, k-half q % 2 (BRAW: 16-column block q)
+            if (BRAW) {
+                int col0 = n0 + q * 16;
+                col0 = col0 < p.N ? col0 : p.N - 1;      // columns past N: read a valid one, never stored
+                int gcol = col0 + t16;
+                gcol = gcol < p.N ? gcol : p.N - 1;
+                b_base[i] = rawb.B + (int64_t)col0 * rawb.ldb;
+                b_lane_raw[i] = (uint32_t)(gcol - col0) * (uint32_t)rawb.ldb + (uint32_t)a_chunk * 16u;
+            } else {
+                int pnl = n0 / 32 + (q >> 1);
+                pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
+                b_base[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes;
+                b_lane_raw[i] = 0;
+            }
         }
         auto dma_one = [&](int s, int d, int buf) {      // copy d (0..7) of stage s into ring buffer buf
             const int g = s < nfull ? s : nfull - 1;     // past the end: a copy nobody reads
@@ -1065,8 +1079,10 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
                 __builtin_amdgcn_global_load_lds((gptr_t)(a_base[d] + (int64_t)g * 64 + a_lane[d]),
                                                  (lptr_t)(dst + (wave + 4 * d) * 1024), 16, 0, 0);
             else
-                __builtin_amdgcn_global_load_lds((gptr_t)(b_base[d - 4] + (int64_t)g * (2 * kFragBytes) + b_lane),
-                                                 (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (d - 4)) * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(
+                    (gptr_t)(BRAW ? b_base[d - 4] + (int64_t)g * 64 + b_lane_raw[d - 4]
+                                  : b_base[d - 4] + (int64_t)g * (2 * kFragBytes) + b_lane),
+                    (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (d - 4)) * 1024), 16, 0, 0);
         };
 
         // B fragments of a stage serve all 64 of its matrix ops: two register sets, the one of stage
@@ -1074,7 +1090,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
         v4i fb[2][8], fa[4];
         auto read_b = [&](auto set, int buf, int j) {
             constexpr int S = decltype(set)::value;
-            fb[S][j] = *(const v4i *)(lds + buf * Cfg::kStageBytes + b_off + (j >> 1) * 2048 + (j & 1) * 512);
+            fb[S][j] = *(const v4i *)(lds + buf * Cfg::kStageBytes + b_off + (BRAW ? j * 1024 : (j >> 1) * 2048 + (j & 1) * 512));
         };
         auto read_a = [&](int buf, int i) {
             fa[i & 3] = *(const v4i *)(lds + buf * Cfg::kStageBytes + a_off + i * 1024);
@@ -1164,7 +1180,12 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p)
                 v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
                 *(v4i *)(lds + q * 1024 + lane * 16) = v;
                 v4i z = {0, 0, 0, 0};
-                if (nfull * 2 + (q & 1) < nslices) z = *(const v4i *)(b_base[i] + b_lane + (int64_t)nfull * (2 * kFragBytes));
+                if (BRAW) {
+                    const uint8_t *bs = b_base[i] + b_lane_raw[i] + kbase;
+                    z = valid >= 16 ? load16_any(bs) : load16_partial(bs, valid < 0 ? 0 : valid);
+                } else if (nfull * 2 + (q & 1) < nslices) {
+                    z = *(const v4i *)(b_base[i] + b_lane + (int64_t)nfull * (2 * kFragBytes));
+                }
                 *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) = z;
             }
             __syncthreads();
