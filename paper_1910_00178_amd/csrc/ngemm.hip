@@ -207,9 +207,9 @@ hipError_t launch_skinny(const GemmParams &p, bool requant, int num_cus, hipStre
 }
 
 // Shape heuristic: the 256 x 256 configuration when it fills at least three quarters of the
-// compute units, the 128 x 128 one when every unit still gets two workgroups, else 64 x 64
-// (measured on 1024 x {768, 3072} outputs: the smallest tile wins as long as the larger ones
-// leave units idle).
+// compute units, the 128 x 128 one when every unit still gets a workgroup, else 64 x 64
+// (measured on 18 shapes from 16 x 512 x 512 to 4096^3: the smallest tile wins as long as the
+// larger ones leave units idle; ngemm_tune_u8s8s32 settles the borderline cases by measurement).
 int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N)
 {
     if (M <= kSkinnyMaxM) return NGEMM_KERNEL_SKINNY;
@@ -893,8 +893,14 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
             else if (which == 1)
                 hipLaunchKernelGGL((gemm_group_tile_kernel<64, 64, 2, 2, 64>), dim3(grid), dim3(256),
                                    (size_t)TCfg::kLdsBytes, st, gp);
-            else
-                hipLaunchKernelGGL(gemm_group_skinny_kernel, dim3(grid), dim3(512), (size_t)(8 * 16 * 64 * 4), st, gp);
+            else {
+                // wavefronts per panel: eight hide latency when the panels are few; with several
+                // panels per compute unit anyway, fewer wavefronts with more fragments each spend
+                // less on the final sum across wavefronts
+                const unsigned cus = (unsigned)(ctx->num_cus > 0 ? ctx->num_cus : 256);
+                const unsigned nw = grid >= 8 * cus ? 2 : (grid >= 4 * cus ? 4 : 8);
+                hipLaunchKernelGGL(gemm_group_skinny_kernel, dim3(grid), dim3(64 * nw), (size_t)(nw * 16 * 64 * 4), st, gp);
+            }
         }
         gp.count = 0;
         gp.unit_start[0] = 0;
