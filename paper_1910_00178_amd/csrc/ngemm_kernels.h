@@ -1036,53 +1036,49 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     const int b_off = BRAW ? Cfg::kABytes + a_off + (wn - wm) * 8192
                            : Cfg::kABytes + (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16;
 
+    // raw buffer descriptors over the operands (no bounds: every offset used below lies inside)
+    const uint8_t *b_mem = BRAW ? rawb.B : p.Bp;
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void *)p.A, (short)0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)b_mem, (short)0, -1, 0x00020000);
+
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
         tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
         const int m0 = tm * 256, n0 = tn * 256;
 
-        // Loader addresses as a wavefront-uniform base plus a 32-bit lane offset: the advance along K
-        // is then scalar arithmetic (the host checks that 16 rows of A span less than 4 GiB).
-        const uint8_t *a_base[4], *b_base[4];
-        uint32_t a_lane[4], b_lane_raw[4];
+        // Loader addresses in buffer form: the matrix as base, a 32-bit lane offset, and the advance
+        // along K as a scalar offset, so that a copy costs no vector arithmetic (the host checks that
+        // both operands span less than 4 GiB).
+        uint32_t a_voff[4], b_voff[4];
         // A B fragment (32 columns x 32 bytes of K, 1 KiB) is copied with its 16-byte chunks permuted:
         // LDS slot 16 * (2 * h + khalf) + t takes column 16 * h + t, k-half khalf (packed slot
         // 32 * khalf + 16 * h + t), so that the two k-halves of a 16-column block lie side by side
         const uint32_t b_lane = (uint32_t)((32 * ((lane >> 4) & 1) + 16 * (lane >> 5) + (lane & 15)) * 16);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int row0 = m0 + (wave + 4 * i) * 16;
-            row0 = row0 < p.M ? row0 : p.M - 1;          // rows past M: read a valid row, never stored
-            int grow = row0 + t16;
-            grow = grow < p.M ? grow : p.M - 1;
-            a_base[i] = p.A + (int64_t)row0 * p.lda;
-            a_lane[i] = (uint32_t)(grow - row0) * (uint32_t)p.lda + (uint32_t)a_chunk * 16u;
+            int grow = m0 + (wave + 4 * i) * 16 + t16;
+            grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
+            a_voff[i] = (uint32_t)grow * (uint32_t)p.lda + (uint32_t)a_chunk * 16u;
             const int q = wave + 4 * i;                  // panel q / 2, k-half q % 2 (BRAW: 16-column block q)
             if (BRAW) {
-                int col0 = n0 + q * 16;
-                col0 = col0 < p.N ? col0 : p.N - 1;      // columns past N: read a valid one, never stored
-                int gcol = col0 + t16;
-                gcol = gcol < p.N ? gcol : p.N - 1;
-                b_base[i] = rawb.B + (int64_t)col0 * rawb.ldb;
-                b_lane_raw[i] = (uint32_t)(gcol - col0) * (uint32_t)rawb.ldb + (uint32_t)a_chunk * 16u;
+                int gcol = n0 + q * 16 + t16;
+                gcol = gcol < p.N ? gcol : p.N - 1;      // columns past N: read a valid one, never stored
+                b_voff[i] = (uint32_t)gcol * (uint32_t)rawb.ldb + (uint32_t)a_chunk * 16u;
             } else {
                 int pnl = n0 / 32 + (q >> 1);
                 pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
-                b_base[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes;
-                b_lane_raw[i] = 0;
+                b_voff[i] = ((uint32_t)pnl * (uint32_t)nslices + (uint32_t)(q & 1)) * (uint32_t)kFragBytes + b_lane;
             }
         }
         auto dma_one = [&](int s, int d, int buf) {      // copy d (0..7) of stage s into ring buffer buf
             const int g = s < nfull ? s : nfull - 1;     // past the end: a copy nobody reads
             uint8_t *dst = lds + buf * Cfg::kStageBytes;
             if (d < 4)
-                __builtin_amdgcn_global_load_lds((gptr_t)(a_base[d] + (int64_t)g * 64 + a_lane[d]),
-                                                 (lptr_t)(dst + (wave + 4 * d) * 1024), 16, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr_t)(dst + (wave + 4 * d) * 1024), 16, a_voff[d],
+                                                         g * 64, 0, 0);
             else
-                __builtin_amdgcn_global_load_lds(
-                    (gptr_t)(BRAW ? b_base[d - 4] + (int64_t)g * 64 + b_lane_raw[d - 4]
-                                  : b_base[d - 4] + (int64_t)g * (2 * kFragBytes) + b_lane),
-                    (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (d - 4)) * 1024), 16, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (d - 4)) * 1024),
+                                                         16, b_voff[d - 4], BRAW ? g * 64 : g * (2 * kFragBytes), 0, 0);
         };
 
         // B fragments of a stage serve all 64 of its matrix ops: two register sets, the one of stage
@@ -1176,15 +1172,15 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             for (int i = 0; i < 4; ++i) {
                 const int q = wave + 4 * i;
                 const int valid = p.K - (kbase + a_chunk * 16);
-                const uint8_t *src = a_base[i] + a_lane[i] + kbase;
+                const uint8_t *src = p.A + a_voff[i] + kbase;
                 v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
                 *(v4i *)(lds + q * 1024 + lane * 16) = v;
                 v4i z = {0, 0, 0, 0};
                 if (BRAW) {
-                    const uint8_t *bs = b_base[i] + b_lane_raw[i] + kbase;
+                    const uint8_t *bs = b_mem + b_voff[i] + kbase;
                     z = valid >= 16 ? load16_any(bs) : load16_partial(bs, valid < 0 ? 0 : valid);
                 } else if (nfull * 2 + (q & 1) < nslices) {
-                    z = *(const v4i *)(b_base[i] + b_lane + (int64_t)nfull * (2 * kFragBytes));
+                    z = *(const v4i *)(b_mem + b_voff[i] + (int64_t)nfull * (2 * kFragBytes));
                 }
                 *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) = z;
             }
