@@ -1129,7 +1129,9 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             //     have until the next row's shift to return:
             //   j = 5 of row i: the read of A fragment i+2 (rows 6, 7: fragments 0, 1 of stage it+1);
             //   j = 6, 7 of rows 2..5: the B fragments of stage it+1 into the other register set;
-            //   j = 0..3 of rows 3, 4: the copies of stage it+NSTAGE-1.
+            //   every sixth gap from the 17th on: one copy of stage it+NSTAGE-1 (eight copies in a row
+            //     from each of the four wavefronts fill the compute unit's memory pipe and hold the
+            //     wavefronts up at issue: spread out they cost 4 % less time).
             // Before row 2: wait for this wavefront's copies of stage it+1, barrier (=> stage it+1 is
             // complete for everybody, and everybody's reads of stage it-1 were consumed a stage ago, so
             // its buffer is free).
@@ -1149,7 +1151,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                         else read_a(buf_n, i - 6);
                     }
                     if (j >= 6 && i >= 2 && i < 6) read_b(other, buf_n, 2 * (i - 2) + (j - 6));
-                    if (j < 4 && (i == 3 || i == 4)) dma_one(it + NSTAGE - 1, 4 * (i - 3) + j, buf_f);
+                    if (m >= 17 && (m - 17) % 6 == 0 && (m - 17) / 6 < 8) dma_one(it + NSTAGE - 1, (m - 17) / 6, buf_f);
                     __builtin_amdgcn_sched_barrier(0);
                     mma(set, m);
                     __builtin_amdgcn_sched_barrier(0);
