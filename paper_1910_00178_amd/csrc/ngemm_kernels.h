@@ -1693,9 +1693,9 @@ __global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
                     if (m < 12) {
                         read_one(other, buf_n, 2 * (m - 8));
                         read_one(other, buf_n, 2 * (m - 8) + 1);
-                    } else {
-                        dma_one(it + NSTAGE - 1, m - 12, buf_f);
                     }
+                    if (m & 1) dma_one(it + NSTAGE - 1, (m - 9) >> 1, buf_f);   // copies every other gap
+
                     __builtin_amdgcn_sched_barrier(0);
                     mma(set, m);
                     __builtin_amdgcn_sched_barrier(0);
