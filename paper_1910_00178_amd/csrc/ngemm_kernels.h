@@ -4,8 +4,9 @@
 //  * phase 1 (multiply narrow operands, widen, one partial sum per output
 //    element held in its own SIMD lane) and phase 2 (accumulate partials
 //    straight into the result vector, no horizontal tree reduction) are one
-//    v_mfma_i32_32x32x32_i8: 1024 distinct C elements per wavefront, each
-//    accumulated in place over the K loop.
+//    matrix instruction -- v_mfma_i32_32x32x32_i8 (1024 distinct C elements per
+//    wavefront) or, in the large int32-output kernel, v_mfma_i32_16x16x64_i8
+//    (256 of them) -- each element accumulated in place over the K loop.
 //  * the packed operand's inner block (Sec. 3.1.1) is the 1 KiB fragment one
 //    MFMA consumes: lane l of the wavefront holds 16 consecutive k-values of
 //    column l%32, depth half l/32.
@@ -23,7 +24,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kFragBytes = 1024;   // 32 columns x 32 k-values
-constexpr int kBK = 64;            // K bytes staged per main-loop step (two fragments deep)
 
 struct GemmParams {
     const uint8_t *A;       // row-major u8
@@ -712,15 +712,6 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-}
-
-// vmcnt <= N and lgkmcnt == 0: this wavefront's older copies have landed in LDS and its own
-// LDS reads have returned.  Used right before a bare s_barrier in the direct-to-LDS kernel,
-// where a workgroup fence would also wait for the younger copies that must stay in flight.
-template <int N>
-__device__ __forceinline__ void wait_vmcnt_and_lds()
-{
-    __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
 }
 
 typedef const __attribute__((address_space(1))) void *gptr_t;
