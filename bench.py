@@ -362,6 +362,11 @@ def main():
         ms_uu = gpu_time_ms(lambda: ng.ngemm_run_u8u8s32(ctx, n, At, n, 0, hun, 128, Ct, n), 100, 100, torch)
         extras["other_integer_types_%d" % n] = {"s8s8s32_TOPS": round(ops / (ms_ss * 1e-3) / 1e12, 1),
                                                 "u8u8s32_TOPS": round(ops / (ms_uu * 1e-3) / 1e12, 1)}
+        # requantised u8 output on the headline shape (per-tensor scale)
+        C8t = torch.empty((n, n), dtype=torch.uint8, device="cuda")
+        ms_q = gpu_time_ms(lambda: ng.ngemm_run_u8s8u8_requant(ctx, n, At, n, 128, hsg, 0, 2.0e-4, 128, C8t, n), 100, 100, torch)
+        extras["other_integer_types_%d" % n]["u8s8u8_requant_TOPS"] = round(ops / (ms_q * 1e-3) / 1e12, 1)
+        del C8t
         ng.ngemm_packed_b_free(hsg)
         ng.ngemm_packed_b_free(hun)
         # 16-bit operands through byte planes (four 8-bit matrix ops per block)

@@ -98,11 +98,31 @@ __device__ __forceinline__ uint8_t requant_u8(int32_t c, float scale, int32_t zc
     float f = (float)c;
     float g = __fmul_rn(f, scale);
     float r = rintf(g);
-    r = fminf(fmaxf(r, -4294967296.0f), 4294967296.0f);   // keeps the clamp below exact, avoids cvt overflow
-    long long q = (long long)r + (long long)zc;
+    // q = r + zc exactly, without a float -> int64 conversion (|r| <= 2^61 here: |c| <= 2^31, scale <= 2^30).
+    // Inside the int32 range (which includes -2^31) r converts exactly and the sum is a 64-bit add.
+    // r > 2^31: r >= 2^31 + 256, so q >= 256 + zc + 2^31 >= 256 whatever zc is.  r == 2^31: q = 2^31 + zc,
+    // which lies in [0, 2^32).  r < -2^31: r <= -2^31 - 256, so q < 0 and q < zc.
+    const float lim = 2147483648.0f;
+    const float rc = fminf(fmaxf(r, -lim), 2147483520.0f);           // 2^31 - 128: the largest float below 2^31
+    long long q = (long long)(int)rc + (long long)zc;
+    if (r >= lim) q = (r == lim) ? (long long)((uint32_t)zc + 0x80000000u) : 256;
+    if (r < -lim) q = -4294967296LL;                                 // below 0 and below every zc
     if (relu && q < (long long)zc) q = zc;
     q = q < 0 ? 0 : (q > 255 ? 255 : q);
     return (uint8_t)q;
+}
+
+// The same value when |zc| < 2^23 (the caller checks; every practical zero-point), in binary32
+// throughout.  r beyond +-2^24 cannot land in [0, 255] after adding zc, nor on the other side of zc, so
+// it may be clamped there first; then |r + zc| < 2^24 + 2^23, where binary32 addition of two integers
+// is exact up to 2^24 and off by at most one beyond, far from 0, 255 and zc.
+__device__ __forceinline__ uint8_t requant_u8_small_zc(int32_t c, float scale, float zcf, int relu)
+{
+    float r = rintf(__fmul_rn((float)c, scale));
+    r = fminf(fmaxf(r, -16777216.0f), 16777216.0f);
+    float q = r + zcf;
+    if (relu) q = fmaxf(q, zcf);
+    return (uint8_t)(int)fminf(fmaxf(q, 0.0f), 255.0f);
 }
 
 // General (per-column capable) value of one requantised element from its shifted-form
@@ -322,7 +342,7 @@ __device__ __forceinline__ int xpose_off(int r, int c)
 template <int TN>
 constexpr int kXposeBytes = 32 * (TN * 128 + 16);      // per wavefront
 
-template <int TM, int TN, int BN, bool REQUANT>
+template <int TM, int TN, int BN, bool REQUANT, bool SMALLZC = false>
 __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[TM][TN], int m0, int n0, int wm,
                                               int wn, int lane, int tid, int nthreads, uint8_t *xpose,
                                               uint32_t *cterm_lds)
@@ -381,10 +401,18 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
                     uint8_t *dst = (uint8_t *)p.C + (int64_t)row * p.ldc + col;
                     const float4 sc = *(const float4 *)((const float *)cterm_lds + 2 * BN + lcol);
                     uint8_t b[4];
-                    b[0] = requant_u8(v[0], sc.x, p.zc, p.relu);
-                    b[1] = requant_u8(v[1], sc.y, p.zc, p.relu);
-                    b[2] = requant_u8(v[2], sc.z, p.zc, p.relu);
-                    b[3] = requant_u8(v[3], sc.w, p.zc, p.relu);
+                    if (SMALLZC) {
+                        const float zcf = (float)p.zc;
+                        b[0] = requant_u8_small_zc(v[0], sc.x, zcf, p.relu);
+                        b[1] = requant_u8_small_zc(v[1], sc.y, zcf, p.relu);
+                        b[2] = requant_u8_small_zc(v[2], sc.z, zcf, p.relu);
+                        b[3] = requant_u8_small_zc(v[3], sc.w, zcf, p.relu);
+                    } else {
+                        b[0] = requant_u8(v[0], sc.x, p.zc, p.relu);
+                        b[1] = requant_u8(v[1], sc.y, p.zc, p.relu);
+                        b[2] = requant_u8(v[2], sc.z, p.zc, p.relu);
+                        b[3] = requant_u8(v[3], sc.w, p.zc, p.relu);
+                    }
                     if (col + 3 < p.N && c_vec_ok) {
                         *(uint32_t *)dst = (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16) |
                                            ((uint32_t)b[3] << 24);
@@ -628,7 +656,12 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
     }
 
     __syncthreads();                                   // every wavefront is done with the stage buffers
-    tile_epilogue<TM, TN, BN, REQUANT>(p, acc, m0, n0, wm, wn, lane, tid, NT, lds + wave * kXposeBytes<TN>,
+    // every practical output zero-point takes the binary32 form of the requantising arithmetic
+    if (REQUANT && p.zc > -8388608 && p.zc < 8388608)
+        tile_epilogue<TM, TN, BN, REQUANT, true>(p, acc, m0, n0, wm, wn, lane, tid, NT, lds + wave * kXposeBytes<TN>,
+                                       (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>));
+    else
+        tile_epilogue<TM, TN, BN, REQUANT, false>(p, acc, m0, n0, wm, wn, lane, tid, NT, lds + wave * kXposeBytes<TN>,
                                        (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>));
 }
 
@@ -958,7 +991,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
         }
 
         __syncthreads();                               // every wavefront is done with the stage buffers
-        tile_epilogue<TM, TN, BN, REQUANT>(p, acc, m0, n0, wm, wn, lane, tid, Cfg::kThreads,
+        // every practical output zero-point takes the binary32 form of the requantising arithmetic
+        if (REQUANT && p.zc > -8388608 && p.zc < 8388608)
+            tile_epilogue<TM, TN, BN, REQUANT, true>(p, acc, m0, n0, wm, wn, lane, tid, Cfg::kThreads,
+                                           lds + wave * kXposeBytes<TN>, (uint32_t *)(lds + NW * kXposeBytes<TN>));
+        else
+            tile_epilogue<TM, TN, BN, REQUANT, false>(p, acc, m0, n0, wm, wn, lane, tid, Cfg::kThreads,
                                            lds + wave * kXposeBytes<TN>, (uint32_t *)(lds + NW * kXposeBytes<TN>));
     }
 }
@@ -1000,7 +1038,7 @@ struct X64Cfg {
 
 // BRAW: B is the caller's plain [N x K] int8 storage (struct RawB); its tiles are then copied and read
 // exactly as A's.
-template <bool BRAW>
+template <bool BRAW, bool REQUANT = false>
 __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, const RawB rawb)
 {
     using Cfg = X64Cfg;
@@ -1192,10 +1230,76 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 
         __syncthreads();                                 // every wavefront is done with the stage buffers
 
+        uint8_t *patch = lds + wave * Cfg::kPatchBytes;
+        if (REQUANT) {
+            // Requantising epilogue (per tensor or per column).  The three per-column arrays of the tile
+            // -- (128-za)*colsum + bias, zero-point of B, scale -- are staged in LDS behind the patches.
+            // A lane requantises its four consecutive columns of each block to four bytes, the 16 x 128
+            // byte block goes through the wavefront's patch and is stored as full 128-byte row pieces.
+            uint32_t *cterm = (uint32_t *)(lds + 4 * Cfg::kPatchBytes);
+            for (int c = tid; c < 256; c += 256) {
+                const int col = n0 + c;
+                const bool ok = col < p.N;
+                uint32_t cb = ok ? p.za_term * (uint32_t)p.colsum[col] : 0u;
+                if (ok && p.bias_vec) cb += (uint32_t)p.bias_vec[col];
+                cterm[c] = cb;
+                cterm[256 + c] = (ok && p.zb_vec) ? (uint32_t)p.zb_vec[col] : p.zb;
+                ((float *)cterm)[512 + c] = (ok && p.scale_vec) ? p.scale_vec[col] : p.scale;
+            }
+            __syncthreads();
+            constexpr int kRow8 = 128 + 16;              // byte patch: 16 rows of 128 bytes, padded
+            const int cg8 = lane & 7, r8 = lane >> 3;    // read-back: 8 lanes of 16 bytes per row, 8 rows per pass
+            const int bcol8 = n0 + wn * 128 + 16 * cg8;
+            const bool interior = m0 + (wm + 1) * 128 <= p.M && n0 + (wn + 1) * 128 <= p.N &&
+                                  ((((uintptr_t)p.C | (uintptr_t)p.ldc) & 15) == 0);
+            const bool small_zc = p.zc > -8388608 && p.zc < 8388608;   // uniform: picks the binary32 form
+            const float zcf = (float)p.zc;
+            auto requant_rows = [&](auto small) __attribute__((always_inline)) {
+            constexpr bool SMALL = decltype(small)::value != 0;
+            auto rq = [&](uint32_t v, float sc) -> uint32_t {
+                return SMALL ? requant_u8_small_zc((int32_t)v, sc, zcf, p.relu) : requant_u8((int32_t)v, sc, p.zc, p.relu);
+            };
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int brow0 = m0 + wm * 128 + 16 * i;
+                const int row = brow0 + ft;
+                // sum_k (A[i][k] - za), multiplied per column by that column's zero-point of B
+                const uint32_t rsum = ((p.rowsum && row < p.M) ? (uint32_t)p.rowsum[row] : 0u) + p.rconst;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int lcol = wn * 128 + 16 * j + 4 * fc;
+                    const uint4 cb = *(const uint4 *)(cterm + lcol);
+                    const uint4 zv = *(const uint4 *)(cterm + 256 + lcol);
+                    const float4 sc = *(const float4 *)((const float *)cterm + 512 + lcol);
+                    const v4i v = acc[i][j];
+                    const uint32_t b0 = rq((uint32_t)v.x + cb.x - zv.x * rsum, sc.x);
+                    const uint32_t b1 = rq((uint32_t)v.y + cb.y - zv.y * rsum, sc.y);
+                    const uint32_t b2 = rq((uint32_t)v.z + cb.z - zv.z * rsum, sc.z);
+                    const uint32_t b3 = rq((uint32_t)v.w + cb.w - zv.w * rsum, sc.w);
+                    *(uint32_t *)(patch + ft * kRow8 + 16 * j + 4 * fc) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+                }
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const v4i o = *(const v4i *)(patch + (8 * q + r8) * kRow8 + cg8 * 16);
+                    const int orow = brow0 + 8 * q + r8;
+                    uint8_t *dst = (uint8_t *)p.C + (int64_t)orow * p.ldc + bcol8;
+                    if (interior) {
+                        *(v4i *)dst = o;
+                    } else if (orow < p.M) {
+                        const uint8_t *ob = (const uint8_t *)&o;
+#pragma unroll
+                        for (int t = 0; t < 16; ++t)
+                            if (bcol8 + t < p.N) dst[t] = ob[t];
+                    }
+                }
+            }
+            };
+            if (small_zc) requant_rows(IntC<1>{});
+            else requant_rows(IntC<0>{});
+        } else {
         // Epilogue.  Per 16-row block: row terms added, the 16 x 128 block written to an LDS patch as
         // it lies in the accumulators, read back two rows per instruction, column terms added, stored
         // as full 512-byte row pieces.
-        uint8_t *patch = lds + wave * Cfg::kPatchBytes;
         const int cg = lane & 31, r2 = lane >> 5;
         const int bcol = n0 + wn * 128 + 4 * cg;
         uint4 ct = {0u, 0u, 0u, 0u};
@@ -1240,6 +1344,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                     }
                 }
             }
+        }
         }
     }
 }
@@ -1455,7 +1560,12 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
         }
 
         __syncthreads();                                 // every wavefront is done with the stage buffers
-        tile_epilogue<T, T, BMN, REQUANT>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
+        // every practical output zero-point takes the binary32 form of the requantising arithmetic
+        if (REQUANT && p.zc > -8388608 && p.zc < 8388608)
+            tile_epilogue<T, T, BMN, REQUANT, true>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
+                                          (uint32_t *)(lds + 4 * kXposeBytes<T>));
+        else
+            tile_epilogue<T, T, BMN, REQUANT, false>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
                                           (uint32_t *)(lds + 4 * kXposeBytes<T>));
     }
 }

@@ -372,6 +372,44 @@ def test_per_channel_epilogue(rt, oracle):
         ng.ngemm_packed_b_free(h)
 
 
+def test_requant_extremes(rt, oracle):
+    """The requantising epilogues at the edges of their arithmetic: products of the accumulator and
+    the scale at and beyond +-2^31 (where the rounded value leaves the int32 range), output
+    zero-points at the ends of the int32 range, with and without ReLU, per tensor and per column,
+    on every kernel."""
+    ng = ng_mod()
+    rng = np.random.default_rng(102)
+    for (M, N, K) in ((16, 96, 64), (300, 300, 64)):
+        za, zb = 77, 0
+        A = np.full((M, K), za, dtype=np.uint8)
+        A[:, 0] = za + 1                                    # c[i][j] = B[j][0]: every small integer occurs
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        B[:16, 0] = np.array([-128, -4, -3, -2, -1, 0, 1, 2, 3, 4, 5, 8, 16, 64, 127, -64], dtype=np.int8)
+        h, packed = rt.pack(B)
+        Ad = torch.from_numpy(A).cuda()
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        for k in ((0,) if M <= 32 else (1, 2, 3)):
+            rt.set_kernel(k)
+            for scale in (2.0 ** 30, 2.0 ** 29, 2.0 ** 24, 1.5 * 2.0 ** 29, 2.0 ** -30):
+                for zc in (-2**31, -2**31 + 100, -2**31 + 300, -1, 0, 255, 2**31 - 1):
+                    for relu in (False, True):
+                        Cd = torch.full((M, N), 0x5A, dtype=torch.uint8, device="cuda")
+                        if relu:
+                            sv = torch.full((N,), scale, dtype=torch.float32, device="cuda")
+                            ng.ngemm_run_u8s8u8_requant_channel(rt.ctx, M, Ad, K, za, h, zb, None, sv, None, True, zc,
+                                                                Cd, N, ws, wsb)
+                            want = oracle.gemm_u8s8u8_requant_channel(A, B, za, zb, np.full(N, scale, np.float32), zc,
+                                                                      relu=True)
+                        else:
+                            ng.ngemm_run_u8s8u8_requant(rt.ctx, M, Ad, K, za, h, zb, scale, zc, Cd, N, ws, wsb)
+                            want = oracle.gemm_u8s8u8_requant(A, B, za, zb, scale, zc)
+                        torch.cuda.synchronize()
+                        assert np.array_equal(Cd.cpu().numpy(), want), (M, N, K, k, scale, zc, relu)
+        rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+        ng.ngemm_packed_b_free(h)
+
+
 def test_signed_a_variant(rt, oracle):
     """s8 x s8 -> s32 on every kernel, ragged shapes, zero-points over the signed range."""
     ng = ng_mod()
