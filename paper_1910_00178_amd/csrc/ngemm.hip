@@ -345,7 +345,7 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
                        : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_256:
-        if (dma_ok && (uint64_t)a.M * (uint64_t)a.lda < (1ull << 32) && B->bytes < (1ull << 32)) {
+        if (dma_ok && B->K >= X64Cfg::kMinK && (uint64_t)a.M * (uint64_t)a.lda < (1ull << 32) && B->bytes < (1ull << 32)) {
             // the 16 x 16 x 64 form of the matrix instruction
             p.tiles_m = (p.M + 255) / 256;
             p.tiles_n = (p.N + 255) / 256;
@@ -840,7 +840,7 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
         hipError_t e;
         if (kernel == NGEMM_KERNEL_TILE_64) e = launch_tile_dma<64, 64, 2, 2>(p, false, budget, st, &rawb);
         else if (kernel == NGEMM_KERNEL_TILE_128) e = launch_tile_dma<128, 128, 2, 2>(p, false, budget, st, &rawb);
-        else if ((uint64_t)M * (uint64_t)lda < (1ull << 32) && (uint64_t)N * (uint64_t)ldb < (1ull << 32)) {
+        else if (K >= X64Cfg::kMinK && (uint64_t)M * (uint64_t)lda < (1ull << 32) && (uint64_t)N * (uint64_t)ldb < (1ull << 32)) {
             p.tiles_m = (int)((M + 255) / 256);
             p.tiles_n = (int)((N + 255) / 256);
             const int ntiles = p.tiles_m * p.tiles_n;

@@ -1008,14 +1008,14 @@ struct IntC {
 };
 
 // ---- 256 x 256 tiles on the 16 x 16 x 64 matrix instruction ------------------------------------
-// The same tiling, ring and copies as gemm_tile_dma_kernel<256,256,2,2,4>, for int32 output.  On
+// The same tiling as gemm_tile_dma_kernel<256,256,2,2,4> (rings and copies of its own, below).  On
 // operands that change with every instruction the chip is limited by power, not by issue slots, and
 // v_mfma_i32_16x16x64_i8 does the same work for less of it than the 32 x 32 x 32 form (a quarter of
 // the accumulator traffic per instruction, half per multiply-add): a register-only loop of the one
 // sustains 3.9 POP/s on random data, of the other 3.5.  A stage of 64 bytes of K is exactly one such
 // instruction deep:
 //   A operand of block i (16 rows): lane l holds row l%16, bytes 16*(l/16) .. +15 of the stage: one
-//     16-byte read per lane from one 1 KiB block of the copies (with its own chunk rotation, below);
+//     16-byte read per lane from the rows' 128-byte places in LDS (chunk placement below);
 //   B operand of block j (16 columns): lane l holds column l%16, the same bytes; they lie in the two
 //     packed fragments (32-byte k-halves) of the block's panel.  A copy's lanes may fetch any 16 bytes
 //     each, so the chunks of a fragment are permuted on the way into LDS (still one contiguous KiB
@@ -1026,23 +1026,37 @@ struct IntC {
 // operand fragments of two stages in registers: those of stage it+1 are read from LDS while the 64
 // matrix ops of stage it run.
 struct X64Cfg {
-    static constexpr int NSTAGE = 4;
-    static constexpr int kABytes = 256 * 64;
-    static constexpr int kStageBytes = 2 * kABytes;
+    // A: ring of three double stages (256 rows x 128 bytes of K); B: ring of three stages (256 columns
+    // x 64 bytes of K) behind it
+    static constexpr int kARing = 3, kBRing = 3;
+    static constexpr int kADouble = 256 * 128;
+    static constexpr int kBBytes = 256 * 64;
+    static constexpr int kBBase = kARing * kADouble;
     static constexpr int kLoadsPerStage = 8;               // per lane: 4 blocks of A, 4 fragments of B
     static constexpr int kPatchRow = 128 * 4 + 16;         // epilogue patch: 16 rows of 128 int32, padded
     static constexpr int kPatchBytes = 16 * kPatchRow;     // per wavefront
-    static constexpr int kLdsBytes = NSTAGE * kStageBytes;
-    static_assert(4 * kPatchBytes <= kLdsBytes, "epilogue patches fit the ring");
+    static constexpr int kLdsBytes = kBBase + kBRing * kBBytes;
+    static constexpr int kMinK = 128;                      // two full stages: the copies assume them
+    static_assert(4 * kPatchBytes + 3 * 1024 <= kLdsBytes, "epilogue patches and column arrays fit the rings");
+    static_assert(kLdsBytes <= 160 * 1024, "LDS of a compute unit");
 };
 
-// BRAW: B is the caller's plain [N x K] int8 storage (struct RawB); its tiles are then copied and read
-// exactly as A's.
+// A's copies fetch whole 128-byte lines: one copy is 8 rows x 128 bytes of K, two stages' worth, so A
+// moves through LDS in double stages.  (With 64 bytes per row and stage, each line was requested
+// twice, a stage apart, and the 32 KiB that pass through the vector cache in between had evicted it:
+// the cache counters showed 1.5 times the requests the tile needs.)  A double stage is 256 rows of
+// 128 bytes, chunk c of row R in place c ^ (R % 8) (four consecutive lanes of a copy stay inside one
+// aligned 64 bytes of memory, eight consecutive lanes of a fragment read hit eight different
+// places); a stage reads chunks 0..3 (even) or 4..7 (odd) of its rows.  When the number of full stages is odd, the last one's copies start 64
+// bytes earlier, so that nothing past the full stages is fetched: it then lies in the odd position.
+// BRAW: B is the caller's plain [N x K] int8 storage (struct RawB); its tiles are copied by stage, in
+// blocks of 16 columns x 64 bytes with the four chunks of column t rotated by t / 2.
+// The host launches this kernel for K >= kMinK only.
 template <bool BRAW, bool REQUANT = false>
 __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, const RawB rawb)
 {
     using Cfg = X64Cfg;
-    constexpr int NSTAGE = Cfg::NSTAGE, LPS = Cfg::kLoadsPerStage;
+    constexpr int LPS = Cfg::kLoadsPerStage;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1054,16 +1068,17 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     const int ntiles = p.tiles_m * p.tiles_n;
     const int gsz = gridDim.x, w = blockIdx.x;
 
-    const int t16 = lane >> 2;                           // loader: row of the 16-row block
-    const int a_chunk = ((lane & 3) - (t16 >> 1)) & 3;   // chunks of row t rotated by t/2: see a_off
+    const int r8 = lane >> 3;                            // A loader: row of the 8-row block
+    const int a_chunk8 = (lane & 7) ^ r8;                //   and which of the row's eight chunks
+    const int t16 = lane >> 2;                           // BRAW loader of B: column of the 16-column block
+    const int b_chunk = ((lane & 3) - (t16 >> 1)) & 3;
     const int ft = lane & 15, fc = lane >> 4;            // fragments: row / column of the block, 16-byte chunk
-    // A block in LDS: row t at 64 * t, its four chunks rotated by t / 2.  (Measured with the bank
-    // conflict counter: this read pattern -- lane l takes row l % 16, chunk l / 16 -- is free of
-    // conflicts with a rotation by t / 2 and takes twice as long with the rotation by t / 4 that
-    // serves the 32 x 32 x 32 kernels' pattern.)
-    const int a_off = (wm * 8) * 1024 + (4 * ft + ((fc + (ft >> 1)) & 3)) * 16;
-    const int b_off = BRAW ? Cfg::kABytes + a_off + (wn - wm) * 8192
-                           : Cfg::kABytes + (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16;
+    // A fragment of a 16-row block: lane l takes row l % 16, chunk l / 16 (+ 4 in the odd position).
+    // Eight consecutive lanes then cover eight different 16-byte columns of LDS: no bank conflicts.
+    const int a_off0 = (wm * 128 + ft) * 128 + (fc ^ (ft & 7)) * 16;
+    const int a_off1 = a_off0 ^ 64;
+    const int b_off = Cfg::kBBase + (BRAW ? (wn * 8) * 1024 + (4 * ft + ((fc + (ft >> 1)) & 3)) * 16
+                                          : (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16);
 
     // raw buffer descriptors over the operands (no bounds: every offset used below lies inside)
     const uint8_t *b_mem = BRAW ? rawb.B : p.Bp;
@@ -1077,48 +1092,59 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 
         // Loader addresses in buffer form: the matrix as base, a 32-bit lane offset, and the advance
         // along K as a scalar offset, so that a copy costs no vector arithmetic (the host checks that
-        // both operands span less than 4 GiB).
-        uint32_t a_voff[4], b_voff[4];
+        // both operands span less than 4 GiB).  A: copy d of half h takes rows 8 * (16 * h + wave + 4 * d) .. +7.
+        uint32_t a_voff[8], b_voff[4];
         // A B fragment (32 columns x 32 bytes of K, 1 KiB) is copied with its 16-byte chunks permuted:
         // LDS slot 16 * (2 * h + khalf) + t takes column 16 * h + t, k-half khalf (packed slot
         // 32 * khalf + 16 * h + t), so that the two k-halves of a 16-column block lie side by side
         const uint32_t b_lane = (uint32_t)((32 * ((lane >> 4) & 1) + 16 * (lane >> 5) + (lane & 15)) * 16);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int grow = m0 + (wave + 4 * i) * 16 + t16;
+        for (int i = 0; i < 8; ++i) {
+            int grow = m0 + ((i >> 2) * 16 + wave + 4 * (i & 3)) * 8 + r8;
             grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
-            a_voff[i] = (uint32_t)grow * (uint32_t)p.lda + (uint32_t)a_chunk * 16u;
+            a_voff[i] = (uint32_t)grow * (uint32_t)p.lda + (uint32_t)a_chunk8 * 16u;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
             const int q = wave + 4 * i;                  // panel q / 2, k-half q % 2 (BRAW: 16-column block q)
             if (BRAW) {
                 int gcol = n0 + q * 16 + t16;
                 gcol = gcol < p.N ? gcol : p.N - 1;      // columns past N: read a valid one, never stored
-                b_voff[i] = (uint32_t)gcol * (uint32_t)rawb.ldb + (uint32_t)a_chunk * 16u;
+                b_voff[i] = (uint32_t)gcol * (uint32_t)rawb.ldb + (uint32_t)b_chunk * 16u;
             } else {
                 int pnl = n0 / 32 + (q >> 1);
                 pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
                 b_voff[i] = ((uint32_t)pnl * (uint32_t)nslices + (uint32_t)(q & 1)) * (uint32_t)kFragBytes + b_lane;
             }
         }
-        auto dma_one = [&](int s, int d, int buf) {      // copy d (0..7) of stage s into ring buffer buf
+        // K offset of double stage D's copies: both stages full: 128 * D; its first stage is the last
+        // full one: 64 bytes back; past the end: a copy nobody reads.  All three: the smaller of 128 * D
+        // and the last 128 bytes of the full stages.
+        auto a_soff = [&](int D) { return 128 * D < 64 * nfull - 128 ? 128 * D : 64 * nfull - 128; };
+        // (slot: byte offset of the ring place, here and below)
+        auto dma_a = [&](auto half, int soff, int d, int slot) {     // copy d (0..3) of one half of a double stage
+            constexpr int H = decltype(half)::value;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr_t)(lds + slot + (16 * H + wave + 4 * d) * 1024),
+                                                     16, a_voff[4 * H + d], soff, 0, 0);
+        };
+        auto b_soff = [&](int s) {                       // K offset of stage s's copies
             const int g = s < nfull ? s : nfull - 1;     // past the end: a copy nobody reads
-            uint8_t *dst = lds + buf * Cfg::kStageBytes;
-            if (d < 4)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr_t)(dst + (wave + 4 * d) * 1024), 16, a_voff[d],
-                                                         g * 64, 0, 0);
-            else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (d - 4)) * 1024),
-                                                         16, b_voff[d - 4], BRAW ? g * 64 : g * (2 * kFragBytes), 0, 0);
+            return BRAW ? g * 64 : g * (2 * kFragBytes);
+        };
+        auto dma_b = [&](int soff, int d, int slot) {    // copy d (0..3) of a stage
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lptr_t)(lds + Cfg::kBBase + slot + (wave + 4 * d) * 1024),
+                                                     16, b_voff[d], soff, 0, 0);
         };
 
         // B fragments of a stage serve all 64 of its matrix ops: two register sets, the one of stage
         // it+1 filled while stage it runs.  An A fragment serves eight: a rolling window of four.
         v4i fb[2][8], fa[4];
-        auto read_b = [&](auto set, int buf, int j) {
+        auto read_b = [&](auto set, int slot, int j) {
             constexpr int S = decltype(set)::value;
-            fb[S][j] = *(const v4i *)(lds + buf * Cfg::kStageBytes + b_off + (BRAW ? j * 1024 : (j >> 1) * 2048 + (j & 1) * 512));
+            fb[S][j] = *(const v4i *)(lds + slot + b_off + (BRAW ? j * 1024 : (j >> 1) * 2048 + (j & 1) * 512));
         };
-        auto read_a = [&](int buf, int i) {
-            fa[i & 3] = *(const v4i *)(lds + buf * Cfg::kStageBytes + a_off + i * 1024);
+        auto read_a = [&](int slot, int off, int i) {
+            fa[i & 3] = *(const v4i *)(lds + slot + off + i * 2048);
         };
 
         v4i acc[8][8];
@@ -1132,88 +1158,139 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             const int i = m >> 3, j = m & 7;
             acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[S][j], fa[i & 3], acc[i][j], 0, 0, 0);
         };
+        auto mma_first = [&](auto set, int m) {          // the first stage starts the sums
+            constexpr int S = decltype(set)::value;
+            const int i = m >> 3, j = m & 7;
+            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[S][j], fa[i & 3], v4i{0, 0, 0, 0}, 0, 0, 0);
+        };
         auto shift_a = [&](int i) { fa[i & 3] = shift_u8_to_s8(fa[i & 3], p.a_xor); };   // u8 -> s8
         auto shift_a_word = [&](int i, int wd) { fa[i & 3][wd] ^= (int)p.a_xor; };      // one dword of it
 
         if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
 
         if (nfull > 0) {
+            // in flight ahead of the loop: A's double stages 0 and 1 (stages 0..3), B's stages 0..2
+            {
+                const int s0 = a_soff(0), s1 = a_soff(1);
 #pragma unroll
-            for (int s = 0; s < NSTAGE - 1; ++s)
+                for (int d = 0; d < 4; ++d) dma_a(IntC<0>{}, s0, d, 0);
 #pragma unroll
-                for (int d = 0; d < LPS; ++d) dma_one(s, d, s);
-            wait_vmcnt<(NSTAGE - 2) * LPS>();            // stage 0 has landed (this wavefront's part)
+                for (int d = 0; d < 4; ++d) dma_a(IntC<1>{}, s0, d, 0);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) dma_b(b_soff(0), d, 0);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) dma_b(b_soff(1), d, Cfg::kBBytes);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) dma_a(IntC<0>{}, s1, d, Cfg::kADouble);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) dma_a(IntC<1>{}, s1, d, Cfg::kADouble);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) dma_b(b_soff(2), d, 2 * Cfg::kBBytes);
+            }
+            wait_vmcnt<16>();                            // A's stages 0, 1 and B's stage 0 have landed (this wavefront's part)
             __builtin_amdgcn_s_barrier();
 #pragma unroll
             for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, 0, j);
-            read_a(0, 0);
-            read_a(0, 1);
+            read_a(0, a_off0, 0);
+            read_a(0, a_off0, 1);
+            read_a(0, a_off0, 2);
             shift_a(0);
             __builtin_amdgcn_sched_barrier(0);
 
-            // One stage: 64 matrix ops, row block by row block (eight ops each, gaps j = 0..7).
+            // One stage: 64 matrix ops, row block by row block (eight ops each, gaps j = 0..7).  One
+            // wavefront per SIMD issues in order, so whatever else is issued while the matrix pipe is
+            // ready for its next op is lost time: everything below sits in a gap of its own choosing.
+            //   gaps 0..3, 8, 9: the scalar bookkeeping (ring places, K offsets of the copies);
             //   j = 4..7 of row i: the u8 -> s8 shift of A fragment i+1, one dword per gap (a gap has
-            //     room for about three vector instructions before the next matrix op is due).  The
-            //     compiler waits for every outstanding LDS read at j = 4, so the reads follow it and
-            //     have until the next row's shift to return:
-            //   j = 5 of row i: the read of A fragment i+2 (rows 6, 7: fragments 0, 1 of stage it+1);
+            //     room for about three vector instructions before the next matrix op is due);
+            //   j = 5 of row i: the read of A fragment i+3 (rows 5..7: fragments 0..2 of stage it+1),
+            //     two rows ahead of its shift;
             //   j = 6, 7 of rows 2..5: the B fragments of stage it+1 into the other register set;
-            //   every sixth gap from the 17th on: one copy of stage it+NSTAGE-1 (eight copies in a row
-            //     from each of the four wavefronts fill the compute unit's memory pipe and hold the
-            //     wavefronts up at issue: spread out they cost 4 % less time).
-            // Before row 2: wait for this wavefront's copies of stage it+1, barrier (=> stage it+1 is
-            // complete for everybody, and everybody's reads of stage it-1 were consumed a stage ago, so
-            // its buffer is free).
-            auto body = [&](auto set, auto other, int it) {
-                const int buf_c = it % NSTAGE, buf_n = (it + 1) % NSTAGE, buf_f = (it + NSTAGE - 1) % NSTAGE;
+            //   every sixth gap from the 17th on: one copy -- four of A (one half of the double stage
+            //     two ahead of this stage's: the even stage issues rows 0..127, the odd one the rest),
+            //     then four of B's stage it+3 (eight copies in a row from each of the four wavefronts
+            //     fill the compute unit's memory pipe and hold the wavefronts up at issue: spread out
+            //     they cost 4 % less time).
+            // Before row 2: wait until at most this wavefront's eight copies of the stage before are
+            // outstanding, barrier (=> everything stage it+1 reads is complete for everybody, and
+            // everybody's reads of stage it-1 were consumed a stage ago, so its places are free: A's
+            // double stage before this one's, B's stage it, read into registers during stage it-1).
+            // Ring places (byte offsets) and K offsets are worked out in the first gaps of the stage.
+            auto body = [&](auto set, auto other, auto first, int it, int a_cur, int a_nxt) {
+                constexpr int S = decltype(set)::value;              // == it & 1
+                constexpr bool FIRST = decltype(first)::value != 0;
+                constexpr int kA = Cfg::kADouble, kB = Cfg::kBBytes;
+                int ra = 0, rb = 0, as_n = 0, as_f = 0, bs_n = 0, soff_a = 0, soff_b = 0;
 #pragma unroll
                 for (int m = 0; m < 64; ++m) {
                     const int i = m >> 3, j = m & 7;
+                    if (m == 0) ra = ((it >> 1) % 3) * kA;               // A: place of this stage's double stage
+                    if (m == 1) {                        // the double stage after / two after this one's
+                        const int nx = ra == 2 * kA ? 0 : ra + kA;
+                        as_n = S ? nx : ra;
+                        as_f = ra == 0 ? 2 * kA : ra - kA;
+                    }
+                    if (m == 2) rb = (it % 3) * kB;                      // B: place of this stage (free: read a stage ago)
+                    if (m == 9) bs_n = rb == 2 * kB ? 0 : rb + kB;
+                    if (m == 3) soff_a = a_soff((it >> 1) + 2);
+                    if (m == 8) soff_b = b_soff(it + 3);
                     if (m == 16) {
-                        wait_vmcnt<(NSTAGE - 3) * LPS>();
+                        wait_vmcnt<LPS>();
                         __builtin_amdgcn_s_barrier();
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     if (j >= 4) shift_a_word(i + 1, j - 4);
                     if (j == 5) {
-                        if (i < 6) read_a(buf_c, i + 2);
-                        else read_a(buf_n, i - 6);
+                        if (i < 5) read_a(ra, a_cur, i + 3);
+                        else read_a(as_n, a_nxt, i - 5);
                     }
-                    if (j >= 6 && i >= 2 && i < 6) read_b(other, buf_n, 2 * (i - 2) + (j - 6));
-                    if (m >= 17 && (m - 17) % 6 == 0 && (m - 17) / 6 < 8) dma_one(it + NSTAGE - 1, (m - 17) / 6, buf_f);
+                    if (j >= 6 && i >= 2 && i < 6) read_b(other, bs_n, 2 * (i - 2) + (j - 6));
+                    if (m >= 17 && (m - 17) % 6 == 0 && (m - 17) / 6 < 8) {
+                        const int d = (m - 17) / 6;
+                        if (d < 4) dma_a(set, soff_a, d, as_f);
+                        else dma_b(soff_b, d - 4, rb);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
-                    mma(set, m);
+                    if (FIRST) mma_first(set, m);
+                    else mma(set, m);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
-            int it = 0;
+            body(IntC<0>{}, IntC<1>{}, IntC<1>{}, 0, a_off0, a_off1);
+            body(IntC<1>{}, IntC<0>{}, IntC<0>{}, 1, a_off1, 3 == nfull ? a_off1 : a_off0);
+            int it = 2;
             for (; it + 1 < nfull; it += 2) {
-                body(IntC<0>{}, IntC<1>{}, it);
-                body(IntC<1>{}, IntC<0>{}, it + 1);
+                body(IntC<0>{}, IntC<1>{}, IntC<0>{}, it, a_off0, a_off1);
+                // the stage after an odd one is even, unless it is the last of an odd number of stages
+                body(IntC<1>{}, IntC<0>{}, IntC<0>{}, it + 1, a_off1, it + 3 == nfull ? a_off1 : a_off0);
             }
-            if (it < nfull) body(IntC<0>{}, IntC<1>{}, it);
+            if (it < nfull) body(IntC<0>{}, IntC<1>{}, IntC<0>{}, it, a_off1, a_off0);
             wait_vmcnt<0>();                             // drain the copies nobody reads
         }
 
-        // K tail: the last, partial stage.  Guarded register loads into buffer 0, same layout.
+        // K tail: the last, partial stage.  Guarded register loads into the first places of the rings
+        // (A: even position), same layouts.
         if (has_tail) {
             const int kbase = nfull * 64;
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int q = wave + 4 * i;
-                const int valid = p.K - (kbase + a_chunk * 16);
-                const uint8_t *src = p.A + a_voff[i] + kbase;
+                const int R = 16 * q + t16, c = lane & 3;
+                const int grow = m0 + R < p.M ? m0 + R : p.M - 1;
+                const int valid = p.K - (kbase + c * 16);
+                const uint8_t *src = p.A + (int64_t)grow * p.lda + kbase + c * 16;
                 v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
-                *(v4i *)(lds + q * 1024 + lane * 16) = v;
+                *(v4i *)(lds + R * 128 + (c ^ (R & 7)) * 16) = v;
                 v4i z = {0, 0, 0, 0};
                 if (BRAW) {
+                    const int bvalid = p.K - (kbase + b_chunk * 16);
                     const uint8_t *bs = b_mem + b_voff[i] + kbase;
-                    z = valid >= 16 ? load16_any(bs) : load16_partial(bs, valid < 0 ? 0 : valid);
+                    z = bvalid >= 16 ? load16_any(bs) : load16_partial(bs, bvalid < 0 ? 0 : bvalid);
                 } else if (nfull * 2 + (q & 1) < nslices) {
                     z = *(const v4i *)(b_mem + b_voff[i] + (int64_t)nfull * (2 * kFragBytes));
                 }
-                *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) = z;
+                *(v4i *)(lds + Cfg::kBBase + q * 1024 + lane * 16) = z;
             }
             __syncthreads();
 #pragma unroll
@@ -1221,7 +1298,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 #pragma unroll
             for (int m = 0; m < 64; ++m) {
                 if ((m & 7) == 0) {
-                    read_a(0, m >> 3);
+                    read_a(0, a_off0, m >> 3);
                     shift_a(m >> 3);
                 }
                 mma(IntC<0>{}, m);

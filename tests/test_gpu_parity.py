@@ -218,6 +218,40 @@ def test_edge_shapes_all_kernels(rt, oracle):
                       ldc_pad=int(rng.integers(0, 3)), a_byte_offset=int(rng.integers(0, 4)))
 
 
+def test_large_tile_kernel_k_edges(rt, oracle):
+    """The 256 x 256 kernel on 16-byte aligned rows (its copy path) around every boundary of its K
+    pipeline: two full stages (the fewest it takes), odd and even numbers of full stages (A moves
+    in double stages of 128 bytes; an odd last stage is fetched 64 bytes early), with and without
+    a partial stage behind them, ragged M and N, int32 and requantised output, and B both packed
+    and as a plain input."""
+    ng = ng_mod()
+    rng = np.random.default_rng(79)
+    ks = (128, 129, 191, 192, 193, 255, 256, 257, 320, 383, 384, 449, 576, 639, 1000, 1088)
+    dims = ((1, 260), (255, 1), (257, 250), (300, 513), (512, 256))
+    for t, K in enumerate(ks):
+        M, N = dims[t % len(dims)]
+        za, zb = ((0, 0), (128, 0), (255, -128), (77, 9))[t % 4]
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        p = wl.Problem(f"kedge_{M}x{N}x{K}", A, B, za=za, zb=zb, scale=float(np.float32(0.003)), zc=31)
+        check_problem(rt, oracle, p, (3,), lda_pad=(-K) % 16, ldb_pad=t % 3)
+        if M > 32:
+            ld = K + (-K) % 16
+            Ah = np.zeros((M, ld), dtype=np.uint8); Ah[:, :K] = A
+            Bh = np.zeros((N, ld), dtype=np.int8); Bh[:, :K] = B
+            Ad, Bd = torch.from_numpy(Ah).cuda(), torch.from_numpy(Bh).cuda()
+            wsb = ng.ngemm_unpacked_workspace_bytes(M, N, K)
+            ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+            Cd = torch.full((M, N), -5, dtype=torch.int32, device="cuda")
+            rt.set_kernel(3)
+            try:
+                ng.ngemm_run_u8s8s32_unpacked(rt.ctx, M, N, K, Ad, ld, za, Bd, ld, zb, Cd, N, ws, wsb)
+                torch.cuda.synchronize()
+            finally:
+                rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+            assert np.array_equal(Cd.cpu().numpy(), oracle.gemm_u8s8s32(A, B, za, zb)), (M, N, K, "plain B")
+
+
 def test_skinny_all_row_counts(rt, oracle):
     rng = np.random.default_rng(78)
     for M in range(1, 33):
