@@ -1047,8 +1047,9 @@ struct X64Cfg {
 // the cache counters showed 1.5 times the requests the tile needs.)  A double stage is 256 rows of
 // 128 bytes, chunk c of row R in place c ^ (R % 8) (four consecutive lanes of a copy stay inside one
 // aligned 64 bytes of memory, eight consecutive lanes of a fragment read hit eight different
-// places); a stage reads chunks 0..3 (even) or 4..7 (odd) of its rows.  When the number of full stages is odd, the last one's copies start 64
-// bytes earlier, so that nothing past the full stages is fetched: it then lies in the odd position.
+// places); a stage reads chunks 0..3 (even) or 4..7 (odd) of its rows.  The pipelined loop takes an
+// even number of stages, so that no copy reaches past the full stages of K; an odd last full stage and
+// the partial stage after it are loaded through registers with guards and consumed without pipelining.
 // BRAW: B is the caller's plain [N x K] int8 storage (struct RawB); its tiles are copied by stage, in
 // blocks of 16 columns x 64 bytes with the four chunks of column t rotated by t / 2.
 // The host launches this kernel for K >= kMinK only.
@@ -1063,8 +1064,8 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int nslices = p.Kp / 32;
-    const int nfull = p.K / 64;
-    const bool has_tail = nfull * 64 < p.Kp;
+    const int nfull = p.K / 64 & ~1;                     // stages of the pipelined loop: an even number
+    const int nstages = p.Kp / 64;                       // the one or two after them (full, partial) go unpipelined
     const int ntiles = p.tiles_m * p.tiles_n;
     const int gsz = gridDim.x, w = blockIdx.x;
 
@@ -1117,9 +1118,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                 b_voff[i] = ((uint32_t)pnl * (uint32_t)nslices + (uint32_t)(q & 1)) * (uint32_t)kFragBytes + b_lane;
             }
         }
-        // K offset of double stage D's copies: both stages full: 128 * D; its first stage is the last
-        // full one: 64 bytes back; past the end: a copy nobody reads.  All three: the smaller of 128 * D
-        // and the last 128 bytes of the full stages.
+        // K offset of double stage D's copies (past the end: the last one again, a copy nobody reads)
         auto a_soff = [&](int D) { return 128 * D < 64 * nfull - 128 ? 128 * D : 64 * nfull - 128; };
         // (slot: byte offset of the ring place, here and below)
         auto dma_a = [&](auto half, int soff, int d, int slot) {     // copy d (0..3) of one half of a double stage
@@ -1139,12 +1138,12 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         // B fragments of a stage serve all 64 of its matrix ops: two register sets, the one of stage
         // it+1 filled while stage it runs.  An A fragment serves eight: a rolling window of four.
         v4i fb[2][8], fa[4];
-        auto read_b = [&](auto set, int slot, int j) {
+        auto read_b = [&](auto set, const uint8_t *from, int j) {     // from: lds + place + b_off
             constexpr int S = decltype(set)::value;
-            fb[S][j] = *(const v4i *)(lds + slot + b_off + (BRAW ? j * 1024 : (j >> 1) * 2048 + (j & 1) * 512));
+            fb[S][j] = *(const v4i *)(from + (BRAW ? j * 1024 : (j >> 1) * 2048 + (j & 1) * 512));
         };
-        auto read_a = [&](int slot, int off, int i) {
-            fa[i & 3] = *(const v4i *)(lds + slot + off + i * 2048);
+        auto read_a = [&](const uint8_t *from, int i) {                // from: lds + place + a_off0 or a_off1
+            fa[i & 3] = *(const v4i *)(from + i * 2048);
         };
 
         v4i acc[8][8];
@@ -1190,50 +1189,50 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             wait_vmcnt<16>();                            // A's stages 0, 1 and B's stage 0 have landed (this wavefront's part)
             __builtin_amdgcn_s_barrier();
 #pragma unroll
-            for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, 0, j);
-            read_a(0, a_off0, 0);
-            read_a(0, a_off0, 1);
-            read_a(0, a_off0, 2);
+            for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, lds + b_off, j);
+            read_a(lds + a_off0, 0);
+            read_a(lds + a_off0, 1);
+            read_a(lds + a_off0, 2);
             shift_a(0);
             __builtin_amdgcn_sched_barrier(0);
 
             // One stage: 64 matrix ops, row block by row block (eight ops each, gaps j = 0..7).  One
-            // wavefront per SIMD issues in order, so whatever else is issued while the matrix pipe is
-            // ready for its next op is lost time: everything below sits in a gap of its own choosing.
-            //   gaps 0..3, 8, 9: the scalar bookkeeping (ring places, K offsets of the copies);
-            //   j = 4..7 of row i: the u8 -> s8 shift of A fragment i+1, one dword per gap (a gap has
-            //     room for about three vector instructions before the next matrix op is due);
+            // wavefront per SIMD issues in order, about one instruction every four cycles, and a matrix
+            // op takes sixteen: a gap has room for three other instructions, a fourth delays the next
+            // matrix op.  So everything sits in a gap of its own choosing:
+            //   j = 4..7 of row i: the u8 -> s8 shift of A fragment i+1, one dword per gap;
             //   j = 5 of row i: the read of A fragment i+3 (rows 5..7: fragments 0..2 of stage it+1),
             //     two rows ahead of its shift;
             //   j = 6, 7 of rows 2..5: the B fragments of stage it+1 into the other register set;
-            //   every sixth gap from the 17th on: one copy -- four of A (one half of the double stage
-            //     two ahead of this stage's: the even stage issues rows 0..127, the odd one the rest),
-            //     then four of B's stage it+3 (eight copies in a row from each of the four wavefronts
-            //     fill the compute unit's memory pipe and hold the wavefronts up at issue: spread out
-            //     they cost 4 % less time).
+            //   j = 1 of rows 2..7 and j = 3 of rows 3, 5: one copy each (M0, the wait state it needs,
+            //     the copy) -- four of A (one half of the double stage two ahead of this stage's: the
+            //     even stage issues rows 0..127, the odd one the rest), then four of B's stage it+3.
+            //     Eight copies in a row from each of the four wavefronts fill the compute unit's memory
+            //     pipe and hold the wavefronts up at issue: spread out they cost 4 % less time;
+            //   j = 0..3 of rows 0, 1: the scalar bookkeeping (ring places as byte offsets, carried from
+            //     stage to stage; K offsets of the copies) and the three LDS addresses it feeds.
             // Before row 2: wait until at most this wavefront's eight copies of the stage before are
             // outstanding, barrier (=> everything stage it+1 reads is complete for everybody, and
             // everybody's reads of stage it-1 were consumed a stage ago, so its places are free: A's
             // double stage before this one's, B's stage it, read into registers during stage it-1).
-            // Ring places (byte offsets) and K offsets are worked out in the first gaps of the stage.
-            auto body = [&](auto set, auto other, auto first, int it, int a_cur, int a_nxt) {
+            int ra = 0, rb = 0;                          // A: place of stage it's double stage; B: of stage it
+            auto body = [&](auto set, auto other, auto first, int it) {
                 constexpr int S = decltype(set)::value;              // == it & 1
                 constexpr bool FIRST = decltype(first)::value != 0;
                 constexpr int kA = Cfg::kADouble, kB = Cfg::kBBytes;
-                int ra = 0, rb = 0, as_n = 0, as_f = 0, bs_n = 0, soff_a = 0, soff_b = 0;
+                int as_n = 0, as_f = 0, bs_n = 0, soff_a = 0, soff_b = 0;
+                const uint8_t *pa_c = nullptr, *pa_n = nullptr, *pb_n = nullptr;
 #pragma unroll
                 for (int m = 0; m < 64; ++m) {
                     const int i = m >> 3, j = m & 7;
-                    if (m == 0) ra = ((it >> 1) % 3) * kA;               // A: place of this stage's double stage
-                    if (m == 1) {                        // the double stage after / two after this one's
-                        const int nx = ra == 2 * kA ? 0 : ra + kA;
-                        as_n = S ? nx : ra;
-                        as_f = ra == 0 ? 2 * kA : ra - kA;
-                    }
-                    if (m == 2) rb = (it % 3) * kB;                      // B: place of this stage (free: read a stage ago)
-                    if (m == 9) bs_n = rb == 2 * kB ? 0 : rb + kB;
-                    if (m == 3) soff_a = a_soff((it >> 1) + 2);
-                    if (m == 8) soff_b = b_soff(it + 3);
+                    if (m == 0) as_n = !S ? ra : (ra == 2 * kA ? 0 : ra + kA);    // double stage of stage it+1
+                    if (m == 1) pa_c = lds + ra + (S ? a_off1 : a_off0);
+                    if (m == 2) as_f = ra == 0 ? 2 * kA : ra - kA;               // two double stages ahead
+                    if (m == 3) pa_n = lds + as_n + (S ? a_off0 : a_off1);
+                    if (m == 8) bs_n = rb == 2 * kB ? 0 : rb + kB;
+                    if (m == 9) soff_a = a_soff((it >> 1) + 2);
+                    if (m == 10) soff_b = b_soff(it + 3);
+                    if (m == 11) pb_n = lds + bs_n + b_off;
                     if (m == 16) {
                         wait_vmcnt<LPS>();
                         __builtin_amdgcn_s_barrier();
@@ -1241,14 +1240,19 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                     }
                     if (j >= 4) shift_a_word(i + 1, j - 4);
                     if (j == 5) {
-                        if (i < 5) read_a(ra, a_cur, i + 3);
-                        else read_a(as_n, a_nxt, i - 5);
+                        if (i < 5) read_a(pa_c, i + 3);
+                        else read_a(pa_n, i - 5);
                     }
-                    if (j >= 6 && i >= 2 && i < 6) read_b(other, bs_n, 2 * (i - 2) + (j - 6));
-                    if (m >= 17 && (m - 17) % 6 == 0 && (m - 17) / 6 < 8) {
-                        const int d = (m - 17) / 6;
+                    if (j >= 6 && i >= 2 && i < 6) read_b(other, pb_n, 2 * (i - 2) + (j - 6));
+                    if (i >= 2 && (j == 1 || (j == 3 && (i == 3 || i == 5)))) {
+                        // copies 0..7 in the gaps m = 17, 25, 27, 33, 41, 43, 49, 57
+                        const int d = i == 2 ? 0 : i == 3 ? (j == 1 ? 1 : 2) : i == 4 ? 3 : i == 5 ? (j == 1 ? 4 : 5) : i;
                         if (d < 4) dma_a(set, soff_a, d, as_f);
                         else dma_b(soff_b, d - 4, rb);
+                    }
+                    if (m == 58) {                       // step the rings
+                        rb = bs_n;
+                        ra = as_n;
                     }
                     __builtin_amdgcn_sched_barrier(0);
                     if (FIRST) mma_first(set, m);
@@ -1256,22 +1260,20 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
-            body(IntC<0>{}, IntC<1>{}, IntC<1>{}, 0, a_off0, a_off1);
-            body(IntC<1>{}, IntC<0>{}, IntC<0>{}, 1, a_off1, 3 == nfull ? a_off1 : a_off0);
-            int it = 2;
-            for (; it + 1 < nfull; it += 2) {
-                body(IntC<0>{}, IntC<1>{}, IntC<0>{}, it, a_off0, a_off1);
-                // the stage after an odd one is even, unless it is the last of an odd number of stages
-                body(IntC<1>{}, IntC<0>{}, IntC<0>{}, it + 1, a_off1, it + 3 == nfull ? a_off1 : a_off0);
+            // the first stage starts the sums (no zeroed accumulators ahead of the loop)
+            body(IntC<0>{}, IntC<1>{}, IntC<1>{}, 0);
+            body(IntC<1>{}, IntC<0>{}, IntC<0>{}, 1);
+            for (int it = 2; it < nfull; it += 2) {
+                body(IntC<0>{}, IntC<1>{}, IntC<0>{}, it);
+                body(IntC<1>{}, IntC<0>{}, IntC<0>{}, it + 1);
             }
-            if (it < nfull) body(IntC<0>{}, IntC<1>{}, IntC<0>{}, it, a_off1, a_off0);
             wait_vmcnt<0>();                             // drain the copies nobody reads
         }
 
-        // K tail: the last, partial stage.  Guarded register loads into the first places of the rings
-        // (A: even position), same layouts.
-        if (has_tail) {
-            const int kbase = nfull * 64;
+        // What is left of K: an odd last full stage and / or a partial one.  Guarded register loads
+        // into the first places of the rings (A: even position), same layouts, no pipelining.
+        for (int ts = nfull; ts < nstages; ++ts) {
+            const int kbase = ts * 64;
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -1287,18 +1289,18 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                     const int bvalid = p.K - (kbase + b_chunk * 16);
                     const uint8_t *bs = b_mem + b_voff[i] + kbase;
                     z = bvalid >= 16 ? load16_any(bs) : load16_partial(bs, bvalid < 0 ? 0 : bvalid);
-                } else if (nfull * 2 + (q & 1) < nslices) {
-                    z = *(const v4i *)(b_mem + b_voff[i] + (int64_t)nfull * (2 * kFragBytes));
+                } else if (ts * 2 + (q & 1) < nslices) {
+                    z = *(const v4i *)(b_mem + b_voff[i] + (int64_t)ts * (2 * kFragBytes));
                 }
                 *(v4i *)(lds + Cfg::kBBase + q * 1024 + lane * 16) = z;
             }
             __syncthreads();
 #pragma unroll
-            for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, 0, j);
+            for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, lds + b_off, j);
 #pragma unroll
             for (int m = 0; m < 64; ++m) {
                 if ((m & 7) == 0) {
-                    read_a(0, a_off0, m >> 3);
+                    read_a(lds + a_off0, m >> 3);
                     shift_a(m >> 3);
                 }
                 mma(IntC<0>{}, m);
