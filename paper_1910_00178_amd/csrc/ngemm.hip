@@ -56,6 +56,13 @@ constexpr int BK256 = NGEMM_BK256;               // stage depth of the 256 x 256
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
+// gemm_tile_x64_kernel addresses its copies with 32-bit offsets from the tile's first row (panel,
+// column): `rows` rows of `pitch` bytes, `extent` bytes used of the last one
+inline bool x64_offsets_fit(int64_t rows, int64_t pitch, int64_t extent)
+{
+    return pitch < (1ll << 32) && (rows - 1) * pitch + extent + 4096 < (1ll << 32);
+}
+
 struct DeviceGuard {
     int prev = -1;
     bool ok = false;
@@ -345,7 +352,7 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
                        : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_256:
-        if (dma_ok && B->K >= X64Cfg::kMinK && (uint64_t)a.M * (uint64_t)a.lda < (1ull << 32) && B->bytes < (1ull << 32)) {
+        if (dma_ok && B->K >= X64Cfg::kMinK && x64_offsets_fit(256, a.lda, B->K) && x64_offsets_fit(9, 32 * round_up(B->K, 64), 0)) {
             // the 16 x 16 x 64 form of the matrix instruction
             p.tiles_m = (p.M + 255) / 256;
             p.tiles_n = (p.N + 255) / 256;
@@ -840,7 +847,7 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
         hipError_t e;
         if (kernel == NGEMM_KERNEL_TILE_64) e = launch_tile_dma<64, 64, 2, 2>(p, false, budget, st, &rawb);
         else if (kernel == NGEMM_KERNEL_TILE_128) e = launch_tile_dma<128, 128, 2, 2>(p, false, budget, st, &rawb);
-        else if (K >= X64Cfg::kMinK && (uint64_t)M * (uint64_t)lda < (1ull << 32) && (uint64_t)N * (uint64_t)ldb < (1ull << 32)) {
+        else if (K >= X64Cfg::kMinK && x64_offsets_fit(256, lda, K) && x64_offsets_fit(256, ldb, K)) {
             p.tiles_m = (int)((M + 255) / 256);
             p.tiles_n = (int)((N + 255) / 256);
             const int ntiles = p.tiles_m * p.tiles_n;

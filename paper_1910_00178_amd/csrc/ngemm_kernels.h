@@ -1081,19 +1081,21 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     const int b_off = Cfg::kBBase + (BRAW ? (wn * 8) * 1024 + (4 * ft + ((fc + (ft >> 1)) & 3)) * 16
                                           : (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16);
 
-    // raw buffer descriptors over the operands (no bounds: every offset used below lies inside)
-    const uint8_t *b_mem = BRAW ? rawb.B : p.Bp;
-    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void *)p.A, (short)0, -1, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)b_mem, (short)0, -1, 0x00020000);
-
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
         tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
         const int m0 = tm * 256, n0 = tn * 256;
 
-        // Loader addresses in buffer form: the matrix as base, a 32-bit lane offset, and the advance
-        // along K as a scalar offset, so that a copy costs no vector arithmetic (the host checks that
-        // both operands span less than 4 GiB).  A: copy d of half h takes rows 8 * (16 * h + wave + 4 * d) .. +7.
+        // Loader addresses in buffer form: the tile's first row of A / first panel (BRAW: column) of B
+        // as base of a raw buffer descriptor (no bounds: every offset used below lies inside), a 32-bit
+        // lane offset, and the advance along K as a scalar offset, so that a copy costs no vector
+        // arithmetic (the host checks that 256 rows of A, and eight panels or 256 columns of B, span
+        // less than 4 GiB).  A: copy d of half h takes rows 8 * (16 * h + wave + 4 * d) .. +7.
+        const uint8_t *b_tile = BRAW ? rawb.B + (int64_t)n0 * rawb.ldb
+                                     : p.Bp + (int64_t)(n0 / 32) * nslices * kFragBytes;
+        const __amdgpu_buffer_rsrc_t rsrc_a =
+            __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (int64_t)m0 * p.lda), (short)0, -1, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)b_tile, (short)0, -1, 0x00020000);
         uint32_t a_voff[8], b_voff[4];
         // A B fragment (32 columns x 32 bytes of K, 1 KiB) is copied with its 16-byte chunks permuted:
         // LDS slot 16 * (2 * h + khalf) + t takes column 16 * h + t, k-half khalf (packed slot
@@ -1103,7 +1105,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         for (int i = 0; i < 8; ++i) {
             int grow = m0 + ((i >> 2) * 16 + wave + 4 * (i & 3)) * 8 + r8;
             grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
-            a_voff[i] = (uint32_t)grow * (uint32_t)p.lda + (uint32_t)a_chunk8 * 16u;
+            a_voff[i] = (uint32_t)(grow - m0) * (uint32_t)p.lda + (uint32_t)a_chunk8 * 16u;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -1111,11 +1113,11 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             if (BRAW) {
                 int gcol = n0 + q * 16 + t16;
                 gcol = gcol < p.N ? gcol : p.N - 1;      // columns past N: read a valid one, never stored
-                b_voff[i] = (uint32_t)gcol * (uint32_t)rawb.ldb + (uint32_t)b_chunk * 16u;
+                b_voff[i] = (uint32_t)(gcol - n0) * (uint32_t)rawb.ldb + (uint32_t)b_chunk * 16u;
             } else {
                 int pnl = n0 / 32 + (q >> 1);
                 pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
-                b_voff[i] = ((uint32_t)pnl * (uint32_t)nslices + (uint32_t)(q & 1)) * (uint32_t)kFragBytes + b_lane;
+                b_voff[i] = ((uint32_t)(pnl - n0 / 32) * (uint32_t)nslices + (uint32_t)(q & 1)) * (uint32_t)kFragBytes + b_lane;
             }
         }
         // K offset of double stage D's copies (past the end: the last one again, a copy nobody reads)
@@ -1287,10 +1289,10 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                 v4i z = {0, 0, 0, 0};
                 if (BRAW) {
                     const int bvalid = p.K - (kbase + b_chunk * 16);
-                    const uint8_t *bs = b_mem + b_voff[i] + kbase;
+                    const uint8_t *bs = b_tile + b_voff[i] + kbase;
                     z = bvalid >= 16 ? load16_any(bs) : load16_partial(bs, bvalid < 0 ? 0 : bvalid);
                 } else if (ts * 2 + (q & 1) < nslices) {
-                    z = *(const v4i *)(b_mem + b_voff[i] + (int64_t)ts * (2 * kFragBytes));
+                    z = *(const v4i *)(b_tile + b_voff[i] + (int64_t)ts * (2 * kFragBytes));
                 }
                 *(v4i *)(lds + Cfg::kBBase + q * 1024 + lane * 16) = z;
             }

@@ -252,6 +252,48 @@ def test_large_tile_kernel_k_edges(rt, oracle):
             assert np.array_equal(Cd.cpu().numpy(), oracle.gemm_u8s8s32(A, B, za, zb)), (M, N, K, "plain B")
 
 
+def test_operands_beyond_4_gib(rt, oracle):
+    """Maximum sizes: an A operand and a B operand of more than 4 GiB each (the 256 x 256 kernel
+    addresses its copies with 32-bit offsets from each tile's first row / panel, the pack and the
+    epilogue with 64-bit ones).  Sampled outputs, weighted towards the rows and columns past the
+    4 GiB mark, against the oracle; zero-points on, so the row and column sums are covered too."""
+    ng = ng_mod()
+    rng = np.random.default_rng(80)
+    big, small, K = 66000, 300, 65536
+    for a_is_big in (True, False):
+        M, N = (big, small) if a_is_big else (small, big)
+        # rank-one-plus-noise operands: cheap to generate at this size, every row and column distinct
+        A = (rng.integers(0, 256, size=(M, 1), dtype=np.uint8) + rng.integers(0, 256, size=(1, K), dtype=np.uint8))
+        B = (rng.integers(-128, 128, size=(N, 1), dtype=np.int8) + rng.integers(-128, 128, size=(1, K), dtype=np.int8))
+        assert A.dtype == np.uint8 and B.dtype == np.int8 and max(A.nbytes, B.nbytes) > 1 << 32
+        za, zb = 117, -5
+        Ad, Bd = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        nbytes = ng.ngemm_packed_b_bytes(K, N)
+        packed = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        h = ng.ngemm_pack_b(rt.ctx, K, N, Bd, K, packed, nbytes)
+        del Bd
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        Cd = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+        rt.set_kernel(3)
+        try:
+            ng.ngemm_run_u8s8s32(rt.ctx, M, Ad, K, za, h, zb, Cd, N, ws, wsb)
+            torch.cuda.synchronize()
+        finally:
+            rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+        nb = big - (1 << 32) // K                      # rows / columns past the 4 GiB mark
+        far = rng.integers(big - nb, big, size=3000)
+        anyb = rng.integers(0, big, size=3000)
+        bi = np.concatenate([far, anyb, [0, big - 1, (1 << 32) // K - 1, (1 << 32) // K]])
+        si = rng.integers(0, small, size=bi.size)
+        ri, ci = (bi, si) if a_is_big else (si, bi)
+        got = Cd[torch.from_numpy(ri).cuda(), torch.from_numpy(ci).cuda()].cpu().numpy()
+        want = oracle.gemm_u8s8s32_sampled(A, B, ri, ci, za, zb)
+        assert np.array_equal(got, want), ("A" if a_is_big else "B", np.count_nonzero(got != want))
+        ng.ngemm_packed_b_free(h)
+        del Ad, packed, Cd, ws, A, B
+
+
 def test_skinny_all_row_counts(rt, oracle):
     rng = np.random.default_rng(78)
     for M in range(1, 33):
