@@ -387,6 +387,25 @@ def main():
         ms_un = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32_unpacked(ctx, n, n, n, At, n, 0, Bt, n, 0, Ct, n, uws, uwb),
                             100, 100, torch)
         extras["unpacked_b_%d" % n] = {"ms": round(ms_un, 4), "TOPS": round(ops / (ms_un * 1e-3) / 1e12, 1)}
+        # The same launch on operands that do not change (A = 129, B = 1): on uniform data the chip runs
+        # at its power cap (shader clock about 1.8 GHz), on such data at its full clock.  Context only.
+        Ac = torch.full((n, n), 129, dtype=torch.uint8, device="cuda")
+        Bc = torch.ones((n, n), dtype=torch.int8, device="cuda")
+        hc = ng.ngemm_pack_b(ctx, n, n, Bc, n, pks, nb)
+        ms_c = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32(ctx, n, Ac, n, 0, hc, 0, Ct, n), 200, 200, torch)
+        ng.ngemm_packed_b_free(hc)
+        pl = {"constant_operands_TOPS": round(ops / (ms_c * 1e-3) / 1e12, 1),
+              "constant_operands_frac_of_peak": round(ops / (ms_c * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4)}
+        # the vendor library's int8 GEMM on the same operands (s8 x s8, B column-major), for context
+        try:
+            Bcol = Bt.t()
+            ms_lu = gpu_time_ms(lambda: torch._int_mm(At.view(torch.int8), Bcol), 100, 100, torch)
+            ms_lc = gpu_time_ms(lambda: torch._int_mm(Ac.view(torch.int8), Bc.t()), 100, 100, torch)
+            pl["library_int_mm_uniform_TOPS"] = round(ops / (ms_lu * 1e-3) / 1e12, 1)
+            pl["library_int_mm_constant_TOPS"] = round(ops / (ms_lc * 1e-3) / 1e12, 1)
+        except Exception as e:  # not every build of the framework has it
+            pl["library_int_mm"] = "unavailable: %s" % type(e).__name__
+        extras["power_limit_context_%d" % n] = pl
         result["extras"] = extras
 
     ng.ngemm_destroy(ctx)
