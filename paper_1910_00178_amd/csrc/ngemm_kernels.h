@@ -1341,12 +1341,23 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             auto rq = [&](uint32_t v, float sc) -> uint32_t {
                 return SMALL ? requant_u8_small_zc((int32_t)v, sc, zcf, p.relu) : requant_u8((int32_t)v, sc, p.zc, p.relu);
             };
+            // sum_k (A[i][k] - za) of this lane's row in each of the eight blocks, multiplied per column
+            // by that column's zero-point of B (all loaded first: a load between the blocks would wait
+            // for the stores of the block before it)
+            uint32_t rsums[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rsums[i] = p.rconst;
+            if (p.rowsum) {                              // rows past M read row M - 1 and are never stored
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int row = m0 + wm * 128 + 16 * i + ft;
+                    rsums[i] += (uint32_t)p.rowsum[row < p.M ? row : p.M - 1];
+                }
+            }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int brow0 = m0 + wm * 128 + 16 * i;
-                const int row = brow0 + ft;
-                // sum_k (A[i][k] - za), multiplied per column by that column's zero-point of B
-                const uint32_t rsum = ((p.rowsum && row < p.M) ? (uint32_t)p.rowsum[row] : 0u) + p.rconst;
+                const uint32_t rsum = rsums[i];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const int lcol = wn * 128 + 16 * j + 4 * fc;
@@ -1391,12 +1402,23 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             ct.z = p.za_term * (uint32_t)cs.z; ct.w = p.za_term * (uint32_t)cs.w;
         }
         const bool interior = m0 + (wm + 1) * 128 <= p.M && n0 + (wn + 1) * 128 <= p.N;
+        // the row terms of all eight blocks first, as eight independent loads (rows past M read row
+        // M - 1 and are never stored): loaded block by block, each load would wait for its own
+        // latency and for the stores of the block before it
+        uint32_t row_terms[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) row_terms[i] = p.kconst;
+        if (p.rowsum) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = m0 + wm * 128 + 16 * i + ft;
+                row_terms[i] -= p.zb * (uint32_t)p.rowsum[row < p.M ? row : p.M - 1];
+            }
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int brow0 = m0 + wm * 128 + 16 * i;
-            const int row = brow0 + ft;
-            uint32_t row_term = p.kconst;
-            if (p.rowsum && row < p.M) row_term -= p.zb * (uint32_t)p.rowsum[row];
+            const uint32_t row_term = row_terms[i];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 v4i v = acc[i][j];
