@@ -1079,8 +1079,11 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     // Eight consecutive lanes then cover eight different 16-byte columns of LDS: no bank conflicts.
     const int a_off0 = (wm * 128 + ft) * 128 + (fc ^ (ft & 7)) * 16;
     const int a_off1 = a_off0 ^ 64;
-    const int b_off = Cfg::kBBase + (BRAW ? (wn * 8) * 1024 + (4 * ft + ((fc + (ft >> 1)) & 3)) * 16
-                                          : (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16);
+    int b_off = Cfg::kBBase + (BRAW ? (wn * 8) * 1024 + (4 * ft + ((fc + (ft >> 1)) & 3)) * 16
+                                    : (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16);
+    // B's ring lies beyond the 64 KiB an LDS instruction's immediate offset reaches: keep its base in
+    // this one register (left to itself the compiler forms a register per ring place and fragment)
+    asm volatile("" : "+v"(b_off));
 
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
@@ -1312,6 +1315,12 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 
         __syncthreads();                                 // every wavefront is done with the stage buffers
 
+        // What the epilogue derives from the lane index is computed from here on (the compiler would
+        // otherwise prepare its addresses ahead of the main loop, carry them across it in registers
+        // the loop needs, and spill them).
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int ft = lane_e & 15, fc = lane_e >> 4;
         uint8_t *patch = lds + wave * Cfg::kPatchBytes;
         if (REQUANT) {
             // Requantising epilogue (per tensor or per column).  The three per-column arrays of the tile
@@ -1330,7 +1339,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             }
             __syncthreads();
             constexpr int kRow8 = 128 + 16;              // byte patch: 16 rows of 128 bytes, padded
-            const int cg8 = lane & 7, r8 = lane >> 3;    // read-back: 8 lanes of 16 bytes per row, 8 rows per pass
+            const int cg8 = lane_e & 7, r8 = lane_e >> 3;    // read-back: 8 lanes of 16 bytes per row, 8 rows per pass
             const int bcol8 = n0 + wn * 128 + 16 * cg8;
             const bool interior = m0 + (wm + 1) * 128 <= p.M && n0 + (wn + 1) * 128 <= p.N &&
                                   ((((uintptr_t)p.C | (uintptr_t)p.ldc) & 15) == 0);
@@ -1393,7 +1402,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         // Epilogue.  Per 16-row block: row terms added, the 16 x 128 block written to an LDS patch as
         // it lies in the accumulators, read back two rows per instruction, column terms added, stored
         // as full 512-byte row pieces.
-        const int cg = lane & 31, r2 = lane >> 5;
+        const int cg = lane_e & 31, r2 = lane_e >> 5;
         const int bcol = n0 + wn * 128 + 4 * cg;
         uint4 ct = {0u, 0u, 0u, 0u};
         if (bcol < p.N) {
