@@ -1070,10 +1070,6 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     const int ntiles = p.tiles_m * p.tiles_n;
     const int gsz = gridDim.x, w = blockIdx.x;
 
-    const int r8 = lane >> 3;                            // A loader: row of the 8-row block
-    const int a_chunk8 = (lane & 7) ^ r8;                //   and which of the row's eight chunks
-    const int t16 = lane >> 2;                           // BRAW loader of B: column of the 16-column block
-    const int b_chunk = ((lane & 3) - (t16 >> 1)) & 3;
     const int ft = lane & 15, fc = lane >> 4;            // fragments: row / column of the block, 16-byte chunk
     // A fragment of a 16-row block: lane l takes row l % 16, chunk l / 16 (+ 4 in the odd position).
     // Eight consecutive lanes then cover eight different 16-byte columns of LDS: no bank conflicts.
@@ -1090,6 +1086,15 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
         const int m0 = tm * 256, n0 = tn * 256;
 
+        // (the loaders' lane arithmetic is redone per tile: kept across the main loop it would be
+        // spilled, and a reload waits for every store of the tile before still in flight)
+        int lane_t = lane;
+        asm volatile("" : "+v"(lane_t));
+        const int r8 = lane_t >> 3;                          // A loader: row of the 8-row block
+        const int a_chunk8 = (lane_t & 7) ^ r8;              //   and which of the row's eight chunks
+        const int t16 = lane_t >> 2;                         // BRAW loader of B: column of the 16-column block
+        const int b_chunk = ((lane_t & 3) - (t16 >> 1)) & 3;
+
         // Loader addresses in buffer form: the tile's first row of A / first panel (BRAW: column) of B
         // as base of a raw buffer descriptor (no bounds: every offset used below lies inside), a 32-bit
         // lane offset, and the advance along K as a scalar offset, so that a copy costs no vector
@@ -1101,15 +1106,16 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (int64_t)m0 * p.lda), (short)0, -1, 0x00020000);
         const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)b_tile, (short)0, -1, 0x00020000);
         uint32_t a_voff[8], b_voff[4];
+        const uint32_t lda32 = (uint32_t)p.lda;                // 256 rows span less than 4 GiB
         // A B fragment (32 columns x 32 bytes of K, 1 KiB) is copied with its 16-byte chunks permuted:
         // LDS slot 16 * (2 * h + khalf) + t takes column 16 * h + t, k-half khalf (packed slot
         // 32 * khalf + 16 * h + t), so that the two k-halves of a 16-column block lie side by side
-        const uint32_t b_lane = (uint32_t)((32 * ((lane >> 4) & 1) + 16 * (lane >> 5) + (lane & 15)) * 16);
+        const uint32_t b_lane = (uint32_t)((32 * ((lane_t >> 4) & 1) + 16 * (lane_t >> 5) + (lane_t & 15)) * 16);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             int grow = m0 + ((i >> 2) * 16 + wave + 4 * (i & 3)) * 8 + r8;
             grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
-            a_voff[i] = (uint32_t)(grow - m0) * (uint32_t)p.lda + (uint32_t)a_chunk8 * 16u;
+            a_voff[i] = (uint32_t)(grow - m0) * lda32 + (uint32_t)a_chunk8 * 16u;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -1152,11 +1158,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             fa[i & 3] = *(const v4i *)(from + i * 2048);
         };
 
-        v4i acc[8][8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+        v4i acc[8][8];                                   // started by the first stage (K >= kMinK: there is one)
         // matrix op m (0..63) of a stage: row block m / 8, column block m % 8
         auto mma = [&](auto set, int m) {
             constexpr int S = decltype(set)::value;
@@ -1173,7 +1175,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 
         if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
 
-        if (nfull > 0) {
+        {
             // in flight ahead of the loop: A's double stages 0 and 1 (stages 0..3), B's stages 0..2
             {
                 const int s0 = a_soff(0), s1 = a_soff(1);
@@ -1276,6 +1278,13 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             wait_vmcnt<0>();                             // drain the copies nobody reads
         }
 
+        // What the rest of the tile derives from the lane index is computed from here on (the compiler
+        // would otherwise prepare the addresses of the K tail and of the epilogue ahead of the main
+        // loop, carry them across it in registers the loop needs, and spill them; a reload then waits
+        // for every copy or store in flight).
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+
         // What is left of K: an odd last full stage and / or a partial one.  Guarded register loads
         // into the first places of the rings (A: even position), same layouts, no pipelining.
         for (int ts = nfull; ts < nstages; ++ts) {
@@ -1284,7 +1293,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int q = wave + 4 * i;
-                const int R = 16 * q + t16, c = lane & 3;
+                const int R = 16 * q + (lane_e >> 2), c = lane_e & 3;
                 const int grow = m0 + R < p.M ? m0 + R : p.M - 1;
                 const int valid = p.K - (kbase + c * 16);
                 const uint8_t *src = p.A + (int64_t)grow * p.lda + kbase + c * 16;
@@ -1292,13 +1301,13 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                 *(v4i *)(lds + R * 128 + (c ^ (R & 7)) * 16) = v;
                 v4i z = {0, 0, 0, 0};
                 if (BRAW) {
-                    const int bvalid = p.K - (kbase + b_chunk * 16);
+                    const int bvalid = p.K - (kbase + (((lane_e & 3) - (lane_e >> 3)) & 3) * 16);
                     const uint8_t *bs = b_tile + b_voff[i] + kbase;
                     z = bvalid >= 16 ? load16_any(bs) : load16_partial(bs, bvalid < 0 ? 0 : bvalid);
                 } else if (ts * 2 + (q & 1) < nslices) {
                     z = *(const v4i *)(b_tile + b_voff[i] + (int64_t)ts * (2 * kFragBytes));
                 }
-                *(v4i *)(lds + Cfg::kBBase + q * 1024 + lane * 16) = z;
+                *(v4i *)(lds + Cfg::kBBase + q * 1024 + lane_e * 16) = z;
             }
             __syncthreads();
 #pragma unroll
@@ -1315,11 +1324,6 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 
         __syncthreads();                                 // every wavefront is done with the stage buffers
 
-        // What the epilogue derives from the lane index is computed from here on (the compiler would
-        // otherwise prepare its addresses ahead of the main loop, carry them across it in registers
-        // the loop needs, and spill them).
-        int lane_e = lane;
-        asm volatile("" : "+v"(lane_e));
         const int ft = lane_e & 15, fc = lane_e >> 4;
         uint8_t *patch = lds + wave * Cfg::kPatchBytes;
         if (REQUANT) {
