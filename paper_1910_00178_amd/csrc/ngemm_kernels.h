@@ -1451,22 +1451,29 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             for (int q = 0; q < 8; ++q) o[q] = *(const v4i *)(patch + (2 * q + r2) * Cfg::kPatchRow + cg * 16);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                v4i v = o[q];
-                v.x = (int)((uint32_t)v.x + ct.x); v.y = (int)((uint32_t)v.y + ct.y);
-                v.z = (int)((uint32_t)v.z + ct.z); v.w = (int)((uint32_t)v.w + ct.w);
-                const int orow = brow0 + 2 * q + r2;
-                int32_t *dst = (int32_t *)p.C + (int64_t)orow * p.ldc + bcol;
-                if (interior) {
+                o[q].x = (int)((uint32_t)o[q].x + ct.x); o[q].y = (int)((uint32_t)o[q].y + ct.y);
+                o[q].z = (int)((uint32_t)o[q].z + ct.z); o[q].w = (int)((uint32_t)o[q].w + ct.w);
+            }
+            int32_t *dst = (int32_t *)p.C + (int64_t)(brow0 + r2) * p.ldc + bcol;   // this lane's first row of the block
+            if (interior) {                              // one branch per block, no per-lane tests
+#pragma unroll
+                for (int q = 0; q < 8; ++q, dst += 2 * p.ldc) {
                     // streaming store (4-byte aligned is enough): C is not read again, and kept out of
                     // L2 it leaves the A and B panels there (6 % fewer main-loop cycles at the full clock)
-                    __builtin_nontemporal_store(v, (v4i_a4 *)dst);
-                } else if (orow < p.M && bcol < p.N) {
-                    if (bcol + 3 < p.N) {
-                        __builtin_memcpy(dst, &v, 16);
-                    } else {
-                        dst[0] = v.x;
-                        if (bcol + 1 < p.N) dst[1] = v.y;
-                        if (bcol + 2 < p.N) dst[2] = v.z;
+                    __builtin_nontemporal_store(o[q], (v4i_a4 *)dst);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 8; ++q, dst += 2 * p.ldc) {
+                    const v4i v = o[q];
+                    if (brow0 + 2 * q + r2 < p.M && bcol < p.N) {
+                        if (bcol + 3 < p.N) {
+                            __builtin_memcpy(dst, &v, 16);
+                        } else {
+                            dst[0] = v.x;
+                            if (bcol + 1 < p.N) dst[1] = v.y;
+                            if (bcol + 2 < p.N) dst[2] = v.z;
+                        }
                     }
                 }
             }
