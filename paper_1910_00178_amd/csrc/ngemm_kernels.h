@@ -1038,6 +1038,7 @@ struct X64Cfg {
     static constexpr int kPatchBytes = 16 * kPatchRow;     // per wavefront
     static constexpr int kLdsBytes = kBBase + kBRing * kBBytes;
     static constexpr int kMinK = 128;                      // two full stages: the copies assume them
+    static constexpr int kCopyBias = 3 * 1024;             // see the copies: lane offsets carry it, the bases lack it
     static_assert(4 * kPatchBytes + 3 * 1024 <= kLdsBytes, "epilogue patches and column arrays fit the rings");
     static_assert(kLdsBytes <= 160 * 1024, "LDS of a compute unit");
 };
@@ -1106,12 +1107,18 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         // as base of a raw buffer descriptor (no bounds: every offset used below lies inside), a 32-bit
         // lane offset, and the advance along K as a scalar offset, so that a copy costs no vector
         // arithmetic (the host checks that 256 rows of A, and eight panels or 256 columns of B, span
-        // less than 4 GiB).  A: copy d of half h takes rows 8 * (16 * h + wave + 4 * d) .. +7.
+        // less than 4 GiB).  A: copy d of half h takes rows 8 * (16 * h + 4 * wave + d) .. +7.
         const uint8_t *b_tile = BRAW ? rawb.B + (int64_t)n0 * rawb.ldb
                                      : p.Bp + (int64_t)(n0 / 32) * nslices * kFragBytes;
-        const __amdgpu_buffer_rsrc_t rsrc_a =
-            __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (int64_t)m0 * p.lda), (short)0, -1, 0x00020000);
-        const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)b_tile, (short)0, -1, 0x00020000);
+        // A wavefront's four copies of one operand go to four consecutive KiB of LDS: the LDS base (M0)
+        // is written once for the four, and copy d carries the immediate offset 1024 * d, which the
+        // instruction adds to the LDS address and to the memory address alike.  The lane offsets take
+        // the latter back (+ kCopyBias - 1024 * d, never negative), the descriptors' bases start
+        // kCopyBias early (an address only: nothing below the operand is touched).
+        const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((uintptr_t)(p.A + (int64_t)m0 * p.lda) - Cfg::kCopyBias), (short)0, -1, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((uintptr_t)b_tile - Cfg::kCopyBias), (short)0, -1, 0x00020000);
         uint32_t a_voff[8], b_voff[4];
         const uint32_t lda32 = (uint32_t)p.lda;                // 256 rows span less than 4 GiB
         // A B fragment (32 columns x 32 bytes of K, 1 KiB) is copied with its 16-byte chunks permuted:
@@ -1120,21 +1127,22 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         const uint32_t b_lane = (uint32_t)((32 * ((lane_t >> 4) & 1) + 16 * (lane_t >> 5) + (lane_t & 15)) * 16);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            int grow = m0 + ((i >> 2) * 16 + wave + 4 * (i & 3)) * 8 + r8;
+            int grow = m0 + ((i >> 2) * 16 + 4 * wave + (i & 3)) * 8 + r8;
             grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
-            a_voff[i] = (uint32_t)(grow - m0) * lda32 + (uint32_t)a_chunk8 * 16u;
+            a_voff[i] = (uint32_t)(grow - m0) * lda32 + (uint32_t)a_chunk8 * 16u + (uint32_t)(Cfg::kCopyBias - 1024 * (i & 3));
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int q = wave + 4 * i;                  // panel q / 2, k-half q % 2 (BRAW: 16-column block q)
+            const int q = 4 * wave + i;                  // panel q / 2, k-half q % 2 (BRAW: 16-column block q)
+            const uint32_t bias = (uint32_t)(Cfg::kCopyBias - 1024 * i);
             if (BRAW) {
                 int gcol = n0 + q * 16 + t16;
                 gcol = gcol < p.N ? gcol : p.N - 1;      // columns past N: read a valid one, never stored
-                b_voff[i] = (uint32_t)(gcol - n0) * (uint32_t)rawb.ldb + (uint32_t)b_chunk * 16u;
+                b_voff[i] = (uint32_t)(gcol - n0) * (uint32_t)rawb.ldb + (uint32_t)b_chunk * 16u + bias;
             } else {
                 int pnl = n0 / 32 + (q >> 1);
                 pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
-                b_voff[i] = ((uint32_t)(pnl - n0 / 32) * (uint32_t)nslices + (uint32_t)(q & 1)) * (uint32_t)kFragBytes + b_lane;
+                b_voff[i] = ((uint32_t)(pnl - n0 / 32) * (uint32_t)nslices + (uint32_t)(q & 1)) * (uint32_t)kFragBytes + b_lane + bias;
             }
         }
         // K offset of double stage D's copies (past the end: the last one again, a copy nobody reads)
@@ -1142,16 +1150,26 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         // (slot: byte offset of the ring place, here and below)
         auto dma_a = [&](auto half, int soff, int d, int slot) {     // copy d (0..3) of one half of a double stage
             constexpr int H = decltype(half)::value;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr_t)(lds + slot + (16 * H + wave + 4 * d) * 1024),
-                                                     16, a_voff[4 * H + d], soff, 0, 0);
+            const lptr_t to = (lptr_t)(lds + slot + (16 * H + 4 * wave) * 1024);
+            switch (d) {                                 // the immediate offset has to be a literal
+            case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[4 * H + 0], soff, 0, 0); break;
+            case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[4 * H + 1], soff, 1024, 0); break;
+            case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[4 * H + 2], soff, 2048, 0); break;
+            default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[4 * H + 3], soff, 3072, 0); break;
+            }
         };
         auto b_soff = [&](int s) {                       // K offset of stage s's copies
             const int g = s < nfull ? s : nfull - 1;     // past the end: a copy nobody reads
             return BRAW ? g * 64 : g * (2 * kFragBytes);
         };
         auto dma_b = [&](int soff, int d, int slot) {    // copy d (0..3) of a stage
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lptr_t)(lds + Cfg::kBBase + slot + (wave + 4 * d) * 1024),
-                                                     16, b_voff[d], soff, 0, 0);
+            const lptr_t to = (lptr_t)(lds + Cfg::kBBase + slot + (4 * wave) * 1024);
+            switch (d) {
+            case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, to, 16, b_voff[0], soff, 0, 0); break;
+            case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, to, 16, b_voff[1], soff, 1024, 0); break;
+            case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, to, 16, b_voff[2], soff, 2048, 0); break;
+            default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, to, 16, b_voff[3], soff, 3072, 0); break;
+            }
         };
 
         // B fragments of a stage serve all 64 of its matrix ops: two register sets, the one of stage
@@ -1299,7 +1317,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int q = wave + 4 * i;
+                const int q = 4 * wave + i;                // the blocks as the copies divide them (B: b_voff[i])
                 const int R = 16 * q + (lane_e >> 2), c = lane_e & 3;
                 const int grow = m0 + R < p.M ? m0 + R : p.M - 1;
                 const int valid = p.K - (kbase + c * 16);
@@ -1309,10 +1327,10 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                 v4i z = {0, 0, 0, 0};
                 if (BRAW) {
                     const int bvalid = p.K - (kbase + (((lane_e & 3) - (lane_e >> 3)) & 3) * 16);
-                    const uint8_t *bs = b_tile + b_voff[i] + kbase;
+                    const uint8_t *bs = b_tile + (b_voff[i] - (uint32_t)(Cfg::kCopyBias - 1024 * i)) + kbase;
                     z = bvalid >= 16 ? load16_any(bs) : load16_partial(bs, bvalid < 0 ? 0 : bvalid);
                 } else if (ts * 2 + (q & 1) < nslices) {
-                    z = *(const v4i *)(b_tile + b_voff[i] + (int64_t)ts * (2 * kFragBytes));
+                    z = *(const v4i *)(b_tile + (b_voff[i] - (uint32_t)(Cfg::kCopyBias - 1024 * i)) + (int64_t)ts * (2 * kFragBytes));
                 }
                 *(v4i *)(lds + Cfg::kBBase + q * 1024 + lane_e * 16) = z;
             }
