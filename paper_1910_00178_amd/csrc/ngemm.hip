@@ -213,16 +213,17 @@ hipError_t launch_skinny(const GemmParams &p, bool requant, int num_cus, hipStre
     return hipGetLastError();
 }
 
-// Shape heuristic: the 256 x 256 configuration when it fills at least three quarters of the
-// compute units, the 128 x 128 one when every unit still gets a workgroup, else 64 x 64
-// (measured on 18 shapes from 16 x 512 x 512 to 4096^3: the smallest tile wins as long as the
-// larger ones leave units idle; ngemm_tune_u8s8s32 settles the borderline cases by measurement).
+// Shape heuristic: the 256 x 256 configuration when it fills at least half of the compute units
+// (3072^3, 144 tiles: 35 us against 47 us with 128 x 128; 2048 x 4096 x 1024, 128 tiles: a tie),
+// the 128 x 128 one when every unit still gets a workgroup, else 64 x 64 (measured on 18 shapes
+// from 16 x 512 x 512 to 4096^3: the smallest tile wins as long as the larger ones leave units
+// idle; ngemm_tune_u8s8s32 settles the borderline cases by measurement).
 int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N)
 {
     if (M <= kSkinnyMaxM) return NGEMM_KERNEL_SKINNY;
     auto tiles = [&](int64_t b) { return ((M + b - 1) / b) * ((N + b - 1) / b); };
     const int64_t cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
-    if (tiles(256) * 4 >= cus * 3) return NGEMM_KERNEL_TILE_256;
+    if (tiles(256) * 2 >= cus) return NGEMM_KERNEL_TILE_256;
     if (tiles(128) >= cus) return NGEMM_KERNEL_TILE_128;
     return NGEMM_KERNEL_TILE_64;
 }
