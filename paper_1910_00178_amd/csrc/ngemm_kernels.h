@@ -1392,16 +1392,24 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                     rsums[i] += (uint32_t)p.rowsum[row < p.M ? row : p.M - 1];
                 }
             }
+            // this lane's columns are the same in every block: their three terms are read once
+            uint4 cbs[8], zvs[8];
+            float4 scs[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int lcol = wn * 128 + 16 * j + 4 * fc;
+                cbs[j] = *(const uint4 *)(cterm + lcol);
+                zvs[j] = *(const uint4 *)(cterm + 256 + lcol);
+                scs[j] = *(const float4 *)((const float *)cterm + 512 + lcol);
+            }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int brow0 = m0 + wm * 128 + 16 * i;
                 const uint32_t rsum = rsums[i];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const int lcol = wn * 128 + 16 * j + 4 * fc;
-                    const uint4 cb = *(const uint4 *)(cterm + lcol);
-                    const uint4 zv = *(const uint4 *)(cterm + 256 + lcol);
-                    const float4 sc = *(const float4 *)((const float *)cterm + 512 + lcol);
+                    const uint4 cb = cbs[j], zv = zvs[j];
+                    const float4 sc = scs[j];
                     const v4i v = acc[i][j];
                     const uint32_t b0 = rq((uint32_t)v.x + cb.x - zv.x * rsum, sc.x);
                     const uint32_t b1 = rq((uint32_t)v.y + cb.y - zv.y * rsum, sc.y);
