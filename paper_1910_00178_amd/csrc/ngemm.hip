@@ -928,7 +928,11 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         return hipGetLastError();
     };
     auto push = [&](GroupParams &gp, const GemmParams &p, int64_t units) {
-        gp.prob[gp.count] = p;
+        GroupMember &m = gp.prob[gp.count];          // the rest is rebuilt on the device
+        m.A = p.A; m.Bp = p.Bp; m.rowsum = p.rowsum; m.C = p.C;
+        m.lda = p.lda; m.ldc = p.ldc;
+        m.M = p.M; m.N = p.N; m.K = p.K;
+        m.za_term = p.za_term; m.zb = p.zb;
         gp.unit_start[gp.count + 1] = gp.unit_start[gp.count] + (int)units;
         ++gp.count;
     };
@@ -965,9 +969,7 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
                 if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
             push(skinny, p, units);
         } else {
-            p.tiles_m = (p.M + 63) / 64;
-            p.tiles_n = (p.N + 63) / 64;
-            const int64_t units = (int64_t)p.tiles_m * p.tiles_n;
+            const int64_t units = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
             if (tiles.count == kGroupMax || tiles.unit_start[tiles.count] + units > kMaxGrid)
                 if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
             push(tiles, p, units);

@@ -674,15 +674,26 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmPar
 }
 
 // ---- grouped launches: several independent problems in one grid -------------------------------
-// The problems' parameters travel in the kernel argument block (at most kGroupMax of them, to
-// stay inside its 4 KiB); unit_start[q] is the first workgroup id of problem q, unit_start[count]
-// the grid size.  What a "unit" is depends on the kernel: a 64 x 64 tile, a 32-column panel, or a
-// group of four rows of A.
-constexpr int kGroupMax = 27;
+// The problems' parameters travel in the kernel argument block, which holds 4 KiB: each member is
+// cut down to what cannot be derived (GroupMember, 72 bytes), so that kGroupMax of them fit, and a
+// workgroup rebuilds the full parameter set of its own member with a few scalar operations.
+// unit_start[q] is the first workgroup id of problem q, unit_start[count] the grid size.  What a
+// "unit" is depends on the kernel: a 64 x 64 tile, a 32-column panel, or a group of four rows of A.
+// Members are u8 x s8 -> s32 problems with per-tensor zero-points.
+constexpr int kGroupMax = 52;
+struct GroupMember {
+    const uint8_t *A;
+    const uint8_t *Bp;       // packed fragments; the column sums follow them
+    const int32_t *rowsum;   // or nullptr when zb == 0
+    void *C;
+    int64_t lda, ldc;
+    int M, N, K;
+    uint32_t za_term, zb;
+};
 struct GroupParams {
     int count;
     int unit_start[kGroupMax + 1];
-    GemmParams prob[kGroupMax];
+    GroupMember prob[kGroupMax];
 };
 
 static_assert(sizeof(GroupParams) <= 4096, "kernel argument block");
@@ -695,12 +706,46 @@ __device__ __forceinline__ int group_find(const GroupParams &g, int bid)
     return q;
 }
 
+// The full parameter set of a member; tiles are counted for BM x BN workgroup tiles.
+template <int BM, int BN>
+__device__ __forceinline__ GemmParams group_member_params(const GroupMember &m)
+{
+    GemmParams p;
+    p.A = m.A;
+    p.lda = m.lda;
+    p.Bp = m.Bp;
+    p.M = m.M;
+    p.N = m.N;
+    p.K = m.K;
+    p.Kp = (m.K + 63) & ~63;
+    p.npanels = (m.N + 31) >> 5;
+    p.colsum = (const int32_t *)(m.Bp + (int64_t)p.Kp * (p.npanels * 32));
+    p.rowsum = m.rowsum;
+    p.C = m.C;
+    p.ldc = m.ldc;
+    p.tiles_m = (m.M + BM - 1) / BM;
+    p.tiles_n = (m.N + BN - 1) / BN;
+    p.za_term = m.za_term;
+    p.zb = m.zb;
+    p.kconst = 0u - m.zb * m.za_term * (uint32_t)m.K;
+    p.scale = 1.0f;
+    p.zc = 0;
+    p.scale_vec = nullptr;
+    p.bias_vec = nullptr;
+    p.zb_vec = nullptr;
+    p.rconst = m.za_term * (uint32_t)m.K;
+    p.relu = 0;
+    p.a_xor = 0x80808080u;
+    return p;
+}
+
 template <int BM, int BN, int WGM, int WGN, int BK>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_group_tile_kernel(const GroupParams g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int q = group_find(g, blockIdx.x);
-    tile_body_staged<BM, BN, WGM, WGN, BK, false>(g.prob[q], blockIdx.x - g.unit_start[q], lds);
+    const GemmParams p = group_member_params<BM, BN>(g.prob[q]);
+    tile_body_staged<BM, BN, WGM, WGN, BK, false>(p, blockIdx.x - g.unit_start[q], lds);
 }
 
 // ---- tiled MFMA kernel, direct-to-LDS variant -------------------------------------------------
@@ -2127,7 +2172,7 @@ __global__ __launch_bounds__(512) void gemm_group_skinny_kernel(const GroupParam
 {
     extern __shared__ int red[];
     const int q = group_find(g, blockIdx.x);
-    const GemmParams &p = g.prob[q];
+    const GemmParams p = group_member_params<64, 64>(g.prob[q]);
     skinny_body<false, 1>(p, blockIdx.x - g.unit_start[q], 4 * ((p.M + 7) / 8), red);
 }
 
@@ -2135,11 +2180,11 @@ __global__ __launch_bounds__(512) void gemm_group_skinny_kernel(const GroupParam
 __global__ __launch_bounds__(256) void rowsum_group_kernel(const GroupParams g)
 {
     const int q = group_find(g, blockIdx.x);
-    const GemmParams &p = g.prob[q];
+    const GroupMember &p = g.prob[q];
     const int i = (blockIdx.x - g.unit_start[q]) * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (i >= p.M) return;
-    const int s = row_sum_shifted(p.A + (int64_t)i * p.lda, p.K, lane, p.a_xor);
+    const int s = row_sum_shifted(p.A + (int64_t)i * p.lda, p.K, lane, 0x80808080u);
     if (lane == 0) ((int32_t *)p.rowsum)[i] = s;
 }
 

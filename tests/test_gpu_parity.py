@@ -166,11 +166,11 @@ def test_config5_batched_mixed(rt, oracle):
 
 def test_batched_degenerate_members(rt, oracle):
     """A batch mixing empty members (M = 0, N = 0, K = 0), skinny and tiled members, with and
-    without a weight zero-point, more than one argument block's worth (> 32) of them."""
+    without a weight zero-point, several argument blocks' worth of each kind of them."""
     ng = ng_mod()
     rng = np.random.default_rng(91)
     shapes = [(0, 5, 7), (5, 0, 7), (5, 7, 0), (1, 1, 1), (33, 65, 129), (32, 64, 64), (70, 3, 300)]
-    shapes += [(int(rng.integers(1, 90)), int(rng.integers(1, 90)), int(rng.integers(1, 200))) for _ in range(40)]
+    shapes += [(int(rng.integers(1, 90)), int(rng.integers(1, 90)), int(rng.integers(1, 200))) for _ in range(200)]
     items, outs, probs, keep, handles = [], [], [], [], []
     for t, (M, N, K) in enumerate(shapes):
         A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
