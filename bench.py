@@ -327,6 +327,25 @@ def main():
             ng.ngemm_packed_b_free(hb)
         extras["bert_fc"] = fc
 
+        # few tiles, long K: K split over the workgroups (the heuristic's choice) against one
+        # workgroup per tile (M > 32) or the streaming kernel (M <= 32)
+        sk_extra = {}
+        for (Ms, Ns, Ks) in ((64, 64, 65536), (256, 256, 16384), (512, 512, 16384), (100, 300, 30000), (16, 1024, 8192)):
+            rngs = wl.rng_for(4, 70 + Ms)
+            As = torch.from_numpy(wl.uniform_u8(rngs, Ms, Ks)).cuda()
+            hb, pk, _ = pack(wl.uniform_s8(rngs, Ns, Ks))
+            Cs = torch.empty((Ms, Ns), dtype=torch.int32, device="cuda")
+            call = [lambda: ng.ngemm_run_u8s8s32(ctx, Ms, As, Ks, 0, hb, 0, Cs, Ns)] * 20
+            ms_split = graph_time_ms(call, 10, torch)
+            ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_SKINNY if Ms <= 32 else ng.NGEMM_KERNEL_TILE_64)
+            ms_plain = graph_time_ms(call, 10, torch)
+            ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_AUTO)
+            o = 2.0 * Ms * Ns * Ks
+            sk_extra["%dx%dx%d" % (Ms, Ns, Ks)] = {"split_k_us": round(ms_split * 1e3, 2), "unsplit_us": round(ms_plain * 1e3, 2),
+                                                   "split_k_TOPS": round(o / (ms_split * 1e-3) / 1e12, 1)}
+            ng.ngemm_packed_b_free(hb)
+        extras["underfilled_long_k"] = sk_extra
+
         # batched odd shapes
         probs = wl.batched()
         items, keep, hs = [], [], []

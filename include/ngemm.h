@@ -58,7 +58,8 @@ enum {
     NGEMM_KERNEL_TILE_64 = 1,    /* 64 x 64 workgroup tile                                */
     NGEMM_KERNEL_TILE_128 = 2,   /* 128 x 128 workgroup tile                              */
     NGEMM_KERNEL_TILE_256 = 3,   /* 256 x 256 workgroup tile (throughput configuration)   */
-    NGEMM_KERNEL_COUNT = 4
+    NGEMM_KERNEL_SPLIT_K = 4,    /* 64 x 64 tiles, K split over workgroups; int32 outputs */
+    NGEMM_KERNEL_COUNT = 5
 };
 
 /* Human-readable name of a status code (static string, never NULL). */
@@ -76,7 +77,13 @@ ngemm_status ngemm_destroy(ngemm_ctx *ctx);
 
 /* Force one kernel for the run calls (NGEMM_KERNEL_*), or NGEMM_KERNEL_AUTO for
  * the shape heuristic.  Forcing NGEMM_KERNEL_SKINNY with M > 32 makes the run
- * call return NGEMM_ERR_INVALID_ARG. */
+ * call return NGEMM_ERR_INVALID_ARG.  NGEMM_KERNEL_SPLIT_K serves outputs with so few
+ * 64 x 64 tiles that most compute units would idle: K is cut into parts of at least 1024
+ * bytes, one workgroup per tile and part; C is cleared by a launch of its own and the parts
+ * add their partial sums with atomic adds (integer addition in any order gives the same
+ * bits, the property Sec. 2.1 rests on).  It needs an int32 output, 16-byte aligned rows of
+ * A and a K of at least 2048; every other call it is forced on runs the 64 x 64 tiles
+ * (the streaming kernel when M <= 32). */
 ngemm_status ngemm_set_kernel(ngemm_ctx *ctx, int kernel);
 
 /*

@@ -172,6 +172,40 @@ hipError_t launch_tile_deep(const GemmParams &p0, bool requant, int num_cus, hip
     return hipGetLastError();
 }
 
+// K split over workgroups for outputs that leave most compute units without a tile (64 x 64 tiles,
+// int32 output): S = the number of parts that brings the grid up to the unit count, each part a
+// multiple of 256 bytes of K (whole stages of the long pipeline) and at least kSplitMinChunk long.
+// C is cleared first and every part adds its partial tile with atomic adds (exact in any order).
+constexpr int kSplitMinChunk = 1024;
+int splitk_parts(int64_t M, int64_t N, int64_t K, int num_cus, int *kchunk)
+{
+    const int64_t ntiles = ((M + 63) / 64) * ((N + 63) / 64);
+    int64_t S = ntiles > 0 ? num_cus / ntiles : 1;
+    if (S * kSplitMinChunk > K) S = K / kSplitMinChunk;
+    if (S < 2) return 1;
+    const int64_t chunk = round_up((K + S - 1) / S, 256);
+    *kchunk = (int)chunk;
+    return (int)((K + chunk - 1) / chunk);         // every part holds at least one byte of K
+}
+
+hipError_t launch_tile_deep_splitk(const GemmParams &p0, int parts, int kchunk, int num_cus, hipStream_t st)
+{
+    using Cfg = DeepCfg<1, kDeepSub<1>, kDeepStages>;
+    GemmParams p = p0;
+    p.tiles_m = (p.M + 63) / 64;
+    p.tiles_n = (p.N + 63) / 64;
+    p.ksplit = parts;
+    p.kchunk = kchunk;
+    const int64_t segs = (p.N + 1023) / 1024;
+    hipLaunchKernelGGL(zero_c_kernel, dim3((unsigned)(p.M * segs)), dim3(256), 0, st, (int32_t *)p.C, p.ldc, p.N, (int)segs);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int nunits = p.tiles_m * p.tiles_n * parts;
+    dim3 grid((unsigned)(nunits < num_cus ? nunits : num_cus)), block(256);
+    hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true>), grid, block, Cfg::kLdsBytes, st, p);
+    return hipGetLastError();
+}
+
 template <int T>
 hipError_t allow_big_lds_deep()
 {
@@ -179,6 +213,11 @@ hipError_t allow_big_lds_deep()
     hipError_t e = hipFuncSetAttribute((const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
+    if (T == 1) {
+        e = hipFuncSetAttribute((const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+        if (e != hipSuccess) return e;
+    }
     return hipFuncSetAttribute((const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
 }
@@ -218,11 +257,21 @@ hipError_t launch_skinny(const GemmParams &p, bool requant, int num_cus, hipStre
 // the 128 x 128 one when every unit still gets a workgroup, else 64 x 64 (measured on 18 shapes
 // from 16 x 512 x 512 to 4096^3: the smallest tile wins as long as the larger ones leave units
 // idle; ngemm_tune_u8s8s32 settles the borderline cases by measurement).
-int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N)
+constexpr int64_t kSplitMinK = 4096;
+int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N, int64_t K)
 {
-    if (M <= kSkinnyMaxM) return NGEMM_KERNEL_SKINNY;
     auto tiles = [&](int64_t b) { return ((M + b - 1) / b) * ((N + b - 1) / b); };
     const int64_t cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
+    // Few tiles and a long K: spread K over the idle units.  The launch that clears C and the
+    // atomic adds have to pay off: measured on 48 shapes, the split wins from K = 4096 on up to 48
+    // tiles of 64 x 64, from 8192 up to 96, from 12288 up to 128; against the streaming kernel
+    // (M <= 32) from K = 8192 while the output has at most 32 such tiles (N <= 2048).
+    const int64_t t64 = tiles(64), step = 3 * cus / 16;
+    if (M <= kSkinnyMaxM) {
+        if (K >= 2 * kSplitMinK && t64 * 8 <= cus) return NGEMM_KERNEL_SPLIT_K;
+        return NGEMM_KERNEL_SKINNY;
+    }
+    if (t64 * 2 <= cus && K >= kSplitMinK * ((t64 + step - 1) / step)) return NGEMM_KERNEL_SPLIT_K;
     if (tiles(256) * 2 >= cus) return NGEMM_KERNEL_TILE_256;
     if (tiles(128) >= cus) return NGEMM_KERNEL_TILE_128;
     return NGEMM_KERNEL_TILE_64;
@@ -277,7 +326,7 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
     if (k == NGEMM_KERNEL_AUTO) {
         for (const ngemm_ctx::Tuned &t : ctx->tuned)
             if (t.M == a.M && t.N == a.B->N && t.K == a.B->K) k = t.kernel;
-        if (k == NGEMM_KERNEL_AUTO) k = choose_kernel(ctx, a.M, a.B->N);
+        if (k == NGEMM_KERNEL_AUTO) k = choose_kernel(ctx, a.M, a.B->N, a.B->K);
     }
     if (k == NGEMM_KERNEL_SKINNY && a.M > kSkinnyMaxM) return NGEMM_ERR_INVALID_ARG;
     *kernel_out = k;
@@ -316,6 +365,8 @@ GemmParams make_params(const RunArgs &a)
     p.zb_vec = a.zb_vec;
     p.rconst = (uint32_t)(shift - a.za) * (uint32_t)B->K;
     p.relu = a.relu;
+    p.ksplit = 1;
+    p.kchunk = 0;
     return p;
 }
 
@@ -334,6 +385,15 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
     }
     hipError_t e;
     const bool dma_ok = (((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0;
+    if (kernel == NGEMM_KERNEL_SPLIT_K) {
+        // int32 outputs and aligned rows of A only; what it cannot serve goes to the 64 x 64 tiles
+        // (to the streaming kernel when M <= 32)
+        int kchunk = 0;
+        const int parts = (!a.requant && dma_ok) ? splitk_parts(a.M, B->N, B->K, num_cus, &kchunk) : 1;
+        if (parts >= 2)
+            return launch_tile_deep_splitk(p, parts, kchunk, num_cus, st) == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
+        kernel = a.M <= kSkinnyMaxM ? NGEMM_KERNEL_SKINNY : NGEMM_KERNEL_TILE_64;
+    }
     switch (kernel) {
     case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, num_cus, st); break;
     // direct-to-LDS copies need 16-byte aligned rows of A; the register-staged kernels take the rest
@@ -489,15 +549,22 @@ ngemm_status ngemm_tune_u8s8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev,
         (void)hipEventDestroy(e0);
         return NGEMM_ERR_DEVICE;
     }
-    const int candidates[4] = {NGEMM_KERNEL_SKINNY, NGEMM_KERNEL_TILE_64, NGEMM_KERNEL_TILE_128, NGEMM_KERNEL_TILE_256};
+    const int candidates[5] = {NGEMM_KERNEL_SKINNY, NGEMM_KERNEL_TILE_64, NGEMM_KERNEL_TILE_128, NGEMM_KERNEL_TILE_256,
+                               NGEMM_KERNEL_SPLIT_K};
     int best = NGEMM_KERNEL_AUTO;
     float best_ms = 0.0f;
     s = NGEMM_OK;
-    for (int c = 0; c < 4 && s == NGEMM_OK; ++c) {
+    for (int c = 0; c < 5 && s == NGEMM_OK; ++c) {
         const int k = candidates[c];
         if (k == NGEMM_KERNEL_SKINNY && M > kSkinnyMaxM) continue;
         // a tile far larger than the output cannot win: skip what would leave most of it empty
         if (k == NGEMM_KERNEL_TILE_256 && (M <= 64 || B->N <= 64)) continue;
+        if (k == NGEMM_KERNEL_SPLIT_K) {
+            // only where it would really split (else it is the 64 x 64 candidate once more)
+            int kchunk = 0;
+            const bool dma_ok = (((uintptr_t)A_dev | (uintptr_t)lda) & 15) == 0;
+            if (!dma_ok || splitk_parts(M, B->N, B->K, workgroup_budget(ctx), &kchunk) < 2) continue;
+        }
         ctx->force_kernel = k;
         // three rounds of 50 launches after a warm-up, the fastest round counts: short kernels are
         // within the noise of one another otherwise (clock ramp, first-touch effects)
@@ -818,7 +885,9 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
     // Rows of both operands 16-byte aligned and an output that takes a tile kernel: no pack pass.
     // The tile kernel reads B from the caller's storage with the same copies as A; only the column
     // sums are computed beforehand (the row-sum kernel applied to B's [N x K] storage).
-    int kernel = ctx->force_kernel == NGEMM_KERNEL_AUTO ? choose_kernel(ctx, M, N) : ctx->force_kernel;
+    int kernel = ctx->force_kernel == NGEMM_KERNEL_AUTO ? choose_kernel(ctx, M, N, K) : ctx->force_kernel;
+    if (kernel == NGEMM_KERNEL_SPLIT_K)                                     // the K split reads a packed B only
+        kernel = M <= kSkinnyMaxM ? NGEMM_KERNEL_SKINNY : NGEMM_KERNEL_TILE_64;
     const bool aligned = (((uintptr_t)A_dev | (uintptr_t)lda | (uintptr_t)B_dev | (uintptr_t)ldb) & 15) == 0;
     if (aligned && K > 0 && kernel != NGEMM_KERNEL_SKINNY) {
         DeviceGuard g(ctx->device);

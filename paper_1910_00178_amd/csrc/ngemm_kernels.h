@@ -51,6 +51,9 @@ struct GemmParams {
     // operand type of A: 0x80808080 for unsigned bytes (shifted to signed by xor), 0 for signed
     // bytes (used as they are; za_term and rconst are then -za and -za*K)
     uint32_t a_xor;
+    // K split over workgroups (gemm_tile_deep_kernel, SPLITK form): unit u of the grid is tile
+    // u % ntiles, bytes [kchunk * (u / ntiles), + kchunk) of K; kchunk is a multiple of 256
+    int ksplit, kchunk;
 };
 
 // ---- small helpers -------------------------------------------------------------------------
@@ -167,6 +170,18 @@ __global__ __launch_bounds__(256) void zero_i32_kernel(int32_t *__restrict__ dst
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i < n) dst[i] = 0;
+}
+
+// Clears the M x N int32 outputs of C (row pitch ldc; the gaps between rows are left alone):
+// workgroup u covers 1024 columns of row u / segs.
+__global__ __launch_bounds__(256) void zero_c_kernel(int32_t *__restrict__ C, int64_t ldc, int N, int segs)
+{
+    const int row = blockIdx.x / segs, seg = blockIdx.x - row * segs;
+    const int col = seg * 1024 + threadIdx.x * 4;
+    int32_t *dst = C + (int64_t)row * ldc + col;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        if (col + t < N) dst[t] = 0;
 }
 
 __global__ __launch_bounds__(256) void pack_b_kernel(const int8_t *__restrict__ B, int64_t ldb, int K, int N,
@@ -343,7 +358,29 @@ __device__ __forceinline__ int xpose_off(int r, int c)
 template <int TN>
 constexpr int kXposeBytes = 32 * (TN * 128 + 16);      // per wavefront
 
-template <int TM, int TN, int BN, bool REQUANT, bool SMALLZC = false>
+// Four int32 outputs: stored, or (ATOMIC) added to what memory holds.  Integer addition mod 2^32 is
+// associative and commutative, so partial sums over parts of K may arrive in any order and the result
+// stays the exact one (the argument of Sec. 2.1 for reordering the additions).
+template <bool ATOMIC>
+__device__ __forceinline__ void put4(int32_t *dst, const v4i &v)
+{
+    if (ATOMIC) {
+        __hip_atomic_fetch_add(dst + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(dst + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(dst + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(dst + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        __builtin_memcpy(dst, &v, 16);               // 4-byte aligned is enough
+    }
+}
+template <bool ATOMIC>
+__device__ __forceinline__ void put1(int32_t *dst, int32_t v)
+{
+    if (ATOMIC) __hip_atomic_fetch_add(dst, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *dst = v;
+}
+
+template <int TM, int TN, int BN, bool REQUANT, bool SMALLZC = false, bool ATOMIC = false>
 __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[TM][TN], int m0, int n0, int wm,
                                               int wn, int lane, int tid, int nthreads, uint8_t *xpose,
                                               uint32_t *cterm_lds)
@@ -434,7 +471,20 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
             // read the block row back row-wise, add the column terms, store full lines
             const int brow0 = m0 + (wm * TM + i) * 32;
             int32_t *dst0 = (int32_t *)p.C + (int64_t)(brow0 + lane / LPR) * p.ldc + bcol;
-            if (interior) {
+            if (ATOMIC) {
+                // one instruction covers whole rows of the block row (consecutive lanes, consecutive
+                // columns): an atomic request is served per cache line, at the memory side
+                constexpr int W = TN * 32, RPI = 64 / W;
+                const int gcol = n0 + wn * W + lane % W;
+                const uint32_t ct1 = gcol < p.N ? p.za_term * (uint32_t)p.colsum[gcol] : 0u;
+#pragma unroll
+                for (int pass = 0; pass < 32 / RPI; ++pass) {
+                    const int r = RPI * pass + lane / W;
+                    const uint32_t v = *(const uint32_t *)(xpose + xpose_off<TN>(r, 0) + (lane % W) * 4) + ct1;
+                    if (brow0 + r < p.M && gcol < p.N)
+                        put1<true>((int32_t *)p.C + (int64_t)(brow0 + r) * p.ldc + gcol, (int32_t)v);
+                }
+            } else if (interior) {
                 // no predicates: all LDS reads first, then all stores
                 v4i o[NPASS];
 #pragma unroll
@@ -446,7 +496,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
                     v4i v = o[pass];
                     v.x = (int)((uint32_t)v.x + ct_back.x); v.y = (int)((uint32_t)v.y + ct_back.y);
                     v.z = (int)((uint32_t)v.z + ct_back.z); v.w = (int)((uint32_t)v.w + ct_back.w);
-                    __builtin_memcpy(dst0 + (int64_t)(RPP * pass) * p.ldc, &v, 16);   // 4-byte aligned is enough
+                    put4<ATOMIC>(dst0 + (int64_t)(RPP * pass) * p.ldc, v);
                 }
             } else {
 #pragma unroll
@@ -458,11 +508,11 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
                     if (brow0 + r < p.M && bcol < p.N) {
                         int32_t *dst = dst0 + (int64_t)(RPP * pass) * p.ldc;
                         if (bcol + 3 < p.N) {
-                            __builtin_memcpy(dst, &v, 16);
+                            put4<ATOMIC>(dst, v);
                         } else {
-                            dst[0] = v.x;
-                            if (bcol + 1 < p.N) dst[1] = v.y;
-                            if (bcol + 2 < p.N) dst[2] = v.z;
+                            put1<ATOMIC>(dst, v.x);
+                            if (bcol + 1 < p.N) put1<ATOMIC>(dst + 1, v.y);
+                            if (bcol + 2 < p.N) put1<ATOMIC>(dst + 2, v.z);
                         }
                     }
                 }
@@ -736,6 +786,8 @@ __device__ __forceinline__ GemmParams group_member_params(const GroupMember &m)
     p.rconst = m.za_term * (uint32_t)m.K;
     p.relu = 0;
     p.a_xor = 0x80808080u;
+    p.ksplit = 1;
+    p.kchunk = 0;
     return p;
 }
 
@@ -1577,7 +1629,7 @@ struct DeepCfg {
     static_assert((NSTAGE - 2) * kLoadsPerStage <= 63, "vmcnt range");
 };
 
-template <int T, int SUB, int NSTAGE, bool REQUANT>
+template <int T, int SUB, int NSTAGE, bool REQUANT, bool SPLITK = false>
 __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
 {
     using Cfg = DeepCfg<T, SUB, NSTAGE>;
@@ -1593,12 +1645,10 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
+    static_assert(!(SPLITK && REQUANT), "partial sums are added as int32");
     const int nslices = p.Kp / 32;
-    const int nsub = p.K / 64;                        // full 64-byte sub-blocks of K
-    const int nst = nsub / SUB, rem = nsub % SUB;     // full stages, sub-blocks of the partial one
-    const int nstages = nst + (rem > 0 ? 1 : 0);
-    const bool has_tail = nsub * 64 < p.Kp;
     const int ntiles = p.tiles_m * p.tiles_n;
+    const int nunits = SPLITK ? ntiles * p.ksplit : ntiles;
     const int gsz = gridDim.x, w = blockIdx.x;
 
     const int t16 = lane >> 2;
@@ -1614,7 +1664,16 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
     }
     const int b_frag_off = Cfg::kABytes + (wn * T * 2) * kFragBytes + lane * 16;
 
-    for (int tile = w; tile < ntiles; tile += gsz) {
+    for (int unit = w; unit < nunits; unit += gsz) {
+        // this unit's tile and part of K: bytes [k0, k0 + kc), k0 a multiple of 256
+        const int split = SPLITK ? unit / ntiles : 0;
+        const int tile = SPLITK ? unit - split * ntiles : unit;
+        const int k0 = SPLITK ? split * p.kchunk : 0;
+        const int kc = SPLITK ? (p.K - k0 < p.kchunk ? p.K - k0 : p.kchunk) : p.K;
+        const int nsub = kc / 64;                         // full 64-byte sub-blocks of K
+        const int nst = nsub / SUB, rem = nsub % SUB;     // full stages, sub-blocks of the partial one
+        const int nstages = nst + (rem > 0 ? 1 : 0);
+        const bool has_tail = nsub * 64 < kc;
         int tm, tn;
         tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
         const int m0 = tm * BMN, n0 = tn * BMN;
@@ -1626,11 +1685,11 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
         for (int i = 0; i < T; ++i) {
             int grow = m0 + (wave + 4 * i) * 16 + t16;
             grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
-            a_src[i] = p.A + (int64_t)grow * p.lda + a_chunk * 16;
+            a_src[i] = p.A + (int64_t)grow * p.lda + a_chunk * 16 + k0;
             const int q = wave + 4 * i;
             int pnl = n0 / 32 + (q >> 1);
             pnl = pnl < p.npanels ? pnl : p.npanels - 1; // panels past N: read a valid panel, never stored
-            b_src[i] = p.Bp + ((int64_t)pnl * nslices + (q & 1)) * kFragBytes + lane * 16;
+            b_src[i] = p.Bp + ((int64_t)pnl * nslices + k0 / 32 + (q & 1)) * kFragBytes + lane * 16;
         }
         // copy number d of stage s into ring buffer buf: sub-block d / 2T, then T blocks of A, T of B
         auto dma_one = [&](int s, int d, int buf) {
@@ -1675,7 +1734,7 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
             acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[S][idx][j], fa[S][idx][i], acc[i][j], 0, 0, 0);
         };
 
-        if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
+        if (unit != w) __syncthreads();                  // the previous tile's LDS traffic is over
 
         if (nsub > 0) {
 #pragma unroll
@@ -1748,12 +1807,12 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
 #pragma unroll
             for (int i = 0; i < T; ++i) {
                 const int q = wave + 4 * i;
-                const int valid = p.K - (kbase + a_chunk * 16);
+                const int valid = kc - (kbase + a_chunk * 16);
                 const uint8_t *src = a_src[i] + kbase;
                 v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
                 *(v4i *)(lds + q * 1024 + lane * 16) = v;
                 v4i z = {0, 0, 0, 0};
-                if (nsub * 2 + (q & 1) < nslices) z = *(const v4i *)(b_src[i] + (int64_t)nsub * (2 * kFragBytes));
+                if (k0 / 32 + nsub * 2 + (q & 1) < nslices) z = *(const v4i *)(b_src[i] + (int64_t)nsub * (2 * kFragBytes));
                 *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) = z;
             }
             __syncthreads();
@@ -1764,6 +1823,17 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
         }
 
         __syncthreads();                                 // every wavefront is done with the stage buffers
+        if (SPLITK) {
+            // the zero-point terms belong to the whole sum: the first part of K brings them
+            GemmParams pe = p;
+            if (split > 0) {
+                pe.za_term = 0u;
+                pe.kconst = 0u;
+                pe.rowsum = nullptr;
+            }
+            tile_epilogue<T, T, BMN, false, false, true>(pe, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
+                                                         (uint32_t *)(lds + 4 * kXposeBytes<T>));
+        } else
         // every practical output zero-point takes the binary32 form of the requantising arithmetic
         if (REQUANT && p.zc > -8388608 && p.zc < 8388608)
             tile_epilogue<T, T, BMN, REQUANT, true>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,

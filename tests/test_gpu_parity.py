@@ -410,6 +410,51 @@ def test_long_pipeline_small_tile_kernel(rt, oracle):
             ng.ngemm_set_max_workgroups(rt.ctx, 0)
 
 
+def test_split_k_kernel(rt, oracle):
+    """Few 64 x 64 tiles and a long K: K is cut into parts over the workgroups, C is cleared and the
+    parts add their partial tiles (bit-exact in any order).  Forced and by the heuristic; ragged
+    M, N and K (a last part that is only a tail, parts with a partial stage), zero-points on,
+    leading-dimension gaps with sentinels (the clearing must stay inside M x N), the wrap of the
+    int32 sum across parts, the signed-A entry point, and the calls it cannot serve (u8 output,
+    unaligned rows of A, short K), which must run the 64 x 64 tiles instead."""
+    ng = ng_mod()
+    rng = np.random.default_rng(83)
+    shapes = ((64, 64, 4096), (100, 70, 5000), (33, 200, 8191), (256, 256, 16384), (65, 1, 2048 + 17),
+              (40, 40, 66000), (200, 130, 2047), (64, 64, 2048), (129, 65, 12345), (500, 33, 4097), (33, 33, 262144 + 3),
+              (16, 256, 16384), (1, 64, 9000), (32, 1024, 8192 + 5), (700, 520, 8192 + 64))
+    for t, (M, N, K) in enumerate(shapes):
+        za, zb = ((0, 0), (128, 0), (255, -128), (77, 9))[t % 4]
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        p = wl.Problem(f"splitk_{M}x{N}x{K}", A, B, za=za, zb=zb, scale=float(np.float32(0.0002)), zc=31)
+        check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K, ng.NGEMM_KERNEL_AUTO), lda_pad=(-K) % 16, ldc_pad=5)
+        if t % 3 == 0:
+            check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K,), lda_pad=(-K) % 16 + 3, ldc_pad=1)   # unaligned rows
+    # the sum wraps at K = 65794 with these values, whatever the number of parts
+    for (K, b) in ((65793, -128), (65794, -128), (66312, 127)):
+        A = np.full((64, K), 255, dtype=np.uint8)
+        B = np.full((70, K), b, dtype=np.int8)
+        p = wl.Problem(f"splitk_wrap_{K}", A, B, za=0, zb=0)
+        check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K,), lda_pad=(-K) % 16)
+    # s8 x s8 through the same kernel
+    M, N, K = 70, 90, 9000 + 16
+    A = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
+    B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+    h, packed = rt.pack(B)
+    Ad = torch.from_numpy(A).cuda()
+    wsb = ng.ngemm_workspace_bytes(M, N, K)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    Cd = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+    rt.set_kernel(ng.NGEMM_KERNEL_SPLIT_K)
+    try:
+        ng.ngemm_run_s8s8s32(rt.ctx, M, Ad, K, -7, h, 11, Cd, N, ws, wsb)
+        torch.cuda.synchronize()
+    finally:
+        rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+    assert np.array_equal(Cd.cpu().numpy(), oracle.gemm_s8s8s32(A, B, -7, 11))
+    ng.ngemm_packed_b_free(h)
+
+
 def test_per_channel_epilogue(rt, oracle):
     """Per-column scales, biases and B zero-points with and without the fused ReLU, on every
     kernel, against the oracle's per-column form; ragged shapes and odd leading dimensions."""
