@@ -241,17 +241,18 @@ def main():
             entry["rotating_weights_us"] = round(ms2 * 1e3, 3)
             entry["rotating_weights_GBps"] = round(abytes / (ms2 * 1e-3) / 1e9, 1)
             entry["rotating_frac_of_hbm_peak"] = round(abytes / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-            # the same rotating GEMMs through the batched entry point, 52 independent problems per call
+            # the same rotating GEMMs through the batched entry point, 59 independent problems per call
             # (one grouped launch each): what a server with many small GEMMs in flight would issue
-            per = 52
+            per = 59
             Cb = [torch.empty((M, N), dtype=torch.int32, device="cuda") for _ in range(per)]
             batches = [ng.make_problems([(M, A_dev[(b * per + t) % 16], K, 0, 0, hs[b * per + t], Cb[t], N)
                                          for t in range(per)]) for b in range(ncopies // per)]
             seqb = [(lambda arr=arr: ng.ngemm_run_batched_u8s8s32(ctx, arr)) for arr in batches]
             msb = graph_time_ms(seqb, 6, torch) / per
-            entry["rotating_weights_batched52_us_per_gemm"] = round(msb * 1e3, 3)
-            entry["rotating_weights_batched52_GBps"] = round(abytes / (msb * 1e-3) / 1e9, 1)
-            entry["rotating_batched52_frac_of_hbm_peak"] = round(abytes / (msb * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            entry["batched_members_per_call"] = per
+            entry["rotating_weights_batched_us_per_gemm"] = round(msb * 1e3, 3)
+            entry["rotating_weights_batched_GBps"] = round(abytes / (msb * 1e-3) / 1e9, 1)
+            entry["rotating_batched_frac_of_hbm_peak"] = round(abytes / (msb * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
             for x in hs:
                 ng.ngemm_packed_b_free(x)
             ng.ngemm_packed_b_free(hb)

@@ -939,48 +939,42 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
 
 size_t ngemm_batched_workspace_bytes(int count, const ngemm_problem *problems)
 {
-    if (count <= 0 || !problems) return 0;
-    size_t total = 0;
-    for (int t = 0; t < count; ++t)
-        if (problems[t].b_zero_point != 0 && problems[t].M > 0 && problems[t].M <= kMaxDim)
-            total += rowsum_bytes(problems[t].M);
-    return total;
+    (void)count;
+    (void)problems;
+    return 0;                    // the grouped kernels form the row sums they need themselves
 }
 
 ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_problem *problems,
                                        void *workspace_dev, size_t workspace_bytes, void *hip_stream)
 {
+    (void)workspace_dev;
+    (void)workspace_bytes;
     if (!ctx_ok(ctx) || count < 0 || (count > 0 && !problems)) return NGEMM_ERR_INVALID_ARG;
-    size_t need = 0;
     for (int t = 0; t < count; ++t) {
         const ngemm_problem &q = problems[t];
         RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
         int kernel;
         ngemm_status s = validate_run(ctx, a, &kernel);
         if (s != NGEMM_OK) return s;
-        if (q.b_zero_point != 0 && q.M > 0 && q.B->N > 0 && q.B->K > 0) need += rowsum_bytes(q.M);
     }
-    if (need > 0 && !workspace_dev) return NGEMM_ERR_INVALID_ARG;
-    if (workspace_bytes < need) return NGEMM_ERR_BUFFER_TOO_SMALL;
     DeviceGuard g(ctx->device);
     if (!g.ok) return NGEMM_ERR_DEVICE;
     hipStream_t st = (hipStream_t)hip_stream;
 
     // Grouped launches: the members' parameters ride in the kernel argument block, up to
-    // kGroupMax per launch; one grid covers the row-sum units of a group, one the 64 x 64 tiles of
-    // its members with M > 32, one the panels of its skinny members.  Launch count, not
-    // arithmetic, is what a batch of small odd shapes costs.
-    GroupParams rows, tiles, skinny;
-    rows.count = tiles.count = skinny.count = 0;
-    rows.unit_start[0] = tiles.unit_start[0] = skinny.unit_start[0] = 0;
+    // kGroupMax per launch; one grid covers the 64 x 64 tiles of a group's members with M > 32, one
+    // the panels of its skinny members.  Launch count, not arithmetic, is what a batch of small odd
+    // shapes costs, so there is no launch for the row sums either: both kernels form them from the
+    // A fragments they read anyway.
+    GroupParams tiles, skinny;
+    tiles.count = skinny.count = 0;
+    tiles.unit_start[0] = skinny.unit_start[0] = 0;
     using TCfg = TileCfg<64, 64, 2, 2, 64>;
     auto flush = [&](GroupParams &gp, int which) -> hipError_t {
         if (gp.count == 0) return hipSuccess;
         const unsigned grid = (unsigned)gp.unit_start[gp.count];
         if (grid > 0) {
-            if (which == 0)
-                hipLaunchKernelGGL(rowsum_group_kernel, dim3(grid), dim3(256), 0, st, gp);
-            else if (which == 1)
+            if (which == 1)
                 hipLaunchKernelGGL((gemm_group_tile_kernel<64, 64, 2, 2, 64>), dim3(grid), dim3(256),
                                    (size_t)TCfg::kLdsBytes, st, gp);
             else {
@@ -998,7 +992,7 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
     };
     auto push = [&](GroupParams &gp, const GemmParams &p, int64_t units) {
         GroupMember &m = gp.prob[gp.count];          // the rest is rebuilt on the device
-        m.A = p.A; m.Bp = p.Bp; m.rowsum = p.rowsum; m.C = p.C;
+        m.A = p.A; m.Bp = p.Bp; m.C = p.C;
         m.lda = p.lda; m.ldc = p.ldc;
         m.M = p.M; m.N = p.N; m.K = p.K;
         m.za_term = p.za_term; m.zb = p.zb;
@@ -1006,32 +1000,11 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         ++gp.count;
     };
     constexpr int64_t kMaxGrid = 1 << 30;
-    size_t off = 0;
-    // pass 1: row sums of every member that needs them (they must precede the GEMMs that read them)
-    for (int t = 0; t < count; ++t) {
-        const ngemm_problem &q = problems[t];
-        if (!(q.b_zero_point != 0 && q.M > 0 && q.B->N > 0 && q.B->K > 0)) continue;
-        RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
-        GemmParams p = make_params(a);
-        p.rowsum = (const int32_t *)((uint8_t *)workspace_dev + off);
-        off += rowsum_bytes(q.M);
-        const int64_t units = (q.M + 3) / 4;
-        if (rows.count == kGroupMax || rows.unit_start[rows.count] + units > kMaxGrid)
-            if (flush(rows, 0) != hipSuccess) return NGEMM_ERR_DEVICE;
-        push(rows, p, units);
-    }
-    if (flush(rows, 0) != hipSuccess) return NGEMM_ERR_DEVICE;
-    // pass 2: the GEMMs
-    off = 0;
     for (int t = 0; t < count; ++t) {
         const ngemm_problem &q = problems[t];
         if (q.M == 0 || q.B->N == 0) continue;
         RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
-        GemmParams p = make_params(a);
-        if (q.b_zero_point != 0 && q.B->K > 0) {
-            p.rowsum = (const int32_t *)((uint8_t *)workspace_dev + off);
-            off += rowsum_bytes(q.M);
-        }
+        const GemmParams p = make_params(a);
         if (q.M <= kSkinnyMaxM) {
             const int64_t units = p.npanels;
             if (skinny.count == kGroupMax || skinny.unit_start[skinny.count] + units > kMaxGrid)

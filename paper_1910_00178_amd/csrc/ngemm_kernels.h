@@ -383,7 +383,7 @@ __device__ __forceinline__ void put1(int32_t *dst, int32_t v)
 template <int TM, int TN, int BN, bool REQUANT, bool SMALLZC = false, bool ATOMIC = false>
 __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[TM][TN], int m0, int n0, int wm,
                                               int wn, int lane, int tid, int nthreads, uint8_t *xpose,
-                                              uint32_t *cterm_lds)
+                                              uint32_t *cterm_lds, const uint32_t *rs_reg = nullptr)
 {
     const bool c_vec_ok = REQUANT ? ((((uintptr_t)p.C | (uintptr_t)p.ldc) & 3) == 0) : true;
     constexpr int LPR = TN * 8, RPP = 64 / LPR, NPASS = 32 / RPP;   // read-back: LPR lanes per row
@@ -412,10 +412,14 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
     for (int i = 0; i < TM; ++i) {
         const int row = m0 + (wm * TM + i) * 32 + (lane & 31);
         if (REQUANT && row >= p.M) continue;
-        uint32_t row_term = p.kconst;
-        if (p.rowsum && row < p.M) row_term -= p.zb * (uint32_t)p.rowsum[row];
+        // the row's sum_k (A[i][k] - shift): from the caller's registers (rs_reg[i], this lane's row)
+        // or from the row-sum pass
+        uint32_t rs_row = 0u;
+        if (rs_reg) rs_row = rs_reg[i];
+        else if (p.rowsum && row < p.M) rs_row = (uint32_t)p.rowsum[row];
+        const uint32_t row_term = p.kconst - p.zb * rs_row;
         // requantising path: sum_k (A[i][k] - za), multiplied per column by that column's zb
-        const uint32_t rsum = ((p.rowsum && row < p.M) ? (uint32_t)p.rowsum[row] : 0u) + p.rconst;
+        const uint32_t rsum = rs_row + p.rconst;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -522,7 +526,10 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
 }
 
 // One workgroup tile (`tile` in the XCD-aware order of tile_of_block) of the problem `p`.
-template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT>
+// ROWSUM_IN: the row sums the zero-point of B needs are formed here, from the A fragments the
+// matrix ops read anyway (a dot product with ones per word; lane l sees row l % 32 of a block, the
+// two halves of K sit in lanes l and l ^ 32), instead of being read from a pass of their own.
+template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT, bool ROWSUM_IN = false>
 __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, uint8_t *lds)
 {
     using Cfg = TileCfg<BM, BN, WGM, WGN, BK>;
@@ -600,7 +607,17 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
     // Matrix instruction with the packed operand first: lane l then holds, for row l%32 of the
     // A block, the four consecutive columns 8*(r/4) + 4*(l/32) + r%4 of the B block in
     // registers r = 4q..4q+3, so the epilogue stores 16 contiguous bytes per lane.
+    int rs[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) rs[i] = 0;
     auto mma_one = [&](int slot, int i, int j) {
+        if (ROWSUM_IN && j == 0) {
+            const v4i a = fa[slot][i];
+            rs[i] = __builtin_amdgcn_sdot4(a.x, 0x01010101, rs[i], false);
+            rs[i] = __builtin_amdgcn_sdot4(a.y, 0x01010101, rs[i], false);
+            rs[i] = __builtin_amdgcn_sdot4(a.z, 0x01010101, rs[i], false);
+            rs[i] = __builtin_amdgcn_sdot4(a.w, 0x01010101, rs[i], false);
+        }
         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
     };
 
@@ -707,13 +724,22 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
     }
 
     __syncthreads();                                   // every wavefront is done with the stage buffers
+    uint32_t rs_reg[TM];
+    if (ROWSUM_IN) {
+        // both halves of K; the zero fill of the K tail was shifted with the rest and counts as
+        // -128 per byte for an unsigned A: taken out again
+        const uint32_t pad = p.a_xor ? 128u * (uint32_t)(p.Kp - p.K) : 0u;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) rs_reg[i] = (uint32_t)(rs[i] + __shfl_xor(rs[i], 32, 64)) + pad;
+    }
+    const uint32_t *rsp = ROWSUM_IN ? rs_reg : nullptr;
     // every practical output zero-point takes the binary32 form of the requantising arithmetic
     if (REQUANT && p.zc > -8388608 && p.zc < 8388608)
         tile_epilogue<TM, TN, BN, REQUANT, true>(p, acc, m0, n0, wm, wn, lane, tid, NT, lds + wave * kXposeBytes<TN>,
-                                       (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>));
+                                       (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>), rsp);
     else
         tile_epilogue<TM, TN, BN, REQUANT, false>(p, acc, m0, n0, wm, wn, lane, tid, NT, lds + wave * kXposeBytes<TN>,
-                                       (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>));
+                                       (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>), rsp);
 }
 
 template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT>
@@ -725,16 +751,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmPar
 
 // ---- grouped launches: several independent problems in one grid -------------------------------
 // The problems' parameters travel in the kernel argument block, which holds 4 KiB: each member is
-// cut down to what cannot be derived (GroupMember, 72 bytes), so that kGroupMax of them fit, and a
+// cut down to what cannot be derived (GroupMember, 64 bytes), so that kGroupMax of them fit, and a
 // workgroup rebuilds the full parameter set of its own member with a few scalar operations.
 // unit_start[q] is the first workgroup id of problem q, unit_start[count] the grid size.  What a
-// "unit" is depends on the kernel: a 64 x 64 tile, a 32-column panel, or a group of four rows of A.
+// "unit" is depends on the kernel: a 64 x 64 tile or a 32-column panel.
 // Members are u8 x s8 -> s32 problems with per-tensor zero-points.
-constexpr int kGroupMax = 52;
+constexpr int kGroupMax = 59;
 struct GroupMember {
     const uint8_t *A;
     const uint8_t *Bp;       // packed fragments; the column sums follow them
-    const int32_t *rowsum;   // or nullptr when zb == 0
     void *C;
     int64_t lda, ldc;
     int M, N, K;
@@ -770,7 +795,7 @@ __device__ __forceinline__ GemmParams group_member_params(const GroupMember &m)
     p.Kp = (m.K + 63) & ~63;
     p.npanels = (m.N + 31) >> 5;
     p.colsum = (const int32_t *)(m.Bp + (int64_t)p.Kp * (p.npanels * 32));
-    p.rowsum = m.rowsum;
+    p.rowsum = nullptr;          // the grouped kernels form the row sums themselves
     p.C = m.C;
     p.ldc = m.ldc;
     p.tiles_m = (m.M + BM - 1) / BM;
@@ -797,7 +822,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_group_tile_kernel(const G
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int q = group_find(g, blockIdx.x);
     const GemmParams p = group_member_params<BM, BN>(g.prob[q]);
-    tile_body_staged<BM, BN, WGM, WGN, BK, false>(p, blockIdx.x - g.unit_start[q], lds);
+    tile_body_staged<BM, BN, WGM, WGN, BK, false, true>(p, blockIdx.x - g.unit_start[q], lds);
 }
 
 // ---- tiled MFMA kernel, direct-to-LDS variant -------------------------------------------------
@@ -2135,9 +2160,22 @@ __global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
 // batch of fragments ahead of the matrix ops that consume them (double buffered).  The partial
 // 32 x 32 accumulators of the wavefronts are added through LDS as whole vectors (phase 2 of
 // Sec. 3.1: vector adds, no lane tree), one panel after the other.
-template <bool REQUANT, int P>
-__device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl0, int nregs, int *red)
+// ROWSUM_IN: the row sums the zero-point of B needs are formed from the A fragments as they pass
+// (a dot product with ones per word of the bytes as loaded, before the shift, so that zero fill
+// counts as zero: lane l sees row l % 32, the two halves of a slice sit in lanes l and l ^ 32; the
+// shift of an unsigned A is K times 128, taken off in the constants).  At the end every lane
+// fetches the sums of the 16 rows its accumulator registers belong to, and each wavefront takes zb
+// times its share off its partial sums before they are added up.
+template <bool REQUANT, int P, bool ROWSUM_IN = false>
+__device__ __forceinline__ void skinny_body(const GemmParams &p0, int pnl0, int nregs, int *red)
 {
+    GemmParams p = p0;
+    if (ROWSUM_IN) {
+        const uint32_t shift_sum = p0.a_xor ? 128u * (uint32_t)p0.K : 0u;     // sum_k A' = sum_k A - this
+        p.rowsum = nullptr;
+        p.kconst = p0.kconst + p0.zb * shift_sum;
+        p.rconst = p0.rconst - shift_sum;
+    }
     constexpr int BATCH = P >= 4 ? 2 : 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = blockDim.x >> 6;
@@ -2171,6 +2209,9 @@ __device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl0, int n
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0;
 
+    int rs_lane = 0;
+    const bool want_rs = ROWSUM_IN && (p.zb != 0u || p.zb_vec != nullptr);
+
     v4i bf[2][BATCH][P], af[2][BATCH];
     const v4i zero = {0, 0, 0, 0};
     auto load_batch = [&](int slot, int t0) {
@@ -2190,6 +2231,22 @@ __device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl0, int n
 #pragma unroll
             for (int j = 0; j < P; ++j)
                 acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bf[slot][u][j], acc[j], 0, 0, 0);
+            if (want_rs) {
+                const v4i raw = af[slot][u];
+                if (p.a_xor) {
+                    uint32_t t = (uint32_t)rs_lane;
+                    t = __builtin_amdgcn_udot4((uint32_t)raw.x, 0x01010101u, t, false);
+                    t = __builtin_amdgcn_udot4((uint32_t)raw.y, 0x01010101u, t, false);
+                    t = __builtin_amdgcn_udot4((uint32_t)raw.z, 0x01010101u, t, false);
+                    t = __builtin_amdgcn_udot4((uint32_t)raw.w, 0x01010101u, t, false);
+                    rs_lane = (int)t;
+                } else {
+                    rs_lane = __builtin_amdgcn_sdot4(raw.x, 0x01010101, rs_lane, false);
+                    rs_lane = __builtin_amdgcn_sdot4(raw.y, 0x01010101, rs_lane, false);
+                    rs_lane = __builtin_amdgcn_sdot4(raw.z, 0x01010101, rs_lane, false);
+                    rs_lane = __builtin_amdgcn_sdot4(raw.w, 0x01010101, rs_lane, false);
+                }
+            }
         }
     };
     if (mine > 0) load_batch(0, 0);
@@ -2199,6 +2256,20 @@ __device__ __forceinline__ void skinny_body(const GemmParams &p, int pnl0, int n
         if (t0 + BATCH < mine) {
             if (t0 + 2 * BATCH < mine) load_batch(0, t0 + 2 * BATCH);
             mma_batch(1);
+        }
+    }
+
+    if (want_rs) {
+        const int rs_row = rs_lane + __shfl_xor(rs_lane, 32, 64);      // this wavefront's share, row lane % 32
+        uint32_t rs_out[16];                                          // ... of the row of accumulator register r
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rs_out[r] = (uint32_t)__shfl(rs_row, 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), 64);
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            const int col = (pnl0 + j) * 32 + (lane & 31);
+            const uint32_t zbj = (p.zb_vec && col < p.N) ? (uint32_t)p.zb_vec[col] : p.zb;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = (int)((uint32_t)acc[j][r] - zbj * rs_out[r]);
         }
     }
 
@@ -2243,19 +2314,7 @@ __global__ __launch_bounds__(512) void gemm_group_skinny_kernel(const GroupParam
     extern __shared__ int red[];
     const int q = group_find(g, blockIdx.x);
     const GemmParams p = group_member_params<64, 64>(g.prob[q]);
-    skinny_body<false, 1>(p, blockIdx.x - g.unit_start[q], 4 * ((p.M + 7) / 8), red);
-}
-
-// Grouped row sums: unit = four rows of A of one problem.
-__global__ __launch_bounds__(256) void rowsum_group_kernel(const GroupParams g)
-{
-    const int q = group_find(g, blockIdx.x);
-    const GroupMember &p = g.prob[q];
-    const int i = (blockIdx.x - g.unit_start[q]) * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (i >= p.M) return;
-    const int s = row_sum_shifted(p.A + (int64_t)i * p.lda, p.K, lane, 0x80808080u);
-    if (lane == 0) ((int32_t *)p.rowsum)[i] = s;
+    skinny_body<false, 1, true>(p, blockIdx.x - g.unit_start[q], 4 * ((p.M + 7) / 8), red);
 }
 
 }  // namespace ngemm
