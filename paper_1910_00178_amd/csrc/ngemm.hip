@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime.h>
 #include <cmath>
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -1000,22 +1001,38 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         ++gp.count;
     };
     constexpr int64_t kMaxGrid = 1 << 30;
+    // Members with the longest K first: a workgroup's time grows with K, and the grid is handed out
+    // in order, so the long ones start at once and the many short ones fill in around them.
+    struct Pending { GemmParams p; int64_t units; };
+    std::vector<Pending> tile_members, skinny_members;
+    try {
+        tile_members.reserve((size_t)count);
+        skinny_members.reserve((size_t)count);
+    } catch (...) {
+        return NGEMM_ERR_DEVICE;                   // out of host memory; nothing was launched
+    }
     for (int t = 0; t < count; ++t) {
         const ngemm_problem &q = problems[t];
         if (q.M == 0 || q.B->N == 0) continue;
         RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
         const GemmParams p = make_params(a);
-        if (q.M <= kSkinnyMaxM) {
-            const int64_t units = p.npanels;
-            if (skinny.count == kGroupMax || skinny.unit_start[skinny.count] + units > kMaxGrid)
-                if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
-            push(skinny, p, units);
-        } else {
-            const int64_t units = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
-            if (tiles.count == kGroupMax || tiles.unit_start[tiles.count] + units > kMaxGrid)
-                if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
-            push(tiles, p, units);
-        }
+        if (q.M <= kSkinnyMaxM)
+            skinny_members.push_back(Pending{p, p.npanels});
+        else
+            tile_members.push_back(Pending{p, (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64)});
+    }
+    auto longer_k = [](const Pending &x, const Pending &y) { return x.p.K > y.p.K; };
+    std::stable_sort(tile_members.begin(), tile_members.end(), longer_k);
+    std::stable_sort(skinny_members.begin(), skinny_members.end(), longer_k);
+    for (const Pending &m : tile_members) {
+        if (tiles.count == kGroupMax || tiles.unit_start[tiles.count] + m.units > kMaxGrid)
+            if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
+        push(tiles, m.p, m.units);
+    }
+    for (const Pending &m : skinny_members) {
+        if (skinny.count == kGroupMax || skinny.unit_start[skinny.count] + m.units > kMaxGrid)
+            if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
+        push(skinny, m.p, m.units);
     }
     if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
     if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;

@@ -525,11 +525,30 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
     }
 }
 
+// compile-time integer as a function argument (register-set selectors of the kernels below)
+template <int V>
+struct IntC {
+    static constexpr int value = V;
+};
+// f(IntC<U>), f(IntC<U + 1>), ..., f(IntC<R - 1>)
+template <int U, int R, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (U < R) {
+        f(IntC<U>{});
+        static_for<U + 1, R>(f);
+    }
+}
+
 // One workgroup tile (`tile` in the XCD-aware order of tile_of_block) of the problem `p`.
+// RING > 1: the stages on their way from memory wait in a ring of RING register sets (stage s in set
+// s % RING) instead of one, so RING loads are in flight per lane: a tile that is alone with a long K
+// is bound by the latency of one load per stage otherwise.  Costs RING * (chunks per lane) * 4
+// registers.
 // ROWSUM_IN: the row sums the zero-point of B needs are formed here, from the A fragments the
 // matrix ops read anyway (a dot product with ones per word; lane l sees row l % 32 of a block, the
 // two halves of K sit in lanes l and l ^ 32), instead of being read from a pass of their own.
-template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT, bool ROWSUM_IN = false>
+template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT, bool ROWSUM_IN = false, int RING = 1>
 __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, uint8_t *lds)
 {
     using Cfg = TileCfg<BM, BN, WGM, WGN, BK>;
@@ -621,6 +640,86 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
     };
 
+    if constexpr (RING > 1) {
+        v4i qa[RING][AI], qb[RING][BI];
+        auto qload = [&](auto set, int kt) {
+            constexpr int S = decltype(set)::value;
+            const int k = kt < nfull ? kt : nfull - 1;  // past the end: the last stage again, never consumed
+#pragma unroll
+            for (int i = 0; i < AI; ++i) qa[S][i] = load16_any(a_src[i] + (int64_t)k * BK);
+#pragma unroll
+            for (int i = 0; i < BI; ++i) qb[S][i] = *(const v4i *)(b_src[i] + (int64_t)k * (KS * kFragBytes));
+        };
+        auto qstore_a = [&](auto set, int i, int buf) {
+            constexpr int S = decltype(set)::value;
+            *(v4i *)(lds + buf * Cfg::kStageBytes + a_dst[i]) = shift_u8_to_s8(qa[S][i], p.a_xor);
+        };
+        auto qstore_b = [&](auto set, int i, int buf) {
+            constexpr int S = decltype(set)::value;
+            *(v4i *)(lds + buf * Cfg::kStageBytes + Cfg::kABytes + (tid + i * NT) * 16) = qb[S][i];
+        };
+        if (nfull > 0) {
+            qload(IntC<0>{}, 0);
+#pragma unroll
+            for (int i = 0; i < AI; ++i) qstore_a(IntC<0>{}, i, 0);
+#pragma unroll
+            for (int i = 0; i < BI; ++i) qstore_b(IntC<0>{}, i, 0);
+            // stages 1 .. RING on their way
+            static_for<1, RING>([&](auto set) { qload(set, decltype(set)::value); });
+            qload(IntC<0>{}, RING);
+            lds_barrier();
+            read_frags(0, 0, 0);
+        }
+        // stage kt: its matrix ops, while stage kt + 1 (register set SET) goes to the other LDS
+        // buffer and stage kt + 1 + RING is requested into the same set
+        auto stage = [&](int kt, auto set) {
+            const int cur = kt & 1, nxt = cur ^ 1;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) {
+                    read_frags(cur, ks + 1, (ks + 1) & 1);
+                } else {
+                    lds_barrier();                      // next stage is complete in LDS[nxt]
+                    read_frags(nxt, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (ks == 0) {
+                    constexpr int NM = TM * TN;
+#pragma unroll
+                    for (int m = 0; m < NM; ++m) {
+                        mma_one(0, m / TN, m % TN);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (m == NM - 1) {
+#pragma unroll
+                            for (int i = 0; i < AI; ++i) qstore_a(set, i, nxt);
+#pragma unroll
+                            for (int i = 0; i < BI; ++i) qstore_b(set, i, nxt);
+                            qload(set, kt + 1 + RING);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) mma_one(ks & 1, i, j);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        // whole rounds of the ring without a branch inside (the pending-load counts the compiler
+        // derives stay exact: RING - 1 sets in flight at every store), then the remainder
+        int kt = 0;
+        for (; kt + RING <= nfull; kt += RING)
+            static_for<0, RING>([&](auto u) {
+                constexpr int U = decltype(u)::value;
+                stage(kt + U, IntC<(U + 1) % RING>{});
+            });
+        static_for<0, RING - 1>([&](auto u) {
+            constexpr int U = decltype(u)::value;
+            if (kt + U < nfull) stage(kt + U, IntC<(U + 1) % RING>{});
+        });
+    } else {
     if (nfull > 0) {
 #pragma unroll
         for (int i = 0; i < AI; ++i) gload_a(i, 0);
@@ -690,6 +789,7 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    }
 
     // K tail: the last, partial stage (K not a multiple of BK).  Guarded loads, no pipelining.
     if (has_tail) {
@@ -728,7 +828,7 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
     if (ROWSUM_IN) {
         // both halves of K; the zero fill of the K tail was shifted with the rest and counts as
         // -128 per byte for an unsigned A: taken out again
-        const uint32_t pad = p.a_xor ? 128u * (uint32_t)(p.Kp - p.K) : 0u;
+        const uint32_t pad = p.a_xor ? 128u * (uint32_t)((nfull + (has_tail ? 1 : 0)) * BK - p.K) : 0u;
 #pragma unroll
         for (int i = 0; i < TM; ++i) rs_reg[i] = (uint32_t)(rs[i] + __shfl_xor(rs[i], 32, 64)) + pad;
     }
@@ -816,13 +916,17 @@ __device__ __forceinline__ GemmParams group_member_params(const GroupMember &m)
     return p;
 }
 
+// Register ring of the grouped tile kernel: with four sets the batch of 64 odd shapes takes 28.8 us,
+// with one 34.8 (a long-K member's loads no longer wait behind the other members' traffic); stages
+// of 128 bytes instead of 64 gain nothing.
+constexpr int kGroupRing = 4;
 template <int BM, int BN, int WGM, int WGN, int BK>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_group_tile_kernel(const GroupParams g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int q = group_find(g, blockIdx.x);
     const GemmParams p = group_member_params<BM, BN>(g.prob[q]);
-    tile_body_staged<BM, BN, WGM, WGN, BK, false, true>(p, blockIdx.x - g.unit_start[q], lds);
+    tile_body_staged<BM, BN, WGM, WGN, BK, false, true, kGroupRing>(p, blockIdx.x - g.unit_start[q], lds);
 }
 
 // ---- tiled MFMA kernel, direct-to-LDS variant -------------------------------------------------
@@ -1123,12 +1227,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
                                            lds + wave * kXposeBytes<TN>, (uint32_t *)(lds + NW * kXposeBytes<TN>));
     }
 }
-
-// compile-time integer as a function argument (register-set selectors of the kernels below)
-template <int V>
-struct IntC {
-    static constexpr int value = V;
-};
 
 // ---- 256 x 256 tiles on the 16 x 16 x 64 matrix instruction ------------------------------------
 // The same tiling as gemm_tile_dma_kernel<256,256,2,2,4> (rings and copies of its own, below).  On
