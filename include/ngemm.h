@@ -304,13 +304,16 @@ typedef struct ngemm_problem {
     int64_t ldc;
 } ngemm_problem;
 
-/* Workspace for a batch: the sum of the members' needs (each rounded to 256 bytes). */
+/* Workspace for a batch: 0 (the grouped kernels form the row sums a weight zero-point needs
+ * themselves); kept so that callers size the argument of the run call by it. */
 size_t ngemm_batched_workspace_bytes(int count, const ngemm_problem *problems);
 
 /*
  * Run `count` independent int32-output GEMMs (arbitrary shapes, per-GEMM
  * zero-points) on one stream.  All members are validated before anything is
- * launched.  Results are those of `count` calls of ngemm_run_u8s8s32.
+ * launched.  Results are those of `count` calls of ngemm_run_u8s8s32.  The members run in
+ * grouped launches (one grid for the tiles of all members with M > 32, one for the panels of
+ * the others, at most 59 members per grid); workspace_dev may be NULL.
  */
 ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_problem *problems,
                                        void *workspace_dev, size_t workspace_bytes,
