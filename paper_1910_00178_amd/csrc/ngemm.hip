@@ -377,7 +377,16 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
     const ngemm_packed_b *B = a.B;
     if (a.M == 0 || B->N == 0) return NGEMM_OK;
     GemmParams p = make_params(a);
-    if (a.needs_rowsum() && B->K > 0) {
+    const bool dma_ok = (((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0;
+    int kchunk = 0, parts = 1;
+    if (kernel == NGEMM_KERNEL_SPLIT_K) {
+        // int32 outputs and aligned rows of A only; what it cannot serve goes to the 64 x 64 tiles
+        // (to the streaming kernel when M <= 32)
+        parts = (!a.requant && dma_ok) ? splitk_parts(a.M, B->N, B->K, num_cus, &kchunk) : 1;
+        if (parts < 2) kernel = a.M <= kSkinnyMaxM ? NGEMM_KERNEL_SKINNY : NGEMM_KERNEL_TILE_64;
+    }
+    // the streaming kernel forms the row sums itself; the others read them from a pass of their own
+    if (a.needs_rowsum() && B->K > 0 && kernel != NGEMM_KERNEL_SKINNY) {
         int32_t *rs = (int32_t *)ws;
         hipLaunchKernelGGL(rowsum_a_kernel, dim3((unsigned)((a.M + 3) / 4)), dim3(256), 0, st, a.A, a.lda,
                            (int)a.M, (int)B->K, p.a_xor, rs);
@@ -385,16 +394,8 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
         p.rowsum = rs;
     }
     hipError_t e;
-    const bool dma_ok = (((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0;
-    if (kernel == NGEMM_KERNEL_SPLIT_K) {
-        // int32 outputs and aligned rows of A only; what it cannot serve goes to the 64 x 64 tiles
-        // (to the streaming kernel when M <= 32)
-        int kchunk = 0;
-        const int parts = (!a.requant && dma_ok) ? splitk_parts(a.M, B->N, B->K, num_cus, &kchunk) : 1;
-        if (parts >= 2)
-            return launch_tile_deep_splitk(p, parts, kchunk, num_cus, st) == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
-        kernel = a.M <= kSkinnyMaxM ? NGEMM_KERNEL_SKINNY : NGEMM_KERNEL_TILE_64;
-    }
+    if (kernel == NGEMM_KERNEL_SPLIT_K)
+        return launch_tile_deep_splitk(p, parts, kchunk, num_cus, st) == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
     switch (kernel) {
     case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, num_cus, st); break;
     // direct-to-LDS copies need 16-byte aligned rows of A; the register-staged kernels take the rest

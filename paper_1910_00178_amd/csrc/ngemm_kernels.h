@@ -2402,7 +2402,7 @@ template <bool REQUANT, int P>
 __global__ __launch_bounds__(512) void gemm_skinny_kernel(const GemmParams p, int nregs)
 {
     extern __shared__ int red[];                       // [nwaves][nregs][64]
-    skinny_body<REQUANT, P>(p, blockIdx.x * P, nregs, red);
+    skinny_body<REQUANT, P, true>(p, blockIdx.x * P, nregs, red);     // row sums formed here: no pass before it
 }
 
 // Grouped form: unit = one 32-column panel of one problem; always 8 wavefronts and room for 16
