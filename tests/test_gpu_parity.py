@@ -763,7 +763,9 @@ def test_hip_graph_replays(rt, oracle):
     replay checked against the oracle with fresh input contents."""
     ng = ng_mod()
     rng = np.random.default_rng(92)
-    cases = [(4, 4096, 1024, 0, 0), (300, 200, 500, 17, -3), (700, 520, 1024, 128, 0)]
+    # the last two take the K split for the int32 output (C cleared and added to on every replay)
+    cases = [(4, 4096, 1024, 0, 0), (300, 200, 500, 17, -3), (700, 520, 1024, 128, 0), (100, 70, 8192, 9, 5),
+             (16, 256, 16384, 3, -2)]
     bufs = []
     for (M, N, K, za, zb) in cases:
         B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
