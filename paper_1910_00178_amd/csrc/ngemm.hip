@@ -157,8 +157,9 @@ constexpr int kDeepStages = 4;
 template <int T>
 constexpr int kDeepSub = T == 1 ? 4 : 2;
 
+// `rows`: the kernel forms the row sums itself (a zero-point of B is there; no row-sum pass ran)
 template <int T>
-hipError_t launch_tile_deep(const GemmParams &p0, bool requant, int num_cus, hipStream_t st)
+hipError_t launch_tile_deep(const GemmParams &p0, bool requant, bool rows, int num_cus, hipStream_t st)
 {
     using Cfg = DeepCfg<T, kDeepSub<T>, kDeepStages>;
     GemmParams p = p0;
@@ -166,8 +167,12 @@ hipError_t launch_tile_deep(const GemmParams &p0, bool requant, int num_cus, hip
     p.tiles_n = (p.N + Cfg::BMN - 1) / Cfg::BMN;
     const int ntiles = p.tiles_m * p.tiles_n;
     dim3 grid((unsigned)(ntiles < num_cus ? ntiles : num_cus)), block(256);
-    if (requant)
+    if (requant && rows)
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true, false, true>), grid, block, Cfg::kLdsBytes, st, p);
+    else if (requant)
         hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true>), grid, block, Cfg::kLdsBytes, st, p);
+    else if (rows)
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false, false, true>), grid, block, Cfg::kLdsBytes, st, p);
     else
         hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false>), grid, block, Cfg::kLdsBytes, st, p);
     return hipGetLastError();
@@ -189,7 +194,7 @@ int splitk_parts(int64_t M, int64_t N, int64_t K, int num_cus, int *kchunk)
     return (int)((K + chunk - 1) / chunk);         // every part holds at least one byte of K
 }
 
-hipError_t launch_tile_deep_splitk(const GemmParams &p0, int parts, int kchunk, int num_cus, hipStream_t st)
+hipError_t launch_tile_deep_splitk(const GemmParams &p0, int parts, int kchunk, bool rows, int num_cus, hipStream_t st)
 {
     using Cfg = DeepCfg<1, kDeepSub<1>, kDeepStages>;
     GemmParams p = p0;
@@ -203,7 +208,10 @@ hipError_t launch_tile_deep_splitk(const GemmParams &p0, int parts, int kchunk, 
     if (e != hipSuccess) return e;
     const int nunits = p.tiles_m * p.tiles_n * parts;
     dim3 grid((unsigned)(nunits < num_cus ? nunits : num_cus)), block(256);
-    hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true>), grid, block, Cfg::kLdsBytes, st, p);
+    if (rows)
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true, true>), grid, block, Cfg::kLdsBytes, st, p);
+    else
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true>), grid, block, Cfg::kLdsBytes, st, p);
     return hipGetLastError();
 }
 
@@ -211,16 +219,19 @@ template <int T>
 hipError_t allow_big_lds_deep()
 {
     using Cfg = DeepCfg<T, kDeepSub<T>, kDeepStages>;
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
-    if (e != hipSuccess) return e;
-    if (T == 1) {
-        e = hipFuncSetAttribute((const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    const void *forms[] = {
+        (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false>,
+        (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true>,
+        (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false, false, true>,
+        (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true, false, true>,
+        (const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true>,
+        (const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true, true>,
+    };
+    for (const void *f : forms) {
+        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
         if (e != hipSuccess) return e;
     }
-    return hipFuncSetAttribute((const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    return hipSuccess;
 }
 
 template <int P>
@@ -385,8 +396,16 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
         parts = (!a.requant && dma_ok) ? splitk_parts(a.M, B->N, B->K, num_cus, &kchunk) : 1;
         if (parts < 2) kernel = a.M <= kSkinnyMaxM ? NGEMM_KERNEL_SKINNY : NGEMM_KERNEL_TILE_64;
     }
-    // the streaming kernel forms the row sums itself; the others read them from a pass of their own
-    if (a.needs_rowsum() && B->K > 0 && kernel != NGEMM_KERNEL_SKINNY) {
+    // at most one tile per compute unit and a K worth pipelining: the long-pipeline variants
+    const bool deep64 = kernel == NGEMM_KERNEL_TILE_64 && dma_ok && B->K >= 512 &&
+                        ((a.M + 63) / 64) * ((B->N + 63) / 64) <= (int64_t)device_cus;
+    const bool deep128 = kernel == NGEMM_KERNEL_TILE_128 && dma_ok && B->K >= 512 &&
+                         ((a.M + 127) / 128) * ((B->N + 127) / 128) <= (int64_t)device_cus;
+    // the streaming kernel and the long-pipeline kernels (the K split is one) form the row sums
+    // themselves; the others read them from a pass of their own
+    const bool rows_in_kernel = kernel == NGEMM_KERNEL_SKINNY || kernel == NGEMM_KERNEL_SPLIT_K || deep64 || deep128;
+    const bool rows_needed = a.needs_rowsum() && B->K > 0;
+    if (rows_needed && !rows_in_kernel) {
         int32_t *rs = (int32_t *)ws;
         hipLaunchKernelGGL(rowsum_a_kernel, dim3((unsigned)((a.M + 3) / 4)), dim3(256), 0, st, a.A, a.lda,
                            (int)a.M, (int)B->K, p.a_xor, rs);
@@ -395,21 +414,20 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
     }
     hipError_t e;
     if (kernel == NGEMM_KERNEL_SPLIT_K)
-        return launch_tile_deep_splitk(p, parts, kchunk, num_cus, st) == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
+        return launch_tile_deep_splitk(p, parts, kchunk, rows_needed, num_cus, st) == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
     switch (kernel) {
     case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, num_cus, st); break;
     // direct-to-LDS copies need 16-byte aligned rows of A; the register-staged kernels take the rest
     case NGEMM_KERNEL_TILE_64:
-        // at most one tile per compute unit and a K worth pipelining: the long-pipeline variant
-        if (dma_ok && B->K >= 512 && ((a.M + 63) / 64) * ((B->N + 63) / 64) <= (int64_t)device_cus)
-            e = launch_tile_deep<1>(p, a.requant, num_cus, st);
+        if (deep64)
+            e = launch_tile_deep<1>(p, a.requant, rows_needed, num_cus, st);
         else
             e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st)
                        : launch_tile<64, 64, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_128:
-        if (dma_ok && B->K >= 512 && ((a.M + 127) / 128) * ((B->N + 127) / 128) <= (int64_t)device_cus)
-            e = launch_tile_deep<2>(p, a.requant, num_cus, st);
+        if (deep128)
+            e = launch_tile_deep<2>(p, a.requant, rows_needed, num_cus, st);
         else
             e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st)
                        : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);

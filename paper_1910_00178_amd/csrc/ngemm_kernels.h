@@ -1752,7 +1752,10 @@ struct DeepCfg {
     static_assert((NSTAGE - 2) * kLoadsPerStage <= 63, "vmcnt range");
 };
 
-template <int T, int SUB, int NSTAGE, bool REQUANT, bool SPLITK = false>
+// ROWS: form the row sums a zero-point of B needs here (four more vector instructions per A fragment:
+// 8 % to 28 % on the T = 1 form, whose wavefronts are bound by instruction issue, so the host picks
+// this form only when the zero-point is there; it then saves the launch of the row-sum pass).
+template <int T, int SUB, int NSTAGE, bool REQUANT, bool SPLITK = false, bool ROWS = false>
 __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
 {
     using Cfg = DeepCfg<T, SUB, NSTAGE>;
@@ -1850,11 +1853,24 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
         // matrix op m of step idx; packed operand first, as in the kernels above (the epilogue
         // expects that register layout).  The u8 -> s8 shift of an A fragment precedes its first use.
+        int rs[T];                                      // this lane's share of the row sums (row lane % 32 of block i)
+#pragma unroll
+        for (int i = 0; i < T; ++i) rs[i] = 0;
         auto mma = [&](auto set, int idx, int m) {
             constexpr int S = decltype(set)::value;
             const int i = m / T, j = m % T;
             if (j == 0) fa[S][idx][i] = shift_u8_to_s8(fa[S][idx][i], p.a_xor);
             acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[S][idx][j], fa[S][idx][i], acc[i][j], 0, 0, 0);
+            if (ROWS && j == 0) {
+                // the row sums a zero-point of B needs, from the fragments as they pass; issued behind
+                // the matrix op, whose passes they overlap
+                __builtin_amdgcn_sched_barrier(0);
+                const v4i a = fa[S][idx][i];
+                rs[i] = __builtin_amdgcn_sdot4(a.x, 0x01010101, rs[i], false);
+                rs[i] = __builtin_amdgcn_sdot4(a.y, 0x01010101, rs[i], false);
+                rs[i] = __builtin_amdgcn_sdot4(a.z, 0x01010101, rs[i], false);
+                rs[i] = __builtin_amdgcn_sdot4(a.w, 0x01010101, rs[i], false);
+            }
         };
 
         if (unit != w) __syncthreads();                  // the previous tile's LDS traffic is over
@@ -1946,24 +1962,33 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
         }
 
         __syncthreads();                                 // every wavefront is done with the stage buffers
+        // Row sums over this unit's part of K: the two halves of each 32-byte step sit in lanes l and
+        // l ^ 32; the zero fill of the K tail was shifted with the rest and counts as -128 per byte
+        // for an unsigned A, which is taken out again.
+        uint32_t rs_reg[T];
+        {
+            const uint32_t pad = (p.a_xor && has_tail) ? 128u * (uint32_t)((nsub + 1) * 64 - kc) : 0u;
+#pragma unroll
+            for (int i = 0; i < T; ++i) rs_reg[i] = (uint32_t)(rs[i] + __shfl_xor(rs[i], 32, 64)) + pad;
+        }
         if (SPLITK) {
-            // the zero-point terms belong to the whole sum: the first part of K brings them
+            // the column and constant terms belong to the whole sum: the first part of K brings
+            // them; the row term is linear in the row sum, so every part takes its own share
             GemmParams pe = p;
             if (split > 0) {
                 pe.za_term = 0u;
                 pe.kconst = 0u;
-                pe.rowsum = nullptr;
             }
             tile_epilogue<T, T, BMN, false, false, true>(pe, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
-                                                         (uint32_t *)(lds + 4 * kXposeBytes<T>));
+                                                         (uint32_t *)(lds + 4 * kXposeBytes<T>), ROWS ? rs_reg : nullptr);
         } else
         // every practical output zero-point takes the binary32 form of the requantising arithmetic
         if (REQUANT && p.zc > -8388608 && p.zc < 8388608)
             tile_epilogue<T, T, BMN, REQUANT, true>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
-                                          (uint32_t *)(lds + 4 * kXposeBytes<T>));
+                                          (uint32_t *)(lds + 4 * kXposeBytes<T>), ROWS ? rs_reg : nullptr);
         else
             tile_epilogue<T, T, BMN, REQUANT, false>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
-                                          (uint32_t *)(lds + 4 * kXposeBytes<T>));
+                                          (uint32_t *)(lds + 4 * kXposeBytes<T>), ROWS ? rs_reg : nullptr);
     }
 }
 
