@@ -113,7 +113,7 @@ hipError_t allow_big_lds()
 
 template <int BM, int BN, int WGM, int WGN, int NSTAGE = 4>
 hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipStream_t st,
-                           const RawB *rawb = nullptr)
+                           const RawB *rawb = nullptr, bool rows = false)
 {
     using Cfg = DmaCfg<BM, BN, WGM, WGN, NSTAGE>;
     GemmParams p = p0;
@@ -127,9 +127,22 @@ hipError_t launch_tile_dma(const GemmParams &p0, bool requant, int num_cus, hipS
     dim3 grid((unsigned)nwg), block(WGM * WGN * 64);
     const size_t smem = Cfg::kLdsBytes;
     const RawB none{nullptr, 0};
-    if (rawb)        // unpacked B: int32 output only
+    if (rawb) {      // unpacked B: int32 output only
         hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false, true>), grid, block, smem, st, p, *rawb);
-    else if (requant)
+        return hipGetLastError();
+    }
+    if constexpr (BM < 256) {
+        // the form that adds up the row sums itself (64 x 64 and 128 x 128 tiles)
+        static_assert(Cfg::kLdsBytes <= 64 * 1024, "needs no LDS attribute");
+        if (rows) {
+            if (requant)
+                hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, true, false, true>), grid, block, smem, st, p, none);
+            else
+                hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false, false, true>), grid, block, smem, st, p, none);
+            return hipGetLastError();
+        }
+    }
+    if (requant)
         hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, true>), grid, block, smem, st, p, none);
     else
         hipLaunchKernelGGL((gemm_tile_dma_kernel<BM, BN, WGM, WGN, NSTAGE, false>), grid, block, smem, st, p, none);
@@ -403,7 +416,8 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
                          ((a.M + 127) / 128) * ((B->N + 127) / 128) <= (int64_t)device_cus;
     // the streaming kernel and the long-pipeline kernels (the K split is one) form the row sums
     // themselves; the others read them from a pass of their own
-    const bool rows_in_kernel = kernel == NGEMM_KERNEL_SKINNY || kernel == NGEMM_KERNEL_SPLIT_K || deep64 || deep128;
+    const bool rows_in_kernel = kernel == NGEMM_KERNEL_SKINNY || kernel == NGEMM_KERNEL_SPLIT_K ||
+                                ((kernel == NGEMM_KERNEL_TILE_64 || kernel == NGEMM_KERNEL_TILE_128) && dma_ok);
     const bool rows_needed = a.needs_rowsum() && B->K > 0;
     if (rows_needed && !rows_in_kernel) {
         int32_t *rs = (int32_t *)ws;
@@ -422,14 +436,14 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
         if (deep64)
             e = launch_tile_deep<1>(p, a.requant, rows_needed, num_cus, st);
         else
-            e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st)
+            e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st, nullptr, rows_needed)
                        : launch_tile<64, 64, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_128:
         if (deep128)
             e = launch_tile_deep<2>(p, a.requant, rows_needed, num_cus, st);
         else
-            e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st)
+            e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st, nullptr, rows_needed)
                        : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
         break;
     case NGEMM_KERNEL_TILE_256:

@@ -985,7 +985,10 @@ struct RawB {
     int64_t ldb;
 };
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool REQUANT, bool BRAW = false>
+// ROWS: the row sums a zero-point of B needs are added up here, from the A fragments behind the matrix
+// op that uses them (no row-sum pass before the kernel); the host takes this form only when the
+// zero-point is there.
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool REQUANT, bool BRAW = false, bool ROWS = false>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const GemmParams p, const RawB rawb)
 {
     using Cfg = DmaCfg<BM, BN, WGM, WGN, NSTAGE>;
@@ -1100,8 +1103,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
         // Matrix instruction with the packed operand first: lane l then holds, for row l%32 of
         // the A block, the four consecutive columns 8*(r/4) + 4*(l/32) + r%4 of the B block in
         // registers r = 4q..4q+3.
+        int rs[TM];                                    // this lane's share of the row sums (row lane % 32 of block i)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) rs[i] = 0;
         auto mma_one = [&](int slot, int i, int j) {
             acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+            if (ROWS && j == 0) {
+                const v4i a = fa[slot][i];             // shifted before its first matrix op
+                rs[i] = __builtin_amdgcn_sdot4(a.x, 0x01010101, rs[i], false);
+                rs[i] = __builtin_amdgcn_sdot4(a.y, 0x01010101, rs[i], false);
+                rs[i] = __builtin_amdgcn_sdot4(a.z, 0x01010101, rs[i], false);
+                rs[i] = __builtin_amdgcn_sdot4(a.w, 0x01010101, rs[i], false);
+            }
         };
 
         // Stage indices past the last full stage are clamped to it: the extra copies land in
@@ -1218,13 +1231,22 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
         }
 
         __syncthreads();                               // every wavefront is done with the stage buffers
+        // Row sums: the halves of each 32-byte step sit in lanes l and l ^ 32; the zero fill of the K
+        // tail was shifted with the rest (-128 per byte of an unsigned A) and is taken out again.
+        uint32_t rs_reg[TM];
+        if (ROWS) {
+            const uint32_t pad = (p.a_xor && has_tail) ? 128u * (uint32_t)((nfull + 1) * BK - p.K) : 0u;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) rs_reg[i] = (uint32_t)(rs[i] + __shfl_xor(rs[i], 32, 64)) + pad;
+        }
+        const uint32_t *rsp = ROWS ? rs_reg : nullptr;
         // every practical output zero-point takes the binary32 form of the requantising arithmetic
         if (REQUANT && p.zc > -8388608 && p.zc < 8388608)
             tile_epilogue<TM, TN, BN, REQUANT, true>(p, acc, m0, n0, wm, wn, lane, tid, Cfg::kThreads,
-                                           lds + wave * kXposeBytes<TN>, (uint32_t *)(lds + NW * kXposeBytes<TN>));
+                                           lds + wave * kXposeBytes<TN>, (uint32_t *)(lds + NW * kXposeBytes<TN>), rsp);
         else
             tile_epilogue<TM, TN, BN, REQUANT, false>(p, acc, m0, n0, wm, wn, lane, tid, Cfg::kThreads,
-                                           lds + wave * kXposeBytes<TN>, (uint32_t *)(lds + NW * kXposeBytes<TN>));
+                                           lds + wave * kXposeBytes<TN>, (uint32_t *)(lds + NW * kXposeBytes<TN>), rsp);
     }
 }
 

@@ -410,6 +410,60 @@ def test_long_pipeline_small_tile_kernel(rt, oracle):
             ng.ngemm_set_max_workgroups(rt.ctx, 0)
 
 
+def test_row_sums_inside_tile_kernels(rt, oracle):
+    """With a zero-point of B and 16-byte aligned rows of A the 64 x 64 and 128 x 128 kernels (many
+    tiles per compute unit: the direct-to-LDS form; few: the long-pipeline form) add up the row sums
+    themselves instead of reading them from a pass before the kernel: K with and without a tail
+    (whose zero fill must not count), K below one stage, ragged M and N, int32 and u8 outputs, a
+    zero-point per column, the signed-A entry point."""
+    ng = ng_mod()
+    rng = np.random.default_rng(84)
+    shapes = ((1100, 1100, 200), (1100, 1100, 193), (2100, 2100, 130), (1100, 1200, 64), (1100, 1100, 40),
+              (300, 200, 1000), (300, 200, 1024))
+    for t, (M, N, K) in enumerate(shapes):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        za, zb = int(rng.integers(0, 256)), (int(rng.integers(1, 128)) if t % 2 else int(rng.integers(-128, 0)))
+        pad = (-K) % 16
+        prob = wl.Problem("rows%d" % t, A, B, za, zb, 0.0004, 77)
+        check_problem(rt, oracle, prob, (ng.NGEMM_KERNEL_TILE_64, ng.NGEMM_KERNEL_TILE_128), lda_pad=pad, ldc_pad=t % 2)
+        # per-column zero-points of B through the same kernels
+        zbv = rng.integers(-8, 9, size=N).astype(np.int32)
+        scale = (10.0 ** rng.uniform(-4, -3, size=N)).astype(np.float32)
+        h, packed = rt.pack(B)
+        Ah = np.zeros((M, K + pad), np.uint8)
+        Ah[:, :K] = A
+        Ad = torch.from_numpy(Ah).cuda()
+        sd, zd = torch.from_numpy(scale).cuda(), torch.from_numpy(zbv).cuda()
+        wsb = ng.ngemm_workspace_bytes(M, N, K)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        want = oracle.gemm_u8s8u8_requant_channel(A, B, za, 0, scale, 100, zb_vec=zbv, bias=None, relu=False)
+        for k in (ng.NGEMM_KERNEL_TILE_64, ng.NGEMM_KERNEL_TILE_128):
+            rt.set_kernel(k)
+            try:
+                Cd = torch.full((M, N), 0xA5, dtype=torch.uint8, device="cuda")
+                ng.ngemm_run_u8s8u8_requant_channel(rt.ctx, M, Ad, K + pad, za, h, 0, zd, sd, None, False, 100, Cd, N, ws, wsb)
+                torch.cuda.synchronize()
+            finally:
+                rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+            assert np.array_equal(Cd.cpu().numpy(), want), (M, N, K, k, "per-column zb")
+        ng.ngemm_packed_b_free(h)
+        if t < 3:
+            As = (A.astype(np.int16) - 128).astype(np.int8)
+            Asd = torch.from_numpy(np.pad(As, ((0, 0), (0, pad)))).cuda()
+            h, packed = rt.pack(B)
+            for k in (ng.NGEMM_KERNEL_TILE_64, ng.NGEMM_KERNEL_TILE_128):
+                rt.set_kernel(k)
+                try:
+                    Cd = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+                    ng.ngemm_run_s8s8s32(rt.ctx, M, Asd, K + pad, -5, h, zb, Cd, N, ws, wsb)
+                    torch.cuda.synchronize()
+                finally:
+                    rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
+                assert np.array_equal(Cd.cpu().numpy(), oracle.gemm_s8s8s32(As, B, -5, zb)), (M, N, K, k, "signed A")
+            ng.ngemm_packed_b_free(h)
+
+
 def test_split_k_kernel(rt, oracle):
     """Few 64 x 64 tiles and a long K: K is cut into parts over the workgroups, C is cleared and the
     parts add their partial tiles (bit-exact in any order).  Forced and by the heuristic; ragged
