@@ -83,7 +83,7 @@ bool ctx_ok(const ngemm_ctx *c) { return c && c->magic == kCtxMagic; }
 bool pack_ok(const ngemm_packed_b *b) { return b && b->magic == kPackMagic; }
 
 template <int BM, int BN, int WGM, int WGN, int BK>
-hipError_t launch_tile(const GemmParams &p0, bool requant, hipStream_t st)
+hipError_t launch_tile(const GemmParams &p0, bool requant, hipStream_t st, bool rows = false)
 {
     using Cfg = TileCfg<BM, BN, WGM, WGN, BK>;
     GemmParams p = p0;
@@ -91,6 +91,17 @@ hipError_t launch_tile(const GemmParams &p0, bool requant, hipStream_t st)
     p.tiles_n = (p.N + BN - 1) / BN;
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WGM * WGN * 64);
     const size_t smem = Cfg::kLdsBytes;
+    if constexpr (BM < 256) {
+        // the form that adds up the row sums itself (64 x 64 and 128 x 128 tiles)
+        static_assert(Cfg::kLdsBytes <= 64 * 1024, "needs no LDS attribute");
+        if (rows) {
+            if (requant)
+                hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, BK, true, true>), grid, block, smem, st, p);
+            else
+                hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, BK, false, true>), grid, block, smem, st, p);
+            return hipGetLastError();
+        }
+    }
     if (requant)
         hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, BK, true>), grid, block, smem, st, p);
     else
@@ -414,10 +425,10 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
                         ((a.M + 63) / 64) * ((B->N + 63) / 64) <= (int64_t)device_cus;
     const bool deep128 = kernel == NGEMM_KERNEL_TILE_128 && dma_ok && B->K >= 512 &&
                          ((a.M + 127) / 128) * ((B->N + 127) / 128) <= (int64_t)device_cus;
-    // the streaming kernel and the long-pipeline kernels (the K split is one) form the row sums
-    // themselves; the others read them from a pass of their own
+    // the streaming kernel and every 64 x 64 and 128 x 128 kernel (the K split is one) form the row
+    // sums themselves; the 256 x 256 kernels read them from a pass of their own
     const bool rows_in_kernel = kernel == NGEMM_KERNEL_SKINNY || kernel == NGEMM_KERNEL_SPLIT_K ||
-                                ((kernel == NGEMM_KERNEL_TILE_64 || kernel == NGEMM_KERNEL_TILE_128) && dma_ok);
+                                kernel == NGEMM_KERNEL_TILE_64 || kernel == NGEMM_KERNEL_TILE_128;
     const bool rows_needed = a.needs_rowsum() && B->K > 0;
     if (rows_needed && !rows_in_kernel) {
         int32_t *rs = (int32_t *)ws;
@@ -437,14 +448,14 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
             e = launch_tile_deep<1>(p, a.requant, rows_needed, num_cus, st);
         else
             e = dma_ok ? launch_tile_dma<64, 64, 2, 2>(p, a.requant, num_cus, st, nullptr, rows_needed)
-                       : launch_tile<64, 64, 2, 2, 64>(p, a.requant, st);
+                       : launch_tile<64, 64, 2, 2, 64>(p, a.requant, st, rows_needed);
         break;
     case NGEMM_KERNEL_TILE_128:
         if (deep128)
             e = launch_tile_deep<2>(p, a.requant, rows_needed, num_cus, st);
         else
             e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st, nullptr, rows_needed)
-                       : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st);
+                       : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st, rows_needed);
         break;
     case NGEMM_KERNEL_TILE_256:
         if (dma_ok && B->K >= X64Cfg::kMinK && x64_offsets_fit(256, a.lda, B->K) && x64_offsets_fit(9, 32 * round_up(B->K, 64), 0)) {

@@ -842,11 +842,11 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
                                        (uint32_t *)(lds + WGM * WGN * kXposeBytes<TN>), rsp);
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT>
+template <int BM, int BN, int WGM, int WGN, int BK, bool REQUANT, bool ROWS = false>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmParams p)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    tile_body_staged<BM, BN, WGM, WGN, BK, REQUANT>(p, blockIdx.x, lds);
+    tile_body_staged<BM, BN, WGM, WGN, BK, REQUANT, ROWS>(p, blockIdx.x, lds);
 }
 
 // ---- grouped launches: several independent problems in one grid -------------------------------
