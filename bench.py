@@ -430,6 +430,25 @@ def main():
             pl["library_int_mm_constant_TOPS"] = round(ops / (ms_lc * 1e-3) / 1e12, 1)
         except Exception as e:  # not every build of the framework has it
             pl["library_int_mm"] = "unavailable: %s" % type(e).__name__
+        # the matrix pipe by itself: a loop of nothing but matrix instructions on register operands
+        # (no LDS, no memory), which is what the power cap leaves of the published peak on such data
+        try:
+            import ctypes
+            from paper_1910_00178_amd.build import PROBE_LIB
+            probe = ctypes.CDLL(PROBE_LIB)
+            probe.ngemm_probe_mfma_rate.restype = ctypes.c_int
+            probe.ngemm_probe_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+            torch.cuda.synchronize()
+            for shape, sname in ((0, "16x16x64"), (1, "32x32x32")):
+                for rnd, dname in ((1, "uniform"), (0, "constant")):
+                    t = ctypes.c_double(0.0)
+                    rc = probe.ngemm_probe_mfma_rate(shape, rnd, ctypes.byref(t))
+                    pl["matrix_pipe_only_%s_%s_TOPS" % (sname, dname)] = round(t.value, 1) if rc == 0 else "error %d" % rc
+            ceil = pl.get("matrix_pipe_only_16x16x64_uniform_TOPS")
+            if isinstance(ceil, float) and ceil > 0:
+                pl["headline_frac_of_matrix_pipe_only_uniform"] = round(result["value"] / ceil, 4)
+        except Exception as e:
+            pl["matrix_pipe_only"] = "unavailable: %s" % type(e).__name__
         extras["power_limit_context_%d" % n] = pl
         result["extras"] = extras
 

@@ -7,6 +7,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "ngemm.hip")
 LIB = os.path.join(HERE, "libngemm.so")
+# measurement aid of bench.py (the rate of the matrix pipe by itself), a library of its own
+PROBE_SRC = os.path.join(HERE, "csrc", "mfma_rate_probe.hip")
+PROBE_LIB = os.path.join(HERE, "libngemm_probe.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -18,8 +21,8 @@ FLAGS = [
 ]
 
 
-def build_library(verbose=False):
-    cmd = [HIPCC, *FLAGS, "-o", LIB, SRC]
+def _compile(src, lib, verbose):
+    cmd = [HIPCC, *FLAGS, "-o", lib, src]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -28,7 +31,12 @@ def build_library(verbose=False):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return LIB
+    return lib
+
+
+def build_library(verbose=False):
+    _compile(PROBE_SRC, PROBE_LIB, verbose)
+    return _compile(SRC, LIB, verbose)
 
 
 if __name__ == "__main__":
