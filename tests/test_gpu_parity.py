@@ -834,10 +834,15 @@ def test_hip_graph_replays(rt, oracle):
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
 
+    # the same problems once more through the batched entry point, into outputs of their own
+    Cb = [torch.zeros((M, N), dtype=torch.int32, device="cuda") for (M, N, K, za, zb) in cases]
+    arr = ng.make_problems([(M, b[3], K, za, zb, b[1], cb, N) for (M, N, K, za, zb), b, cb in zip(cases, bufs, Cb)])
+
     def launch_all():
         for (M, N, K, za, zb), (B, h, packed, Ad, Cd, C8, ws, wsb) in zip(cases, bufs):
             ng.ngemm_run_u8s8s32(rt.ctx, M, Ad, K, za, h, zb, Cd, N, ws, wsb)
             ng.ngemm_run_u8s8u8_requant(rt.ctx, M, Ad, K, za, h, zb, 0.0007, 128, C8, N, ws, wsb)
+        ng.ngemm_run_batched_u8s8s32(rt.ctx, arr)
 
     with torch.cuda.stream(side):
         launch_all()                                   # warm-up outside the capture
@@ -851,11 +856,15 @@ def test_hip_graph_replays(rt, oracle):
             b[3].copy_(torch.from_numpy(A).cuda())     # eager work between replays
             b[4].fill_(-1)
             b[5].fill_(7)
+        for cb in Cb:
+            cb.fill_(-2)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         for A, (M, N, K, za, zb), b in zip(As, cases, bufs):
-            assert np.array_equal(b[4].cpu().numpy(), oracle.gemm_u8s8s32(A, b[0], za, zb)), (rep, M, N, K)
+            want = oracle.gemm_u8s8s32(A, b[0], za, zb)
+            assert np.array_equal(b[4].cpu().numpy(), want), (rep, M, N, K)
+            assert np.array_equal(Cb[cases.index((M, N, K, za, zb))].cpu().numpy(), want), (rep, M, N, K, "batched")
             assert np.array_equal(b[5].cpu().numpy(),
                                   oracle.gemm_u8s8u8_requant(A, b[0], za, zb, np.float32(0.0007), 128)), (rep, M, N, K)
     for b in bufs:
