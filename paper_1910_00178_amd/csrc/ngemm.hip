@@ -467,6 +467,9 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
             if (a.requant)
                 hipLaunchKernelGGL((gemm_tile_x64_kernel<false, true>), grid, dim3(256), X64Cfg::kLdsBytes, st, p,
                                    RawB{nullptr, 0});
+            else if (a.a_signed)      // signed A: the form without the u8 -> s8 shift
+                hipLaunchKernelGGL((gemm_tile_x64_kernel<false, false, false>), grid, dim3(256), X64Cfg::kLdsBytes, st, p,
+                                   RawB{nullptr, 0});
             else
                 hipLaunchKernelGGL((gemm_tile_x64_kernel<false, false>), grid, dim3(256), X64Cfg::kLdsBytes, st, p,
                                    RawB{nullptr, 0});
@@ -543,6 +546,8 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
             hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 X64Cfg::kLdsBytes) != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                X64Cfg::kLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<false, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 X64Cfg::kLdsBytes) != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_s16_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S16Cfg::kLdsBytes) != hipSuccess) {

@@ -1297,7 +1297,9 @@ struct X64Cfg {
 // BRAW: B is the caller's plain [N x K] int8 storage (struct RawB); its tiles are copied by stage, in
 // blocks of 16 columns x 64 bytes with the four chunks of column t rotated by t / 2.
 // The host launches this kernel for K >= kMinK only.
-template <bool BRAW, bool REQUANT = false>
+// SHIFT = false: A holds signed bytes, the u8 -> s8 shift (32 vector instructions per stage and
+// wavefront, 1.7 % of the time on uniform data) is left out.
+template <bool BRAW, bool REQUANT = false, bool SHIFT = true>
 __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, const RawB rawb)
 {
     using Cfg = X64Cfg;
@@ -1437,8 +1439,8 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             const int i = m >> 3, j = m & 7;
             acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[S][j], fa[i & 3], v4i{0, 0, 0, 0}, 0, 0, 0);
         };
-        auto shift_a = [&](int i) { fa[i & 3] = shift_u8_to_s8(fa[i & 3], p.a_xor); };   // u8 -> s8
-        auto shift_a_word = [&](int i, int wd) { fa[i & 3][wd] ^= (int)p.a_xor; };      // one dword of it
+        auto shift_a = [&](int i) { if (SHIFT) fa[i & 3] = shift_u8_to_s8(fa[i & 3], p.a_xor); };   // u8 -> s8
+        auto shift_a_word = [&](int i, int wd) { if (SHIFT) fa[i & 3][wd] ^= (int)p.a_xor; };      // one dword of it
 
         if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
 
