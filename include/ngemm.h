@@ -81,9 +81,11 @@ ngemm_status ngemm_destroy(ngemm_ctx *ctx);
  * 64 x 64 tiles that most compute units would idle: K is cut into parts of at least 1024
  * bytes, one workgroup per tile and part; C is cleared by a launch of its own and the parts
  * add their partial sums with atomic adds (integer addition in any order gives the same
- * bits, the property Sec. 2.1 rests on).  It needs an int32 output, 16-byte aligned rows of
- * A and a K of at least 2048; every other call it is forced on runs the 64 x 64 tiles
- * (the streaming kernel when M <= 32). */
+ * bits, the property Sec. 2.1 rests on); when the workspace has the room ngemm_workspace_bytes
+ * counts for it, the parts store their partial tiles there instead and a second kernel sums
+ * them and finishes the epilogue, which also serves u8 outputs (per-tensor b_zero_point).
+ * It needs 16-byte aligned rows of A and a K of at least 2048; every other call it is forced
+ * on runs the 64 x 64 tiles (the streaming kernel when M <= 32). */
 ngemm_status ngemm_set_kernel(ngemm_ctx *ctx, int kernel);
 
 /*
@@ -154,9 +156,11 @@ ngemm_status ngemm_packed_b_free(ngemm_packed_b *b);
 ngemm_status ngemm_packed_b_shape(const ngemm_packed_b *b, int64_t *K, int64_t *N);
 
 /*
- * Workspace the run calls need for an M-row input (device bytes, pure
- * function): room for the int32 row sums of A, used only when b_zero_point != 0.
- * A NULL workspace is accepted when b_zero_point == 0.
+ * Workspace of the run calls (device bytes, pure function): room for the int32 row sums
+ * of A, needed only when b_zero_point != 0 (a NULL workspace is accepted otherwise), and,
+ * for outputs of few tiles with a long K, room for the partial results of the K split (at
+ * most 4 MiB).  A workspace that holds the row sums only is always enough: the K split then
+ * adds its parts to C with atomic adds (int32 outputs) or is not used (u8 outputs).
  */
 size_t ngemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 

@@ -192,11 +192,11 @@ hipError_t launch_tile_deep(const GemmParams &p0, bool requant, bool rows, int n
     const int ntiles = p.tiles_m * p.tiles_n;
     dim3 grid((unsigned)(ntiles < num_cus ? ntiles : num_cus)), block(256);
     if (requant && rows)
-        hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true, false, true>), grid, block, Cfg::kLdsBytes, st, p);
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true, 0, true>), grid, block, Cfg::kLdsBytes, st, p);
     else if (requant)
         hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true>), grid, block, Cfg::kLdsBytes, st, p);
     else if (rows)
-        hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false, false, true>), grid, block, Cfg::kLdsBytes, st, p);
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false, 0, true>), grid, block, Cfg::kLdsBytes, st, p);
     else
         hipLaunchKernelGGL((gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false>), grid, block, Cfg::kLdsBytes, st, p);
     return hipGetLastError();
@@ -205,11 +205,15 @@ hipError_t launch_tile_deep(const GemmParams &p0, bool requant, bool rows, int n
 // K split over workgroups for outputs that leave most compute units without a tile (64 x 64 tiles,
 // int32 output): S = the number of parts that brings the grid up to the unit count, each part a
 // multiple of 256 bytes of K (whole stages of the long pipeline) and at least kSplitMinChunk long.
-// C is cleared first and every part adds its partial tile with atomic adds (exact in any order).
+// With room in the workspace the parts store their partial tiles there and a second kernel sums them
+// and finishes the epilogue (any output type); without it C is cleared first and every part adds its
+// partial tile with atomic adds (int32 outputs; exact in any order).
 constexpr int kSplitMinChunk = 1024;
+constexpr int kSplitMaxUnits = 256;        // (tile, part) units of a K split: one per compute unit at most
 int splitk_parts(int64_t M, int64_t N, int64_t K, int num_cus, int *kchunk)
 {
     const int64_t ntiles = ((M + 63) / 64) * ((N + 63) / 64);
+    if (num_cus > kSplitMaxUnits) num_cus = kSplitMaxUnits;
     int64_t S = ntiles > 0 ? num_cus / ntiles : 1;
     if (S * kSplitMinChunk > K) S = K / kSplitMinChunk;
     if (S < 2) return 1;
@@ -218,7 +222,15 @@ int splitk_parts(int64_t M, int64_t N, int64_t K, int num_cus, int *kchunk)
     return (int)((K + chunk - 1) / chunk);         // every part holds at least one byte of K
 }
 
-hipError_t launch_tile_deep_splitk(const GemmParams &p0, int parts, int kchunk, bool rows, int num_cus, hipStream_t st)
+// Bytes of the partial results of a K split into `parts`.
+size_t splitk_part_bytes(int64_t M, int64_t N, int parts)
+{
+    return (size_t)round_up((int64_t)parts * M * splitk_part_pitch(N) * 4, 256);
+}
+
+// part_ws: room for the partial results (splitk_part_bytes), or nullptr for the atomic form.
+hipError_t launch_tile_deep_splitk(const GemmParams &p0, int parts, int kchunk, bool rows, bool requant, int32_t *part_ws,
+                                   int num_cus, hipStream_t st)
 {
     using Cfg = DeepCfg<1, kDeepSub<1>, kDeepStages>;
     GemmParams p = p0;
@@ -226,16 +238,32 @@ hipError_t launch_tile_deep_splitk(const GemmParams &p0, int parts, int kchunk, 
     p.tiles_n = (p.N + 63) / 64;
     p.ksplit = parts;
     p.kchunk = kchunk;
+    p.part_ws = part_ws;
+    const int nunits = p.tiles_m * p.tiles_n * parts;
+    dim3 grid((unsigned)(nunits < num_cus ? nunits : num_cus)), block(256);
+    if (part_ws) {
+        if (rows)
+            hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, 2, true>), grid, block, Cfg::kLdsBytes, st, p);
+        else
+            hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, 2, false>), grid, block, Cfg::kLdsBytes, st, p);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const int64_t lanes = (int64_t)p.M * (splitk_part_pitch(p.N) / 4);
+        const dim3 rgrid((unsigned)((lanes + 63) / 64)), rblock(64 * (parts < kReduceWaves ? parts : kReduceWaves));
+        if (requant)
+            hipLaunchKernelGGL(splitk_reduce_kernel<true>, rgrid, rblock, 0, st, p, parts);
+        else
+            hipLaunchKernelGGL(splitk_reduce_kernel<false>, rgrid, rblock, 0, st, p, parts);
+        return hipGetLastError();
+    }
     const int64_t segs = (p.N + 1023) / 1024;
     hipLaunchKernelGGL(zero_c_kernel, dim3((unsigned)(p.M * segs)), dim3(256), 0, st, (int32_t *)p.C, p.ldc, p.N, (int)segs);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int nunits = p.tiles_m * p.tiles_n * parts;
-    dim3 grid((unsigned)(nunits < num_cus ? nunits : num_cus)), block(256);
     if (rows)
-        hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true, true>), grid, block, Cfg::kLdsBytes, st, p);
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, 1, true>), grid, block, Cfg::kLdsBytes, st, p);
     else
-        hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true>), grid, block, Cfg::kLdsBytes, st, p);
+        hipLaunchKernelGGL((gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, 1, false>), grid, block, Cfg::kLdsBytes, st, p);
     return hipGetLastError();
 }
 
@@ -246,10 +274,12 @@ hipError_t allow_big_lds_deep()
     const void *forms[] = {
         (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false>,
         (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true>,
-        (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false, false, true>,
-        (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true, false, true>,
-        (const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true>,
-        (const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, true, true>,
+        (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, false, 0, true>,
+        (const void *)gemm_tile_deep_kernel<T, kDeepSub<T>, kDeepStages, true, 0, true>,
+        (const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, 1, false>,
+        (const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, 1, true>,
+        (const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, 2, false>,
+        (const void *)gemm_tile_deep_kernel<1, kDeepSub<1>, kDeepStages, false, 2, true>,
     };
     for (const void *f : forms) {
         hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
@@ -406,18 +436,25 @@ GemmParams make_params(const RunArgs &a)
     return p;
 }
 
-// Launches one validated GEMM; `ws` must hold rowsum_bytes(M) when zb != 0.
-ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cus, void *ws, hipStream_t st)
+// Launches one validated GEMM; `ws` must hold rowsum_bytes(M) when zb != 0.  What lies beyond those
+// bytes serves the K split for its partial results when there is enough of it.
+ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cus, void *ws, size_t ws_bytes, hipStream_t st)
 {
     const ngemm_packed_b *B = a.B;
     if (a.M == 0 || B->N == 0) return NGEMM_OK;
     GemmParams p = make_params(a);
     const bool dma_ok = (((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0;
     int kchunk = 0, parts = 1;
+    int32_t *part_ws = nullptr;
     if (kernel == NGEMM_KERNEL_SPLIT_K) {
-        // int32 outputs and aligned rows of A only; what it cannot serve goes to the 64 x 64 tiles
-        // (to the streaming kernel when M <= 32)
-        parts = (!a.requant && dma_ok) ? splitk_parts(a.M, B->N, B->K, num_cus, &kchunk) : 1;
+        // aligned rows of A only; u8 outputs need the workspace form and a zero-point of B per tensor;
+        // what it cannot serve goes to the 64 x 64 tiles (to the streaming kernel when M <= 32)
+        parts = dma_ok ? splitk_parts(a.M, B->N, B->K, num_cus, &kchunk) : 1;
+        // int32 outputs always take the atomic form (never slower: 7.0 against 7.2 us for one tile,
+        // 10.4 against 15.2 for 128 tiles at K = 4096); u8 outputs need the partial results in memory
+        if (a.requant && parts >= 2 && ws && ws_bytes >= rowsum_bytes(a.M) + splitk_part_bytes(a.M, B->N, parts) && !a.zb_vec)
+            part_ws = (int32_t *)((uint8_t *)ws + rowsum_bytes(a.M));
+        if (a.requant && !part_ws) parts = 1;
         if (parts < 2) kernel = a.M <= kSkinnyMaxM ? NGEMM_KERNEL_SKINNY : NGEMM_KERNEL_TILE_64;
     }
     // at most one tile per compute unit and a K worth pipelining: the long-pipeline variants
@@ -439,7 +476,8 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
     }
     hipError_t e;
     if (kernel == NGEMM_KERNEL_SPLIT_K)
-        return launch_tile_deep_splitk(p, parts, kchunk, rows_needed, num_cus, st) == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
+        return launch_tile_deep_splitk(p, parts, kchunk, rows_needed, a.requant, part_ws, num_cus, st) == hipSuccess ? NGEMM_OK
+                                                                                                                : NGEMM_ERR_DEVICE;
     switch (kernel) {
     case NGEMM_KERNEL_SKINNY: e = launch_skinny(p, a.requant, num_cus, st); break;
     // direct-to-LDS copies need 16-byte aligned rows of A; the register-staged kernels take the rest
@@ -496,7 +534,7 @@ ngemm_status run_common(ngemm_ctx *ctx, const RunArgs &a, void *ws, size_t ws_by
     }
     DeviceGuard g(ctx->device);
     if (!g.ok) return NGEMM_ERR_DEVICE;
-    return launch_run(a, kernel, workgroup_budget(ctx), ctx->num_cus > 0 ? ctx->num_cus : 256, ws,
+    return launch_run(a, kernel, workgroup_budget(ctx), ctx->num_cus > 0 ? ctx->num_cus : 256, ws, ws_bytes,
                       (hipStream_t)stream);
 }
 
@@ -753,9 +791,15 @@ ngemm_status ngemm_packed_b_shape(const ngemm_packed_b *b, int64_t *K, int64_t *
 
 size_t ngemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    (void)N; (void)K;
     if (M <= 0 || M > kMaxDim) return 0;
-    return rowsum_bytes(M);
+    size_t bytes = rowsum_bytes(M);
+    // room for the partial results of the K split (outputs of few tiles with a long K: at most 4 MiB)
+    if (N > 0 && N <= kMaxDim && K > 0 && K <= kMaxDim) {
+        int kchunk = 0;
+        const int parts = splitk_parts(M, N, K, kSplitMaxUnits, &kchunk);
+        if (parts >= 2) bytes += splitk_part_bytes(M, N, parts);
+    }
+    return bytes;
 }
 
 ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,

@@ -51,9 +51,12 @@ struct GemmParams {
     // operand type of A: 0x80808080 for unsigned bytes (shifted to signed by xor), 0 for signed
     // bytes (used as they are; za_term and rconst are then -za and -za*K)
     uint32_t a_xor;
-    // K split over workgroups (gemm_tile_deep_kernel, SPLITK form): unit u of the grid is tile
-    // u % ntiles, bytes [kchunk * (u / ntiles), + kchunk) of K; kchunk is a multiple of 256
+    // K split over workgroups (gemm_tile_deep_kernel, SPLITK forms): unit u of the grid is tile
+    // u % ntiles, bytes [kchunk * (u / ntiles), + kchunk) of K; kchunk is a multiple of 256.
+    // part_ws (SPLITK = 2): the parts' partial results, `ksplit` dense int32 matrices of M rows,
+    // row pitch N rounded up to 4.
     int ksplit, kchunk;
+    int32_t *part_ws;
 };
 
 // ---- small helpers -------------------------------------------------------------------------
@@ -913,6 +916,7 @@ __device__ __forceinline__ GemmParams group_member_params(const GroupMember &m)
     p.a_xor = 0x80808080u;
     p.ksplit = 1;
     p.kchunk = 0;
+    p.part_ws = nullptr;
     return p;
 }
 
@@ -1779,7 +1783,10 @@ struct DeepCfg {
 // ROWS: form the row sums a zero-point of B needs here (four more vector instructions per A fragment:
 // 8 % to 28 % on the T = 1 form, whose wavefronts are bound by instruction issue, so the host picks
 // this form only when the zero-point is there; it then saves the launch of the row-sum pass).
-template <int T, int SUB, int NSTAGE, bool REQUANT, bool SPLITK = false, bool ROWS = false>
+// SPLITK: 0 one workgroup per tile; 1 K split, the parts add their partial tiles to a cleared C with
+// atomic adds; 2 K split, the parts store their partial tiles (row terms taken off already) to
+// p.part_ws and splitk_reduce_kernel forms the output (any output type).
+template <int T, int SUB, int NSTAGE, bool REQUANT, int SPLITK = 0, bool ROWS = false>
 __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
 {
     using Cfg = DeepCfg<T, SUB, NSTAGE>;
@@ -1795,10 +1802,10 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    static_assert(!(SPLITK && REQUANT), "partial sums are added as int32");
+    static_assert(!(SPLITK != 0 && REQUANT), "partial sums are int32");
     const int nslices = p.Kp / 32;
     const int ntiles = p.tiles_m * p.tiles_n;
-    const int nunits = SPLITK ? ntiles * p.ksplit : ntiles;
+    const int nunits = (SPLITK != 0) ? ntiles * p.ksplit : ntiles;
     const int gsz = gridDim.x, w = blockIdx.x;
 
     const int t16 = lane >> 2;
@@ -1816,10 +1823,10 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
 
     for (int unit = w; unit < nunits; unit += gsz) {
         // this unit's tile and part of K: bytes [k0, k0 + kc), k0 a multiple of 256
-        const int split = SPLITK ? unit / ntiles : 0;
-        const int tile = SPLITK ? unit - split * ntiles : unit;
-        const int k0 = SPLITK ? split * p.kchunk : 0;
-        const int kc = SPLITK ? (p.K - k0 < p.kchunk ? p.K - k0 : p.kchunk) : p.K;
+        const int split = (SPLITK != 0) ? unit / ntiles : 0;
+        const int tile = (SPLITK != 0) ? unit - split * ntiles : unit;
+        const int k0 = (SPLITK != 0) ? split * p.kchunk : 0;
+        const int kc = (SPLITK != 0) ? (p.K - k0 < p.kchunk ? p.K - k0 : p.kchunk) : p.K;
         const int nsub = kc / 64;                         // full 64-byte sub-blocks of K
         const int nst = nsub / SUB, rem = nsub % SUB;     // full stages, sub-blocks of the partial one
         const int nstages = nst + (rem > 0 ? 1 : 0);
@@ -1995,7 +2002,17 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
 #pragma unroll
             for (int i = 0; i < T; ++i) rs_reg[i] = (uint32_t)(rs[i] + __shfl_xor(rs[i], 32, 64)) + pad;
         }
-        if (SPLITK) {
+        if (SPLITK == 2) {
+            // partial tile of this part, dense, with this part's share of the row term; the column
+            // and constant terms are added when the parts are summed
+            GemmParams pe = p;
+            pe.za_term = 0u;
+            pe.kconst = 0u;
+            pe.ldc = (p.N + 3) & ~3;                     // row pitch of the partial matrices
+            pe.C = p.part_ws + (int64_t)split * p.M * pe.ldc;
+            tile_epilogue<T, T, BMN, false, false, false>(pe, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
+                                                          (uint32_t *)(lds + 4 * kXposeBytes<T>), ROWS ? rs_reg : nullptr);
+        } else if (SPLITK == 1) {
             // the column and constant terms belong to the whole sum: the first part of K brings
             // them; the row term is linear in the row sum, so every part takes its own share
             GemmParams pe = p;
@@ -2014,6 +2031,57 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
             tile_epilogue<T, T, BMN, REQUANT, false>(p, acc, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<T>,
                                           (uint32_t *)(lds + 4 * kXposeBytes<T>), ROWS ? rs_reg : nullptr);
     }
+}
+
+// Sum of the K split's partial results (SPLITK = 2) and the rest of the epilogue: column term,
+// constant term, and for u8 outputs the requantising sequence.  The partial matrices are dense with
+// a row pitch of N rounded up to 4 (16-byte loads).  A workgroup of up to 16 wavefronts (as many as
+// there are parts) covers 64 groups of four columns: wavefront w sums the parts w, w + nw, ... (all
+// its loads in flight at once), the shares meet in LDS and wavefront 0 finishes and stores.
+constexpr int kReduceWaves = 16;
+__host__ __device__ inline int64_t splitk_part_pitch(int64_t N) { return (N + 3) & ~(int64_t)3; }
+
+template <bool REQUANT>
+__global__ __launch_bounds__(64 * kReduceWaves) void splitk_reduce_kernel(const GemmParams p, int parts)
+{
+    __shared__ uint4 red[kReduceWaves][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int64_t ldp = splitk_part_pitch(p.N), quads = ldp / 4;
+    const int64_t u = (int64_t)blockIdx.x * 64 + lane;
+    const bool ok = u < (int64_t)p.M * quads;
+    const int row = ok ? (int)(u / quads) : 0, col = ok ? (int)(u - (int64_t)row * quads) * 4 : 0;
+    const int64_t mn = (int64_t)p.M * ldp;
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (ok) {
+        const int32_t *src = p.part_ws + (int64_t)row * ldp + col + (int64_t)wave * mn;
+#pragma unroll 4
+        for (int sp = wave; sp < parts; sp += nw) {
+            const uint4 t = *(const uint4 *)src;        // columns past N: never written, never used
+            v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+            src += (int64_t)nw * mn;
+        }
+    }
+    red[wave][lane] = v;
+    __syncthreads();
+    if (wave != 0 || !ok) return;
+    for (int w = 1; w < nw; ++w) {
+        const uint4 t = red[w][lane];
+        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+    }
+    // the parts took the row term off already: what is left has no row-dependent part
+    GemmParams pe = p;
+    pe.rowsum = nullptr;
+    pe.zb = 0u;
+    pe.zb_vec = nullptr;
+    if (REQUANT) pe.rconst = 0u;
+    const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        if (col + t < p.N) {
+            const uint32_t cs_term = p.za_term * (uint32_t)p.colsum[col + t];
+            // finish_s32 adds kconst itself; the requantising form has it inside the row term
+            store_out<REQUANT>(pe, row, col + t, (int32_t)(REQUANT ? vv[t] + p.kconst : vv[t]), cs_term);
+        }
 }
 
 // ---- 16-bit operands: s16 x s16 -> s32 on the 8-bit matrix pipe -------------------------------

@@ -38,7 +38,7 @@ class Runner:
         return h, packed
 
     def run(self, A, handle, N, za=0, zb=0, scale=None, zc=0, lda_pad=0, ldc_pad=0, a_byte_offset=0,
-            A_dev=None):
+            A_dev=None, small_ws=False):
         """One GEMM through the C ABI.  Returns the M x N numpy result (int32 or uint8) after
         checking that nothing outside the M x N window of C was written."""
         M, K = A.shape
@@ -62,6 +62,8 @@ class Runner:
         else:
             Cd = torch.full((rows, max(ldc, 1)), SENTINEL8, dtype=torch.uint8, device="cuda")
         wsb = ng.ngemm_workspace_bytes(M, N, K)
+        if small_ws:                                   # the row sums only: no room for a K split's partial results
+            wsb = min(wsb, (4 * M + 255) // 256 * 256)
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
         if scale is None:
             ng.ngemm_run_u8s8s32(self.ctx, M, a_ptr, lda, za, handle, zb, Cd, ldc, ws, wsb)

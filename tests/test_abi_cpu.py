@@ -41,6 +41,11 @@ def test_workspace_and_status_strings():
     assert ng.ngemm_workspace_bytes(1, 10, 10) == 256
     assert ng.ngemm_workspace_bytes(1000, 10, 10) == 4096
     assert ng.ngemm_workspace_bytes(0, 10, 10) == 0
+    # few tiles and a long K: room for the partial results of the K split, at most 4 MiB
+    assert ng.ngemm_workspace_bytes(64, 64, 65536) == 256 + 64 * 64 * 64 * 4
+    assert ng.ngemm_workspace_bytes(512, 512, 65536) == 2048 + 4 * 512 * 512 * 4
+    assert ng.ngemm_workspace_bytes(512, 512, 1024) == 2048
+    assert ng.ngemm_workspace_bytes(4096, 4096, 65536) == 16384
     seen = {ng.ngemm_status_string(s) for s in range(-5, 1)}
     assert len(seen) == 6 and "ok" in seen
 

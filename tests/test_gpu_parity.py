@@ -465,8 +465,10 @@ def test_row_sums_inside_tile_kernels(rt, oracle):
 
 
 def test_split_k_kernel(rt, oracle):
-    """Few 64 x 64 tiles and a long K: K is cut into parts over the workgroups, C is cleared and the
-    parts add their partial tiles (bit-exact in any order).  Forced and by the heuristic; ragged
+    """Few 64 x 64 tiles and a long K: K is cut into parts over the workgroups; with room in the
+    workspace the parts store their partial tiles and a second kernel sums them (int32 and u8
+    outputs), with a workspace for the row sums only C is cleared and the parts add their partial
+    tiles with atomic adds (bit-exact in any order).  Forced and by the heuristic; ragged
     M, N and K (a last part that is only a tail, parts with a partial stage), zero-points on,
     leading-dimension gaps with sentinels (the clearing must stay inside M x N), the wrap of the
     int32 sum across parts, the signed-A entry point, and the calls it cannot serve (u8 output,
@@ -482,6 +484,8 @@ def test_split_k_kernel(rt, oracle):
         B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
         p = wl.Problem(f"splitk_{M}x{N}x{K}", A, B, za=za, zb=zb, scale=float(np.float32(0.0002)), zc=31)
         check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K, ng.NGEMM_KERNEL_AUTO), lda_pad=(-K) % 16, ldc_pad=5)
+        check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K, ng.NGEMM_KERNEL_AUTO), lda_pad=(-K) % 16, ldc_pad=5,
+                      small_ws=True)
         if t % 3 == 0:
             check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K,), lda_pad=(-K) % 16 + 3, ldc_pad=1)   # unaligned rows
     # the sum wraps at K = 65794 with these values, whatever the number of parts
@@ -490,6 +494,7 @@ def test_split_k_kernel(rt, oracle):
         B = np.full((70, K), b, dtype=np.int8)
         p = wl.Problem(f"splitk_wrap_{K}", A, B, za=0, zb=0)
         check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K,), lda_pad=(-K) % 16)
+        check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K,), lda_pad=(-K) % 16, small_ws=True)
     # s8 x s8 through the same kernel
     M, N, K = 70, 90, 9000 + 16
     A = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
