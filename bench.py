@@ -341,14 +341,22 @@ def main():
             As = torch.from_numpy(wl.uniform_u8(rngs, Ms, Ks)).cuda()
             hb, pk, _ = pack(wl.uniform_s8(rngs, Ns, Ks))
             Cs = torch.empty((Ms, Ns), dtype=torch.int32, device="cuda")
+            C8s = torch.empty((Ms, Ns), dtype=torch.uint8, device="cuda")
+            wss = ng.ngemm_workspace_bytes(Ms, Ns, Ks)       # with room for the partial results (u8 output)
+            wsd = torch.empty(max(wss, 16), dtype=torch.uint8, device="cuda")
             call = [lambda: ng.ngemm_run_u8s8s32(ctx, Ms, As, Ks, 0, hb, 0, Cs, Ns)] * 20
+            call8 = [lambda: ng.ngemm_run_u8s8u8_requant(ctx, Ms, As, Ks, 128, hb, 0, 2.0e-4, 128, C8s, Ns, wsd, wss)] * 20
             ms_split = graph_time_ms(call, 10, torch)
+            ms_split8 = graph_time_ms(call8, 10, torch)
             ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_SKINNY if Ms <= 32 else ng.NGEMM_KERNEL_TILE_64)
             ms_plain = graph_time_ms(call, 10, torch)
+            ms_plain8 = graph_time_ms(call8, 10, torch)
             ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_AUTO)
             o = 2.0 * Ms * Ns * Ks
             sk_extra["%dx%dx%d" % (Ms, Ns, Ks)] = {"split_k_us": round(ms_split * 1e3, 2), "unsplit_us": round(ms_plain * 1e3, 2),
-                                                   "split_k_TOPS": round(o / (ms_split * 1e-3) / 1e12, 1)}
+                                                   "split_k_TOPS": round(o / (ms_split * 1e-3) / 1e12, 1),
+                                                   "u8_split_k_us": round(ms_split8 * 1e3, 2),
+                                                   "u8_unsplit_us": round(ms_plain8 * 1e3, 2)}
             ng.ngemm_packed_b_free(hb)
         extras["underfilled_long_k"] = sk_extra
 
