@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak, GB/s (published)
 # HBM-side bytes per launch of the 8192^3 kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/large_square_8192_hbm_traffic.txt (scaled by the same counters' readings for
 # the 1 GiB copy below).  Valid for --size 8192 only.
-MEASURED_TRAFFIC_BYTES = 1081734424
+MEASURED_TRAFFIC_BYTES = 1081698657
 
 
 def gpu_time_ms(fn, iters, warmup, torch):
