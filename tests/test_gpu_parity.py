@@ -488,6 +488,17 @@ def test_split_k_kernel(rt, oracle):
                       small_ws=True)
         if t % 3 == 0:
             check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K,), lda_pad=(-K) % 16 + 3, ldc_pad=1)   # unaligned rows
+    # fewer workgroups than compute units: fewer, longer parts
+    for budget in (5, 8, 40):
+        ng.ngemm_set_max_workgroups(rt.ctx, budget)
+        try:
+            for (M, N, K) in ((64, 64, 8192), (100, 70, 5000), (130, 130, 9000 + 3)):
+                A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+                B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+                p = wl.Problem(f"splitk_budget{budget}_{M}x{N}x{K}", A, B, za=3, zb=-4, scale=float(np.float32(0.0002)), zc=9)
+                check_problem(rt, oracle, p, (ng.NGEMM_KERNEL_SPLIT_K,), lda_pad=(-K) % 16)
+        finally:
+            ng.ngemm_set_max_workgroups(rt.ctx, 0)
     # the sum wraps at K = 65794 with these values, whatever the number of parts
     for (K, b) in ((65793, -128), (65794, -128), (66312, 127)):
         A = np.full((64, K), 255, dtype=np.uint8)
