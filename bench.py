@@ -81,7 +81,7 @@ def main():
     ap.add_argument("--size", type=int, default=8192, help="square size of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle wall time")
+    ap.add_argument("--cpu-seconds", type=float, default=16.0, help="target oracle wall time")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -185,7 +185,7 @@ def main():
 
     # ---------------- CPU baseline: the oracle as it stands, bounded sample ----------------
     if not args.no_cpu_baseline:
-        cal_rows = 2 * oracle.num_threads()
+        cal_rows = 16 * oracle.num_threads()
         t = time.perf_counter()
         oracle.gemm_u8s8s32(np.ascontiguousarray(prob.A[:cal_rows]), prob.B)
         per_row = (time.perf_counter() - t) / cal_rows
