@@ -183,6 +183,28 @@ def test_k_permutation_invariance(oracle):
                                               np.ascontiguousarray(B[:, p]), 9, -3))
 
 
+def test_k_split_additivity_through_the_wrap(oracle):
+    """Sec. 2.1: partial sums over parts of K add up to the whole sum in the ring of integers mod 2^32,
+    zero-points included and also where the whole sum wraps (what a K split over workgroups with
+    atomic adds relies on)."""
+    rng = np.random.default_rng(23)
+    A, B = rand_ab(rng, 7, 9, 300)
+    cuts = (0, 1, 64, 65, 256, 299, 300)
+    whole = oracle.gemm_u8s8s32(A, B, 200, -100).astype(np.uint32)
+    parts = np.zeros_like(whole)
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        parts += oracle.gemm_u8s8s32(np.ascontiguousarray(A[:, lo:hi]), np.ascontiguousarray(B[:, lo:hi]), 200, -100).astype(np.uint32)
+    assert np.array_equal(parts, whole)
+    K = 66000                                           # 66000 * 255 * 128 > 2^31: the whole sum wraps
+    A = np.full((2, K), 255, dtype=np.uint8)
+    B = np.full((3, K), -128, dtype=np.int8)
+    whole = oracle.gemm_u8s8s32(A, B).astype(np.uint32)
+    assert int(whole[0, 0]) == (-K * 32640) % 2**32
+    halves = sum(oracle.gemm_u8s8s32(A[:, lo:hi].copy(), B[:, lo:hi].copy()).astype(np.uint32)
+                 for lo, hi in ((0, 30000), (30000, K)))
+    assert np.array_equal(halves.astype(np.uint32), whole)
+
+
 @pytest.mark.parametrize("K,b,want32", [
     (65793, -128, -65793 * 32640),                  # last K whose negative extreme still fits (-2147483520)
     (65794, -128, (-65794 * 32640) + 2**32),        # one more wraps to +2147451136
