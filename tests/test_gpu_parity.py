@@ -27,7 +27,7 @@ def ng_mod():
     return ng
 
 
-TILE_KERNELS = (1, 2, 3)
+TILE_KERNELS = (1, 2, 3, 4)      # 4: the K split; it runs the 64 x 64 tiles where it cannot split
 
 
 def check_problem(rt, oracle, prob, kernels, **kw):
