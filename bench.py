@@ -23,10 +23,23 @@ if ROOT not in sys.path:
 INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense INT8 matrix peak, TOP/s (published)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak, GB/s (published)
 
-# HBM-side bytes per launch of the 8192^3 kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/large_square_8192_hbm_traffic.txt (scaled by the same counters' readings for
-# the 1 GiB copy below).  Valid for --size 8192 only.
-MEASURED_TRAFFIC_BYTES = 1081698657
+# Figures that only a counter or trace run can give (HBM-side bytes per launch, kernel-only
+# durations) are read from the rocprofv3 summaries under profiles/: lines of the form
+# "bench_key <name> = <number>".  Each is reported with the file it came from; a missing file or
+# key gives null.
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def profile_figure(fname, key):
+    try:
+        with open(os.path.join(PROFILES, fname)) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 4 and parts[0] == "bench_key" and parts[1] == key and parts[2] == "=":
+                    return float(parts[3])
+    except OSError:
+        pass
+    return None
 
 
 def gpu_time_ms(fn, iters, warmup, torch):
@@ -71,48 +84,34 @@ def graph_time_ms(fn_seq, replays, torch):
     return e0.elapsed_time(e1) / (replays * len(fn_seq))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    # the clocks of an idle MI355X take some 50 ms of this kernel to settle: the defaults warm up
-    # long enough for the timed steps to see the sustained state (0.2 s in all)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--size", type=int, default=8192, help="square size of the headline workload")
-    ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=16.0, help="target oracle wall time")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+TRAFFIC_PROFILE = "large_square_8192_hbm_traffic.txt"
+SKINNY_PROFILE = "skinny_4096x1024_kernel_trace.txt"
+SECTIONS = ("skinny", "fc", "longk", "batched", "types")
 
-    import numpy as np
-    import torch
 
-    import paper_1910_00178_amd as ng
-    from paper_1910_00178_amd import workloads as wl
+class Bench:
+    """Shared state of the sections: the context, torch, the binding and small helpers."""
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
-        sys.exit(3)
-    torch.cuda.set_device(0)
-    ctx = ng.ngemm_create(0)
+    def __init__(self, ng, wl, torch, np, ctx):
+        self.ng, self.wl, self.torch, self.np, self.ctx = ng, wl, torch, np, ctx
 
-    def pack(B_np):
+    def pack(self, B_np):
+        ng, torch = self.ng, self.torch
         N, K = B_np.shape
         Bd = torch.from_numpy(B_np).cuda()
         nbytes = ng.ngemm_packed_b_bytes(K, N)
         packed = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        h = ng.ngemm_pack_b(ctx, K, N, Bd, K, packed, nbytes)
+        h = ng.ngemm_pack_b(self.ctx, K, N, Bd, K, packed, nbytes)
         torch.cuda.synchronize()
         return h, packed, Bd
 
-    # ---------------- headline: large square ----------------
+
+def bench_headline(b, args, result):
+    """Config 4.  Fills the contract's keys of `result`; returns (ops, n)."""
+    ng, wl, torch, np, ctx = b.ng, b.wl, b.torch, b.np, b.ctx
     n = args.size
     prob = wl.large_square(n)
-    h, packed, Bd = pack(prob.B)
+    h, packed, Bd = b.pack(prob.B)
     Ad = torch.from_numpy(prob.A).cuda()
     Cd = torch.empty((n, n), dtype=torch.int32, device="cuda")
 
@@ -158,7 +157,8 @@ def main():
     copy_ms = gpu_time_ms(lambda: cdst.copy_(csrc), 5, 2, torch)
     del csrc, cdst
 
-    result = {
+    traffic = profile_figure(TRAFFIC_PROFILE, "traffic_bytes_per_launch") if n == 8192 else None
+    result.update({
         "metric": "int8 GEMM TOPS (u8 x s8 -> s32, M=N=K=%d)" % n,
         "value": round(tops, 2),
         "unit": "TOPS",
@@ -176,12 +176,15 @@ def main():
                    "kernel": "gemm_tile_x64_kernel (256 x 256 tiles, v_mfma_i32_16x16x64_i8)", "sampled_outputs_match_oracle": sample_ok},
         "roofline": {"bound": "mfma", "achieved": round(kern_tops, 2), "peak": INT8_MFMA_PEAK_TOPS,
                      "unit": "TOP/s", "frac": round(kern_tops / INT8_MFMA_PEAK_TOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES if n == 8192 else None, "kernel_ms": round(kern_ms, 5),
+                     "traffic": int(traffic) if traffic else None,
+                     "traffic_source": ("profiles/%s (rocprofv3 --pmc runs of this script, not this run)" % TRAFFIC_PROFILE)
+                     if traffic else None,
+                     "kernel_ms": round(kern_ms, 5),
                      "algorithmic_ops_per_launch": ops,
                      "algorithmic_bytes_per_launch": 2 * n * n + 4 * n * n},
         "pack_b": {"ms": round(pack_ms, 4), "GBps": round(2.0 * n * n / (pack_ms * 1e-3) / 1e9, 1)},
         "copy_1GiB": {"ms": round(copy_ms, 4), "GBps_read_plus_write": round(2.0 * (1 << 30) / (copy_ms * 1e-3) / 1e9, 1)},
-    }
+    })
 
     # ---------------- CPU baseline: the oracle as it stands, bounded sample ----------------
     if not args.no_cpu_baseline:
@@ -205,264 +208,319 @@ def main():
     del packed, Bd
     torch.cuda.empty_cache()
 
-    # ---------------- extras ----------------
-    if not args.no_extras:
-        extras = {}
-        # skinny-M: (i) as specified, (ii) rotating weights, (iii) asymptote
-        sk = {}
-        for M in (1, 4, 16):
-            probs = wl.skinny(M)
-            B = probs[0].B
-            N, K = B.shape
-            hb, pk, _ = pack(B)
-            A_dev = [torch.from_numpy(p.A).cuda() for p in probs]
-            C = torch.empty((M, N), dtype=torch.int32, device="cuda")
-            cnt = [0]
 
-            def call():
-                ng.ngemm_run_u8s8s32(ctx, M, A_dev[cnt[0] % 16], K, 0, hb, 0, C, N)
-                cnt[0] += 1
-            ms_eager = gpu_time_ms(call, 1000, 50, torch)
-            seq = [(lambda t=t: ng.ngemm_run_u8s8s32(ctx, M, A_dev[t % 16], K, 0, hb, 0, C, N)) for t in range(250)]
-            ms = graph_time_ms(seq, 4, torch)            # 1000 calls, one weight matrix, pool of 16 inputs
-            abytes = K * N + M * K + 4 * M * N
-            entry = {"as_specified_us": round(ms * 1e3, 3), "as_specified_GBps": round(abytes / (ms * 1e-3) / 1e9, 1),
-                     "as_specified_eager_python_us": round(ms_eager * 1e3, 3),
-                     "algorithmic_bytes": abytes}
-            # rotating: 160 distinct packed copies (> 512 MiB, beyond the 256 MiB Infinity Cache)
-            nb = ng.ngemm_packed_b_bytes(K, N)
-            ncopies = 160
-            pool = torch.empty((ncopies, nb), dtype=torch.uint8, device="cuda")
-            pool[:] = pk
-            hs = []
-            Bd2 = torch.from_numpy(B).cuda()
-            for c in range(ncopies):
-                hs.append(ng.ngemm_pack_b(ctx, K, N, Bd2, K, pool[c], nb))
-            torch.cuda.synchronize()
+def bench_skinny(b, args):
+    """Config 3: (i) as specified, (ii) rotating weights (single calls and grouped calls),
+    (iii) asymptotes."""
+    ng, wl, torch, ctx = b.ng, b.wl, b.torch, b.ctx
+    sk = {}
+    per = 59                       # members of one grouped call
+    ncopies = 4 * per              # distinct packed copies: 236 x 4 MiB, four times the 256 MiB memory-side cache
+    for M in (1, 4, 16):
+        probs = wl.skinny(M)
+        B = probs[0].B
+        N, K = B.shape
+        hb, pk, _ = b.pack(B)
+        A_dev = [torch.from_numpy(p.A).cuda() for p in probs]
+        C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        cnt = [0]
 
-            seq = [(lambda t=t: ng.ngemm_run_u8s8s32(ctx, M, A_dev[t % 16], K, 0, hs[t % ncopies], 0, C, N))
-                   for t in range(ncopies)]
-            ms2 = graph_time_ms(seq, 6, torch)
-            entry["rotating_weights_us"] = round(ms2 * 1e3, 3)
-            entry["rotating_weights_GBps"] = round(abytes / (ms2 * 1e-3) / 1e9, 1)
-            entry["rotating_frac_of_hbm_peak"] = round(abytes / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-            # the same rotating GEMMs through the batched entry point, 59 independent problems per call
-            # (one grouped launch each): what a server with many small GEMMs in flight would issue
-            per = 59
-            Cb = [torch.empty((M, N), dtype=torch.int32, device="cuda") for _ in range(per)]
-            batches = [ng.make_problems([(M, A_dev[(b * per + t) % 16], K, 0, 0, hs[b * per + t], Cb[t], N)
-                                         for t in range(per)]) for b in range(ncopies // per)]
-            seqb = [(lambda arr=arr: ng.ngemm_run_batched_u8s8s32(ctx, arr)) for arr in batches]
-            msb = graph_time_ms(seqb, 6, torch) / per
-            entry["batched_members_per_call"] = per
-            entry["rotating_weights_batched_us_per_gemm"] = round(msb * 1e3, 3)
-            entry["rotating_weights_batched_GBps"] = round(abytes / (msb * 1e-3) / 1e9, 1)
-            entry["rotating_batched_frac_of_hbm_peak"] = round(abytes / (msb * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-            for x in hs:
-                ng.ngemm_packed_b_free(x)
-            ng.ngemm_packed_b_free(hb)
-            del pool
-            sk["M%d" % M] = entry
-        # launch floor: the smallest possible call through the same entry point, in the same graph
-        tinyB = torch.zeros((32, 64), dtype=torch.int8, device="cuda")
-        tb = ng.ngemm_packed_b_bytes(64, 32)
-        tpk = torch.empty(tb, dtype=torch.uint8, device="cuda")
-        th = ng.ngemm_pack_b(ctx, 64, 32, tinyB, 64, tpk, tb)
-        tA = torch.zeros((1, 64), dtype=torch.uint8, device="cuda")
-        tC = torch.empty((1, 32), dtype=torch.int32, device="cuda")
-        msf = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, 1, tA, 64, 0, th, 0, tC, 32)] * 250, 4, torch)
-        sk["launch_floor_us_1x32x64"] = round(msf * 1e3, 3)
-        ng.ngemm_packed_b_free(th)
-        # asymptotes: the same kernel on weights large enough to leave launch and latency behind
-        # (rotating copies, 512 MiB or more in all, so that every byte comes from HBM)
-        for (Mb, Nb, Kb, ncp) in ((16, 16384, 4096, 8), (16, 32768, 8192, 3), (1, 32768, 8192, 3)):
-            rngb = wl.rng_for(3, 90 + Mb)
-            Bbig = wl.uniform_s8(rngb, Nb, Kb)
-            Abig = torch.from_numpy(wl.uniform_u8(rngb, Mb, Kb)).cuda()
-            nb = ng.ngemm_packed_b_bytes(Kb, Nb)
-            pool = torch.empty((ncp, nb), dtype=torch.uint8, device="cuda")
-            Bd2 = torch.from_numpy(Bbig).cuda()
-            hs = [ng.ngemm_pack_b(ctx, Kb, Nb, Bd2, Kb, pool[c], nb) for c in range(ncp)]
-            Cb = torch.empty((Mb, Nb), dtype=torch.int32, device="cuda")
-            seq = [(lambda t=t: ng.ngemm_run_u8s8s32(ctx, Mb, Abig, Kb, 0, hs[t % ncp], 0, Cb, Nb))
-                   for t in range(4 * ncp)]
-            ms3 = graph_time_ms(seq, 5, torch)
-            ab = Kb * Nb + Mb * Kb + 4 * Mb * Nb
-            sk["asymptote_M%d_N%d_K%d" % (Mb, Nb, Kb)] = {
-                "us": round(ms3 * 1e3, 2), "GBps": round(ab / (ms3 * 1e-3) / 1e9, 1),
-                "frac_of_hbm_peak": round(ab / (ms3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-            for x in hs:
-                ng.ngemm_packed_b_free(x)
-            del pool, Bd2, Bbig
-        extras["skinny"] = sk
+        def call():
+            ng.ngemm_run_u8s8s32(ctx, M, A_dev[cnt[0] % 16], K, 0, hb, 0, C, N)
+            cnt[0] += 1
+        ms_eager = gpu_time_ms(call, 1000, 50, torch)
+        seq = [(lambda t=t: ng.ngemm_run_u8s8s32(ctx, M, A_dev[t % 16], K, 0, hb, 0, C, N)) for t in range(250)]
+        ms = graph_time_ms(seq, 4, torch)            # 1000 calls, one weight matrix, pool of 16 inputs
+        abytes = K * N + M * K + 4 * M * N
+        entry = {"as_specified_us": round(ms * 1e3, 3), "as_specified_GBps": round(abytes / (ms * 1e-3) / 1e9, 1),
+                 "as_specified_eager_python_us": round(ms_eager * 1e3, 3),
+                 "algorithmic_bytes": abytes}
+        # rotating: distinct packed copies, so that every byte comes from HBM
+        nb = ng.ngemm_packed_b_bytes(K, N)
+        pool = torch.empty((ncopies, nb), dtype=torch.uint8, device="cuda")
+        pool[:] = pk
+        hs = []
+        Bd2 = torch.from_numpy(B).cuda()
+        for c in range(ncopies):
+            hs.append(ng.ngemm_pack_b(ctx, K, N, Bd2, K, pool[c], nb))
+        torch.cuda.synchronize()
 
-        # transformer FC shapes
-        fc = {}
-        for idx in range(3):
-            p = wl.bert_fc(idx)
-            hb, pk, _ = pack(p.B)
-            A = torch.from_numpy(p.A).cuda()
-            C = torch.empty((p.M, p.N), dtype=torch.int32, device="cuda")
-            C8 = torch.empty((p.M, p.N), dtype=torch.uint8, device="cuda")
-            ms = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, p.M, A, p.K, p.za, hb, p.zb, C, p.N)] * 50, 4, torch)
-            ms8 = graph_time_ms([lambda: ng.ngemm_run_u8s8u8_requant(ctx, p.M, A, p.K, p.za, hb, p.zb, p.scale, p.zc,
-                                                                     C8, p.N)] * 50, 4, torch)
-            # per-column scales + bias + ReLU, and the online-pack path (B packed inside the call)
-            sv = torch.full((p.N,), p.scale, dtype=torch.float32, device="cuda")
-            bv = torch.zeros((p.N,), dtype=torch.int32, device="cuda")
-            msc = graph_time_ms([lambda: ng.ngemm_run_u8s8u8_requant_channel(
-                ctx, p.M, A, p.K, p.za, hb, p.zb, None, sv, bv, True, p.zc, C8, p.N)] * 50, 4, torch)
-            Bdev = torch.from_numpy(p.B).cuda()
-            uwb = ng.ngemm_unpacked_workspace_bytes(p.M, p.N, p.K)
-            uws = torch.empty(uwb, dtype=torch.uint8, device="cuda")
-            msu = graph_time_ms([lambda: ng.ngemm_run_u8s8s32_unpacked(
-                ctx, p.M, p.N, p.K, A, p.K, p.za, Bdev, p.K, p.zb, C, p.N, uws, uwb)] * 50, 4, torch)
-            # a weight zero-point (the row sums are formed inside these kernels: no extra launch)
-            wsz = ng.ngemm_workspace_bytes(p.M, p.N, p.K)
-            wz = torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda")
-            msz = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, p.M, A, p.K, p.za, hb, 5, C, p.N, wz, wsz)] * 50, 4, torch)
-            # after shape tuning (the fastest kernel for this shape, measured on these operands)
-            tuned = ng.ngemm_tune_u8s8s32(ctx, p.M, A, p.K, p.za, hb, p.zb, C, p.N)
-            mst = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, p.M, A, p.K, p.za, hb, p.zb, C, p.N)] * 50, 4, torch)
-            o = 2.0 * p.M * p.N * p.K
-            b32 = p.M * p.K + p.N * p.K + 4 * p.M * p.N
-            b8 = p.M * p.K + p.N * p.K + p.M * p.N
-            fc[p.name] = {"s32_us": round(ms * 1e3, 2), "s32_TOPS": round(o / (ms * 1e-3) / 1e12, 1),
-                          "s32_GBps": round(b32 / (ms * 1e-3) / 1e9, 1),
-                          "u8_us": round(ms8 * 1e3, 2), "u8_TOPS": round(o / (ms8 * 1e-3) / 1e12, 1),
-                          "u8_GBps": round(b8 / (ms8 * 1e-3) / 1e9, 1),
-                          "u8_per_channel_bias_relu_us": round(msc * 1e3, 2),
-                          "s32_unpacked_b_us": round(msu * 1e3, 2),
-                          "s32_weight_zero_point_5_us": round(msz * 1e3, 2),
-                          "s32_tuned_us": round(mst * 1e3, 2), "tuned_kernel": int(tuned)}
-            ng.ngemm_packed_b_free(hb)
-        extras["bert_fc"] = fc
-
-        # few tiles, long K: K split over the workgroups (the heuristic's choice) against one
-        # workgroup per tile (M > 32) or the streaming kernel (M <= 32)
-        sk_extra = {}
-        for (Ms, Ns, Ks) in ((64, 64, 65536), (256, 256, 16384), (512, 512, 16384), (100, 300, 30000), (16, 1024, 8192)):
-            rngs = wl.rng_for(4, 70 + Ms)
-            As = torch.from_numpy(wl.uniform_u8(rngs, Ms, Ks)).cuda()
-            hb, pk, _ = pack(wl.uniform_s8(rngs, Ns, Ks))
-            Cs = torch.empty((Ms, Ns), dtype=torch.int32, device="cuda")
-            C8s = torch.empty((Ms, Ns), dtype=torch.uint8, device="cuda")
-            wss = ng.ngemm_workspace_bytes(Ms, Ns, Ks)       # with room for the partial results (u8 output)
-            wsd = torch.empty(max(wss, 16), dtype=torch.uint8, device="cuda")
-            call = [lambda: ng.ngemm_run_u8s8s32(ctx, Ms, As, Ks, 0, hb, 0, Cs, Ns)] * 20
-            call8 = [lambda: ng.ngemm_run_u8s8u8_requant(ctx, Ms, As, Ks, 128, hb, 0, 2.0e-4, 128, C8s, Ns, wsd, wss)] * 20
-            ms_split = graph_time_ms(call, 10, torch)
-            ms_split8 = graph_time_ms(call8, 10, torch)
-            ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_SKINNY if Ms <= 32 else ng.NGEMM_KERNEL_TILE_64)
-            ms_plain = graph_time_ms(call, 10, torch)
-            ms_plain8 = graph_time_ms(call8, 10, torch)
-            ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_AUTO)
-            o = 2.0 * Ms * Ns * Ks
-            sk_extra["%dx%dx%d" % (Ms, Ns, Ks)] = {"split_k_us": round(ms_split * 1e3, 2), "unsplit_us": round(ms_plain * 1e3, 2),
-                                                   "split_k_TOPS": round(o / (ms_split * 1e-3) / 1e12, 1),
-                                                   "u8_split_k_us": round(ms_split8 * 1e3, 2),
-                                                   "u8_unsplit_us": round(ms_plain8 * 1e3, 2)}
-            ng.ngemm_packed_b_free(hb)
-        extras["underfilled_long_k"] = sk_extra
-
-        # batched odd shapes
-        probs = wl.batched()
-        items, keep, hs = [], [], []
-        for p in probs:
-            hb, pk, _ = pack(p.B)
-            A = torch.from_numpy(p.A).cuda()
-            C = torch.empty((p.M, p.N), dtype=torch.int32, device="cuda")
-            keep.append((pk, A, C))
-            hs.append(hb)
-            items.append((p.M, A, p.K, p.za, p.zb, hb, C, p.N))
-        arr = ng.make_problems(items)
-        wsb = ng.ngemm_batched_workspace_bytes(arr)
-        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
-        msb = gpu_time_ms(lambda: ng.ngemm_run_batched_u8s8s32(ctx, arr, ws, wsb), 20, 3, torch)
-        o = sum(2.0 * p.M * p.N * p.K for p in probs)
-        by = sum(p.M * p.K + p.N * p.K + 4 * p.M * p.N for p in probs)
-        extras["batched_64_odd_shapes"] = {"ms": round(msb, 4), "TOPS": round(o / (msb * 1e-3) / 1e12, 2),
-                                           "GBps": round(by / (msb * 1e-3) / 1e9, 1)}
+        seq = [(lambda t=t: ng.ngemm_run_u8s8s32(ctx, M, A_dev[t % 16], K, 0, hs[t % ncopies], 0, C, N))
+               for t in range(ncopies)]
+        ms2 = graph_time_ms(seq, 6, torch)
+        entry["rotating_weights_us"] = round(ms2 * 1e3, 3)
+        entry["rotating_weights_GBps"] = round(abytes / (ms2 * 1e-3) / 1e9, 1)
+        entry["rotating_frac_of_hbm_peak"] = round(abytes / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        # the same rotating GEMMs through the batched entry point, 59 independent problems per call
+        # (one grouped launch each): what a server with many small GEMMs in flight would issue
+        Cb = [torch.empty((M, N), dtype=torch.int32, device="cuda") for _ in range(per)]
+        batches = [ng.make_problems([(M, A_dev[(g * per + t) % 16], K, 0, 0, hs[g * per + t], Cb[t], N)
+                                     for t in range(per)]) for g in range(ncopies // per)]
+        seqb = [(lambda arr=arr: ng.ngemm_run_batched_u8s8s32(ctx, arr)) for arr in batches]
+        msb = graph_time_ms(seqb, 6, torch) / per
+        entry["batched_members_per_call"] = per
+        entry["rotating_weights_batched_us_per_gemm"] = round(msb * 1e3, 3)
+        entry["rotating_weights_batched_GBps"] = round(abytes / (msb * 1e-3) / 1e9, 1)
+        entry["rotating_batched_frac_of_hbm_peak"] = round(abytes / (msb * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        # kernel-only durations of the same launches (no gap between launches), from the trace summary
+        for key in ("as_specified", "rotating", "rotating_batched"):
+            us = profile_figure(SKINNY_PROFILE, "%s_kernel_only_us_per_gemm_M%d" % (key, M))
+            if us:
+                entry["%s_kernel_only_GBps_from_profile" % key] = round(abytes / (us * 1e-6) / 1e9, 1)
         for x in hs:
             ng.ngemm_packed_b_free(x)
-        del keep, items
+        ng.ngemm_packed_b_free(hb)
+        del pool
+        sk["M%d" % M] = entry
+    sk["kernel_only_source"] = "profiles/%s (rocprofv3 --kernel-trace of this section, not this run)" % SKINNY_PROFILE
+    # launch floor: the smallest possible call through the same entry point, in the same graph
+    tinyB = torch.zeros((32, 64), dtype=torch.int8, device="cuda")
+    tb = ng.ngemm_packed_b_bytes(64, 32)
+    tpk = torch.empty(tb, dtype=torch.uint8, device="cuda")
+    th = ng.ngemm_pack_b(ctx, 64, 32, tinyB, 64, tpk, tb)
+    tA = torch.zeros((1, 64), dtype=torch.uint8, device="cuda")
+    tC = torch.empty((1, 32), dtype=torch.int32, device="cuda")
+    msf = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, 1, tA, 64, 0, th, 0, tC, 32)] * 250, 4, torch)
+    sk["launch_floor_us_1x32x64"] = round(msf * 1e3, 3)
+    ng.ngemm_packed_b_free(th)
+    # asymptotes: the same kernel on weights large enough to leave launch and latency behind
+    # (rotating copies, 512 MiB or more in all, so that every byte comes from HBM)
+    for (Mb, Nb, Kb, ncp) in ((16, 16384, 4096, 8), (16, 32768, 8192, 3), (1, 32768, 8192, 3)):
+        rngb = wl.rng_for(3, 90 + Mb)
+        Bbig = wl.uniform_s8(rngb, Nb, Kb)
+        Abig = torch.from_numpy(wl.uniform_u8(rngb, Mb, Kb)).cuda()
+        nb = ng.ngemm_packed_b_bytes(Kb, Nb)
+        pool = torch.empty((ncp, nb), dtype=torch.uint8, device="cuda")
+        Bd2 = torch.from_numpy(Bbig).cuda()
+        hs = [ng.ngemm_pack_b(ctx, Kb, Nb, Bd2, Kb, pool[c], nb) for c in range(ncp)]
+        Cb = torch.empty((Mb, Nb), dtype=torch.int32, device="cuda")
+        seq = [(lambda t=t: ng.ngemm_run_u8s8s32(ctx, Mb, Abig, Kb, 0, hs[t % ncp], 0, Cb, Nb))
+               for t in range(4 * ncp)]
+        ms3 = graph_time_ms(seq, 5, torch)
+        ab = Kb * Nb + Mb * Kb + 4 * Mb * Nb
+        sk["asymptote_M%d_N%d_K%d" % (Mb, Nb, Kb)] = {
+            "us": round(ms3 * 1e3, 2), "GBps": round(ab / (ms3 * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(ab / (ms3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        for x in hs:
+            ng.ngemm_packed_b_free(x)
+        del pool, Bd2, Bbig
+    return sk
 
-        # the other integer types on the headline shape: signed A, and unsigned B (shifted in the pack)
-        rngt = wl.rng_for(4, 50)
-        At = torch.from_numpy(wl.uniform_u8(rngt, n, n)).cuda()
-        Bt = torch.from_numpy(wl.uniform_s8(rngt, n, n)).cuda()
-        Ct = torch.empty((n, n), dtype=torch.int32, device="cuda")
-        nb = ng.ngemm_packed_b_bytes(n, n)
-        pks, pku = (torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(2))
-        hsg = ng.ngemm_pack_b(ctx, n, n, Bt, n, pks, nb)
-        hun = ng.ngemm_pack_b_u8(ctx, n, n, Bt.view(torch.uint8), n, pku, nb)
-        ms_ss = gpu_time_ms(lambda: ng.ngemm_run_s8s8s32(ctx, n, At.view(torch.int8), n, 0, hsg, 0, Ct, n), 100, 100, torch)
-        ms_uu = gpu_time_ms(lambda: ng.ngemm_run_u8u8s32(ctx, n, At, n, 0, hun, 128, Ct, n), 100, 100, torch)
-        extras["other_integer_types_%d" % n] = {"s8s8s32_TOPS": round(ops / (ms_ss * 1e-3) / 1e12, 1),
-                                                "u8u8s32_TOPS": round(ops / (ms_uu * 1e-3) / 1e12, 1)}
-        # requantised u8 output on the headline shape (per-tensor scale)
-        C8t = torch.empty((n, n), dtype=torch.uint8, device="cuda")
-        ms_q = gpu_time_ms(lambda: ng.ngemm_run_u8s8u8_requant(ctx, n, At, n, 128, hsg, 0, 2.0e-4, 128, C8t, n), 100, 100, torch)
-        extras["other_integer_types_%d" % n]["u8s8u8_requant_TOPS"] = round(ops / (ms_q * 1e-3) / 1e12, 1)
-        del C8t
-        ng.ngemm_packed_b_free(hsg)
-        ng.ngemm_packed_b_free(hun)
-        # 16-bit operands through byte planes (four 8-bit matrix ops per block)
-        A16 = torch.from_numpy(rngt.integers(-32768, 32768, size=(n, n), dtype=np.int16)).cuda()
-        B16 = torch.from_numpy(rngt.integers(-32768, 32768, size=(n, n), dtype=np.int16)).cuda()
-        nb16 = ng.ngemm_packed_b_bytes_s16(n, n)
-        pk16 = torch.empty(nb16, dtype=torch.uint8, device="cuda")
-        h16 = ng.ngemm_pack_b_s16(ctx, n, n, B16, n, pk16, nb16)
-        wsb16 = ng.ngemm_workspace_bytes(n, n, n)
-        ws16 = torch.empty(wsb16, dtype=torch.uint8, device="cuda")
-        ms_16 = gpu_time_ms(lambda: ng.ngemm_run_s16s16s32(ctx, n, A16, n, 0, h16, 0, Ct, n, ws16, wsb16), 30, 30, torch)
-        extras["other_integer_types_%d" % n]["s16s16s32_TOPS"] = round(ops / (ms_16 * 1e-3) / 1e12, 1)
-        ng.ngemm_packed_b_free(h16)
-        del A16, B16, pk16
-        # both operands as inputs: B read from its plain [N x K] storage, nothing packed
-        uwb = ng.ngemm_unpacked_workspace_bytes(n, n, n)
+
+def bench_fc(b, args):
+    """Config 2: the transformer FC shapes."""
+    ng, wl, torch, ctx = b.ng, b.wl, b.torch, b.ctx
+    fc = {}
+    for idx in range(3):
+        p = wl.bert_fc(idx)
+        hb, pk, _ = b.pack(p.B)
+        A = torch.from_numpy(p.A).cuda()
+        C = torch.empty((p.M, p.N), dtype=torch.int32, device="cuda")
+        C8 = torch.empty((p.M, p.N), dtype=torch.uint8, device="cuda")
+        ms = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, p.M, A, p.K, p.za, hb, p.zb, C, p.N)] * 50, 4, torch)
+        ms8 = graph_time_ms([lambda: ng.ngemm_run_u8s8u8_requant(ctx, p.M, A, p.K, p.za, hb, p.zb, p.scale, p.zc,
+                                                                 C8, p.N)] * 50, 4, torch)
+        # per-column scales + bias + ReLU, and the online-pack path (B packed inside the call)
+        sv = torch.full((p.N,), p.scale, dtype=torch.float32, device="cuda")
+        bv = torch.zeros((p.N,), dtype=torch.int32, device="cuda")
+        msc = graph_time_ms([lambda: ng.ngemm_run_u8s8u8_requant_channel(
+            ctx, p.M, A, p.K, p.za, hb, p.zb, None, sv, bv, True, p.zc, C8, p.N)] * 50, 4, torch)
+        Bdev = torch.from_numpy(p.B).cuda()
+        uwb = ng.ngemm_unpacked_workspace_bytes(p.M, p.N, p.K)
         uws = torch.empty(uwb, dtype=torch.uint8, device="cuda")
-        ms_un = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32_unpacked(ctx, n, n, n, At, n, 0, Bt, n, 0, Ct, n, uws, uwb),
-                            100, 100, torch)
-        extras["unpacked_b_%d" % n] = {"ms": round(ms_un, 4), "TOPS": round(ops / (ms_un * 1e-3) / 1e12, 1)}
-        # The same launch on operands that do not change (A = 129, B = 1): on uniform data the chip runs
-        # at its power cap (shader clock about 1.8 GHz), on such data at its full clock.  Context only.
-        Ac = torch.full((n, n), 129, dtype=torch.uint8, device="cuda")
-        Bc = torch.ones((n, n), dtype=torch.int8, device="cuda")
-        hc = ng.ngemm_pack_b(ctx, n, n, Bc, n, pks, nb)
-        ms_c = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32(ctx, n, Ac, n, 0, hc, 0, Ct, n), 200, 200, torch)
-        ng.ngemm_packed_b_free(hc)
-        pl = {"constant_operands_TOPS": round(ops / (ms_c * 1e-3) / 1e12, 1),
-              "constant_operands_frac_of_peak": round(ops / (ms_c * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4)}
-        # the vendor library's int8 GEMM on the same operands (s8 x s8, B column-major), for context
-        try:
-            Bcol = Bt.t()
-            ms_lu = gpu_time_ms(lambda: torch._int_mm(At.view(torch.int8), Bcol), 100, 100, torch)
-            ms_lc = gpu_time_ms(lambda: torch._int_mm(Ac.view(torch.int8), Bc.t()), 100, 100, torch)
-            pl["library_int_mm_uniform_TOPS"] = round(ops / (ms_lu * 1e-3) / 1e12, 1)
-            pl["library_int_mm_constant_TOPS"] = round(ops / (ms_lc * 1e-3) / 1e12, 1)
-        except Exception as e:  # not every build of the framework has it
-            pl["library_int_mm"] = "unavailable: %s" % type(e).__name__
-        # the matrix pipe by itself: a loop of nothing but matrix instructions on register operands
-        # (no LDS, no memory), which is what the power cap leaves of the published peak on such data
-        try:
-            import ctypes
-            from paper_1910_00178_amd.build import PROBE_LIB
-            probe = ctypes.CDLL(PROBE_LIB)
-            probe.ngemm_probe_mfma_rate.restype = ctypes.c_int
-            probe.ngemm_probe_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
-            torch.cuda.synchronize()
-            for shape, sname in ((0, "16x16x64"), (1, "32x32x32")):
-                for rnd, dname in ((1, "uniform"), (0, "constant")):
-                    t = ctypes.c_double(0.0)
-                    rc = probe.ngemm_probe_mfma_rate(shape, rnd, ctypes.byref(t))
-                    pl["matrix_pipe_only_%s_%s_TOPS" % (sname, dname)] = round(t.value, 1) if rc == 0 else "error %d" % rc
-            ceil = pl.get("matrix_pipe_only_16x16x64_uniform_TOPS")
-            if isinstance(ceil, float) and ceil > 0:
-                pl["headline_frac_of_matrix_pipe_only_uniform"] = round(result["value"] / ceil, 4)
-        except Exception as e:
-            pl["matrix_pipe_only"] = "unavailable: %s" % type(e).__name__
-        extras["power_limit_context_%d" % n] = pl
+        msu = graph_time_ms([lambda: ng.ngemm_run_u8s8s32_unpacked(
+            ctx, p.M, p.N, p.K, A, p.K, p.za, Bdev, p.K, p.zb, C, p.N, uws, uwb)] * 50, 4, torch)
+        # a weight zero-point (the row sums are formed inside these kernels: no extra launch)
+        wsz = ng.ngemm_workspace_bytes(p.M, p.N, p.K)
+        wz = torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda")
+        msz = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, p.M, A, p.K, p.za, hb, 5, C, p.N, wz, wsz)] * 50, 4, torch)
+        # after shape tuning (the fastest kernel for this shape, measured on these operands)
+        tuned = ng.ngemm_tune_u8s8s32(ctx, p.M, A, p.K, p.za, hb, p.zb, C, p.N)
+        mst = graph_time_ms([lambda: ng.ngemm_run_u8s8s32(ctx, p.M, A, p.K, p.za, hb, p.zb, C, p.N)] * 50, 4, torch)
+        o = 2.0 * p.M * p.N * p.K
+        b32 = p.M * p.K + p.N * p.K + 4 * p.M * p.N
+        b8 = p.M * p.K + p.N * p.K + p.M * p.N
+        fc[p.name] = {"s32_us": round(ms * 1e3, 2), "s32_TOPS": round(o / (ms * 1e-3) / 1e12, 1),
+                      "s32_GBps": round(b32 / (ms * 1e-3) / 1e9, 1),
+                      "u8_us": round(ms8 * 1e3, 2), "u8_TOPS": round(o / (ms8 * 1e-3) / 1e12, 1),
+                      "u8_GBps": round(b8 / (ms8 * 1e-3) / 1e9, 1),
+                      "u8_per_channel_bias_relu_us": round(msc * 1e3, 2),
+                      "s32_unpacked_b_us": round(msu * 1e3, 2),
+                      "s32_weight_zero_point_5_us": round(msz * 1e3, 2),
+                      "s32_tuned_us": round(mst * 1e3, 2), "tuned_kernel": int(tuned)}
+        ng.ngemm_packed_b_free(hb)
+    return fc
+
+
+def bench_longk(b, args):
+    """Few tiles, long K: K split over the workgroups (the heuristic's choice) against one
+    workgroup per tile (M > 32) or the streaming kernel (M <= 32)."""
+    ng, wl, torch, ctx = b.ng, b.wl, b.torch, b.ctx
+    out = {}
+    for (Ms, Ns, Ks) in ((64, 64, 65536), (256, 256, 16384), (512, 512, 16384), (100, 300, 30000), (16, 1024, 8192)):
+        rngs = wl.rng_for(4, 70 + Ms)
+        As = torch.from_numpy(wl.uniform_u8(rngs, Ms, Ks)).cuda()
+        hb, pk, _ = b.pack(wl.uniform_s8(rngs, Ns, Ks))
+        Cs = torch.empty((Ms, Ns), dtype=torch.int32, device="cuda")
+        C8s = torch.empty((Ms, Ns), dtype=torch.uint8, device="cuda")
+        wss = ng.ngemm_workspace_bytes(Ms, Ns, Ks)       # with room for the partial results (u8 output)
+        wsd = torch.empty(max(wss, 16), dtype=torch.uint8, device="cuda")
+        call = [lambda: ng.ngemm_run_u8s8s32(ctx, Ms, As, Ks, 0, hb, 0, Cs, Ns)] * 20
+        call8 = [lambda: ng.ngemm_run_u8s8u8_requant(ctx, Ms, As, Ks, 128, hb, 0, 2.0e-4, 128, C8s, Ns, wsd, wss)] * 20
+        ms_split = graph_time_ms(call, 10, torch)
+        ms_split8 = graph_time_ms(call8, 10, torch)
+        ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_SKINNY if Ms <= 32 else ng.NGEMM_KERNEL_TILE_64)
+        ms_plain = graph_time_ms(call, 10, torch)
+        ms_plain8 = graph_time_ms(call8, 10, torch)
+        ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_AUTO)
+        o = 2.0 * Ms * Ns * Ks
+        out["%dx%dx%d" % (Ms, Ns, Ks)] = {"split_k_us": round(ms_split * 1e3, 2), "unsplit_us": round(ms_plain * 1e3, 2),
+                                          "split_k_TOPS": round(o / (ms_split * 1e-3) / 1e12, 1),
+                                          "u8_split_k_us": round(ms_split8 * 1e3, 2),
+                                          "u8_unsplit_us": round(ms_plain8 * 1e3, 2)}
+        ng.ngemm_packed_b_free(hb)
+    return out
+
+
+def bench_batched(b, args):
+    """Config 5: 64 odd shapes in one call."""
+    ng, wl, torch, ctx = b.ng, b.wl, b.torch, b.ctx
+    probs = wl.batched()
+    items, keep, hs = [], [], []
+    for p in probs:
+        hb, pk, _ = b.pack(p.B)
+        A = torch.from_numpy(p.A).cuda()
+        C = torch.empty((p.M, p.N), dtype=torch.int32, device="cuda")
+        keep.append((pk, A, C))
+        hs.append(hb)
+        items.append((p.M, A, p.K, p.za, p.zb, hb, C, p.N))
+    arr = ng.make_problems(items)
+    wsb = ng.ngemm_batched_workspace_bytes(arr)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    msb = gpu_time_ms(lambda: ng.ngemm_run_batched_u8s8s32(ctx, arr, ws, wsb), 20, 3, torch)
+    o = sum(2.0 * p.M * p.N * p.K for p in probs)
+    by = sum(p.M * p.K + p.N * p.K + 4 * p.M * p.N for p in probs)
+    for x in hs:
+        ng.ngemm_packed_b_free(x)
+    return {"ms": round(msb, 4), "TOPS": round(o / (msb * 1e-3) / 1e12, 2), "GBps": round(by / (msb * 1e-3) / 1e9, 1)}
+
+
+def bench_types(b, args, extras):
+    """The other entry points on the headline shape: signed A, unsigned B (shifted in the pack),
+    requantised output, 16-bit operands, unpacked B, and the headline launch on constant operands."""
+    ng, wl, torch, np, ctx = b.ng, b.wl, b.torch, b.np, b.ctx
+    n = args.size
+    ops = 2.0 * n * n * n
+    rngt = wl.rng_for(4, 50)
+    At = torch.from_numpy(wl.uniform_u8(rngt, n, n)).cuda()
+    Bt = torch.from_numpy(wl.uniform_s8(rngt, n, n)).cuda()
+    Ct = torch.empty((n, n), dtype=torch.int32, device="cuda")
+    nb = ng.ngemm_packed_b_bytes(n, n)
+    pks, pku = (torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(2))
+    hsg = ng.ngemm_pack_b(ctx, n, n, Bt, n, pks, nb)
+    hun = ng.ngemm_pack_b_u8(ctx, n, n, Bt.view(torch.uint8), n, pku, nb)
+    ms_ss = gpu_time_ms(lambda: ng.ngemm_run_s8s8s32(ctx, n, At.view(torch.int8), n, 0, hsg, 0, Ct, n), 100, 100, torch)
+    ms_uu = gpu_time_ms(lambda: ng.ngemm_run_u8u8s32(ctx, n, At, n, 0, hun, 128, Ct, n), 100, 100, torch)
+    ty = {"s8s8s32_TOPS": round(ops / (ms_ss * 1e-3) / 1e12, 1), "u8u8s32_TOPS": round(ops / (ms_uu * 1e-3) / 1e12, 1)}
+    # requantised u8 output on the headline shape (per-tensor scale)
+    C8t = torch.empty((n, n), dtype=torch.uint8, device="cuda")
+    ms_q = gpu_time_ms(lambda: ng.ngemm_run_u8s8u8_requant(ctx, n, At, n, 128, hsg, 0, 2.0e-4, 128, C8t, n), 100, 100, torch)
+    ty["u8s8u8_requant_TOPS"] = round(ops / (ms_q * 1e-3) / 1e12, 1)
+    del C8t
+    ng.ngemm_packed_b_free(hsg)
+    ng.ngemm_packed_b_free(hun)
+    # 16-bit operands through byte planes (four 8-bit matrix ops per block)
+    A16 = torch.from_numpy(rngt.integers(-32768, 32768, size=(n, n), dtype=np.int16)).cuda()
+    B16 = torch.from_numpy(rngt.integers(-32768, 32768, size=(n, n), dtype=np.int16)).cuda()
+    nb16 = ng.ngemm_packed_b_bytes_s16(n, n)
+    pk16 = torch.empty(nb16, dtype=torch.uint8, device="cuda")
+    h16 = ng.ngemm_pack_b_s16(ctx, n, n, B16, n, pk16, nb16)
+    wsb16 = ng.ngemm_workspace_bytes(n, n, n)
+    ws16 = torch.empty(wsb16, dtype=torch.uint8, device="cuda")
+    ms_16 = gpu_time_ms(lambda: ng.ngemm_run_s16s16s32(ctx, n, A16, n, 0, h16, 0, Ct, n, ws16, wsb16), 30, 30, torch)
+    ty["s16s16s32_TOPS"] = round(ops / (ms_16 * 1e-3) / 1e12, 1)
+    ng.ngemm_packed_b_free(h16)
+    del A16, B16, pk16
+    extras["other_integer_types_%d" % n] = ty
+    # both operands as inputs: B read from its plain [N x K] storage, nothing packed
+    uwb = ng.ngemm_unpacked_workspace_bytes(n, n, n)
+    uws = torch.empty(uwb, dtype=torch.uint8, device="cuda")
+    ms_un = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32_unpacked(ctx, n, n, n, At, n, 0, Bt, n, 0, Ct, n, uws, uwb),
+                        100, 100, torch)
+    extras["unpacked_b_%d" % n] = {"ms": round(ms_un, 4), "TOPS": round(ops / (ms_un * 1e-3) / 1e12, 1)}
+    # The same launch on operands that do not change (A = 129, B = 1): on uniform data the chip runs
+    # at its power cap (shader clock about 1.8 GHz), on such data at its full clock.  Context only.
+    Ac = torch.full((n, n), 129, dtype=torch.uint8, device="cuda")
+    Bc = torch.ones((n, n), dtype=torch.int8, device="cuda")
+    hc = ng.ngemm_pack_b(ctx, n, n, Bc, n, pks, nb)
+    ms_c = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32(ctx, n, Ac, n, 0, hc, 0, Ct, n), 200, 200, torch)
+    ng.ngemm_packed_b_free(hc)
+    extras["power_limit_context_%d" % n] = {
+        "constant_operands_TOPS": round(ops / (ms_c * 1e-3) / 1e12, 1),
+        "constant_operands_frac_of_peak": round(ops / (ms_c * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
+        "matrix_pipe_only_rates": "profiles/matrix_pipe_power_limit.txt"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    # the clocks of an idle MI355X take some 50 ms of this kernel to settle: the defaults warm up
+    # long enough for the timed steps to see the sustained state (0.2 s in all)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--size", type=int, default=8192, help="square size of the headline workload")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
+    ap.add_argument("--sections", default="all",
+                    help="comma-separated extras to run, of: %s (default all)" % ", ".join(SECTIONS))
+    ap.add_argument("--skip-headline", action="store_true",
+                    help="run the chosen extras only (to profile one kernel class); the line then carries no "
+                         "headline value")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=16.0, help="target oracle wall time")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    want = set(SECTIONS) if args.sections == "all" else set(x for x in args.sections.split(",") if x)
+    if args.no_extras:
+        want = set()
+    unknown = want - set(SECTIONS)
+    if unknown:
+        print("bench.py: unknown section(s) %s" % ", ".join(sorted(unknown)), file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1910_00178_amd as ng
+    from paper_1910_00178_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    ctx = ng.ngemm_create(0)
+    b = Bench(ng, wl, torch, np, ctx)
+
+    result = {}
+    if not args.skip_headline:
+        bench_headline(b, args, result)
+    else:
+        result["metric"] = "extras only (--skip-headline)"
+        result["value"] = None
+    if want:
+        extras = {}
+        if "skinny" in want:
+            extras["skinny"] = bench_skinny(b, args)
+        if "fc" in want:
+            extras["bert_fc"] = bench_fc(b, args)
+        if "longk" in want:
+            extras["underfilled_long_k"] = bench_longk(b, args)
+        if "batched" in want:
+            extras["batched_64_odd_shapes"] = bench_batched(b, args)
+        if "types" in want:
+            bench_types(b, args, extras)
         result["extras"] = extras
 
     ng.ngemm_destroy(ctx)

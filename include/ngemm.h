@@ -66,13 +66,18 @@ enum {
 const char *ngemm_status_string(ngemm_status s);
 
 /*
- * Create a context bound to HIP device `device_ordinal`.  Fails with
- * NGEMM_ERR_DEVICE when there is no such device and NGEMM_ERR_UNSUPPORTED_ARCH
- * when it is not a gfx950 part.  Makes no large allocation.
+ * Create a context bound to HIP device `device_ordinal`: the handle under which a weight operand
+ * is packed once and multiplied many times (Sec. 3.1.1 and Sec. 4 "Layout": the marshalling is
+ * set-up work, outside the GEMM calls).  Reads the device's compute-unit and XCD counts, which
+ * the launches are sized by.  Fails with NGEMM_ERR_DEVICE when there is no such device and
+ * NGEMM_ERR_UNSUPPORTED_ARCH when it is not a gfx950 part.  Makes no large allocation.  *out is
+ * a host object owned by the caller until ngemm_destroy.
  */
 ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal);
 
-/* Destroy a context.  NULL is accepted. */
+/* Destroy a context (the end of the pack-once / multiply-many lifetime of Sec. 4 "Layout").  Host
+ * memory only: packed operands and every other device buffer stay with the caller.  NULL is
+ * accepted; a pointer that is not a live context gives NGEMM_ERR_INVALID_ARG. */
 ngemm_status ngemm_destroy(ngemm_ctx *ctx);
 
 /* Force one kernel for the run calls (NGEMM_KERNEL_*), or NGEMM_KERNEL_AUTO for
@@ -161,14 +166,22 @@ ngemm_status ngemm_packed_b_shape(const ngemm_packed_b *b, int64_t *K, int64_t *
  * for outputs of few tiles with a long K, room for the partial results of the K split (at
  * most 4 MiB).  A workspace that holds the row sums only is always enough: the K split then
  * adds its parts to C with atomic adds (int32 outputs) or is not used (u8 outputs).
+ * A workspace handed to a run call must be 16-byte aligned (NGEMM_ERR_INVALID_ARG otherwise):
+ * the kernels move it in 16-byte pieces.
  */
 size_t ngemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
- * C[i][j] = sum_k (A[i][k] - a_zero_point) * (B[k][j] - b_zero_point), int32.
+ * The GEMM of the problem statement (Sec. 2.1: unsigned 8-bit times signed 8-bit, 32-bit sums;
+ * Sec. 3.1 phases 1 and 2: every output element is accumulated in place over K, no reduction
+ * across vector lanes), on a B packed beforehand (Sec. 3.1.1):
+ *   C[i][j] = sum_k (A[i][k] - a_zero_point) * (B[k][j] - b_zero_point), int32.
+ *   A_dev: device, M rows of K bytes, pitch lda >= K; C_dev: device, M rows of N int32, pitch
+ *   ldc >= N; workspace_dev: device, ngemm_workspace_bytes(M, N, K) bytes or NULL (see there).
  *   a_zero_point in [0,255], b_zero_point in [-128,127], else INVALID_ARG.
  *   M == 0 or N == 0: nothing is written, NGEMM_OK.  K == 0: C is all zeros.
- * Asynchronous on `hip_stream`.  A and the packed buffer are only read.
+ * Asynchronous on `hip_stream`.  A and the packed buffer are only read; every buffer stays the
+ * caller's.  On an error nothing has been launched.
  */
 ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M,
                                const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
@@ -209,14 +222,16 @@ ngemm_status ngemm_run_s8s8s32(ngemm_ctx *ctx, int64_t M,
                                void *hip_stream);
 
 /*
- * Same sum with the fused requantise-to-u8 epilogue, applied to the int32
- * value c of every element in exactly this order:
+ * Same sum (Sec. 2.1, Sec. 3.1) with a requantise-to-u8 step fused behind it, the "operation
+ * fusion" that Sec. 4 names without a formula; this library fixes it as follows, applied to the
+ * int32 value c of every element in exactly this order:
  *     f = (float)c            binary32, round to nearest even
  *     g = f * scale           one binary32 multiply (not fused with anything)
  *     r = round-half-even(g)
  *     C[i][j] = (uint8) min(255, max(0, r + c_zero_point))
  * `scale` must be finite and in [2^-30, 2^30] (INVALID_ARG otherwise), which
- * keeps every intermediate a normal binary32 number.
+ * keeps every intermediate a normal binary32 number.  C_dev: device, M rows of N bytes, pitch
+ * ldc >= N; the other arguments, ownership and error behaviour as for ngemm_run_u8s8s32.
  */
 ngemm_status ngemm_run_u8s8u8_requant(ngemm_ctx *ctx, int64_t M,
                                       const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,

@@ -7,9 +7,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "ngemm.hip")
 LIB = os.path.join(HERE, "libngemm.so")
-# measurement aid of bench.py (the rate of the matrix pipe by itself), a library of its own
-PROBE_SRC = os.path.join(HERE, "csrc", "mfma_rate_probe.hip")
-PROBE_LIB = os.path.join(HERE, "libngemm_probe.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -35,7 +32,6 @@ def _compile(src, lib, verbose):
 
 
 def build_library(verbose=False):
-    _compile(PROBE_SRC, PROBE_LIB, verbose)
     return _compile(SRC, LIB, verbose)
 
 

@@ -17,6 +17,7 @@ struct ngemm_ctx {
     uint32_t magic;
     int device;
     int num_cus;
+    int num_xcd;             // XCDs (L2 domains) of the device; workgroup ids go round them in turn
     int force_kernel;
     int max_workgroups;      // 0 = one per compute unit
     // kernels found fastest by ngemm_tune_u8s8s32, by shape; consulted before the shape heuristic
@@ -43,17 +44,8 @@ constexpr uint32_t kCtxMagic = 0x4e47454du;   // "NGEM"
 constexpr uint32_t kPackMagic = 0x4e47504bu;  // "NGPK"
 constexpr int64_t kMaxDim = 0x7fffffff - 4096;
 constexpr int kSkinnyMaxM = 32;
-#ifndef NGEMM_WGM256
-#define NGEMM_WGM256 2
-#define NGEMM_WGN256 2
-#endif
-#ifndef NGEMM_STAGES256
-#define NGEMM_STAGES256 4
-#endif
-#ifndef NGEMM_BK256
-#define NGEMM_BK256 64
-#endif
-constexpr int BK256 = NGEMM_BK256;               // stage depth of the 256 x 256 configuration
+constexpr int BK256 = 64;                        // stage depth of the 256 x 256 configuration
+constexpr int kStages256 = 4;                    // ring depth of its direct-to-LDS form
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
@@ -72,6 +64,9 @@ struct DeviceGuard {
         if (hipGetDevice(&prev) != hipSuccess) return;
         ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
         if (prev == dev) prev = -1;
+        // the launches below are checked with hipGetLastError(): drop an error that other code on
+        // this thread left behind, so that it is not reported as one of ours
+        (void)hipGetLastError();
     }
     ~DeviceGuard()
     {
@@ -402,7 +397,7 @@ ngemm_status validate_run(const ngemm_ctx *ctx, const RunArgs &a, int *kernel_ou
 size_t rowsum_bytes(int64_t M) { return (size_t)round_up(M * 4, 256); }
 
 // Kernel parameters of one validated GEMM (row sums not yet attached).
-GemmParams make_params(const RunArgs &a)
+GemmParams make_params(const RunArgs &a, int nxcd)
 {
     const ngemm_packed_b *B = a.B;
     GemmParams p;
@@ -433,16 +428,18 @@ GemmParams make_params(const RunArgs &a)
     p.relu = a.relu;
     p.ksplit = 1;
     p.kchunk = 0;
+    p.nxcd = nxcd;
     return p;
 }
 
 // Launches one validated GEMM; `ws` must hold rowsum_bytes(M) when zb != 0.  What lies beyond those
 // bytes serves the K split for its partial results when there is enough of it.
-ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cus, void *ws, size_t ws_bytes, hipStream_t st)
+ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cus, int nxcd, void *ws, size_t ws_bytes,
+                        hipStream_t st)
 {
     const ngemm_packed_b *B = a.B;
     if (a.M == 0 || B->N == 0) return NGEMM_OK;
-    GemmParams p = make_params(a);
+    GemmParams p = make_params(a, nxcd);
     const bool dma_ok = (((uintptr_t)a.A | (uintptr_t)a.lda) & 15) == 0;
     int kchunk = 0, parts = 1;
     int32_t *part_ws = nullptr;
@@ -513,7 +510,7 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
                                    RawB{nullptr, 0});
             e = hipGetLastError();
         } else {
-            e = dma_ok ? launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, a.requant, num_cus, st)
+            e = dma_ok ? launch_tile_dma<256, 256, 2, 2, kStages256>(p, a.requant, num_cus, st)
                        : launch_tile<256, 256, 2, 2, BK256>(p, a.requant, st);
         }
         break;
@@ -532,9 +529,11 @@ ngemm_status run_common(ngemm_ctx *ctx, const RunArgs &a, void *ws, size_t ws_by
         if (!ws) return NGEMM_ERR_INVALID_ARG;
         if (ws_bytes < rowsum_bytes(a.M)) return NGEMM_ERR_BUFFER_TOO_SMALL;
     }
+    // the kernels read and write the workspace in 16-byte pieces
+    if (ws && ws_bytes > 0 && ((uintptr_t)ws & 15u) != 0) return NGEMM_ERR_INVALID_ARG;
     DeviceGuard g(ctx->device);
     if (!g.ok) return NGEMM_ERR_DEVICE;
-    return launch_run(a, kernel, workgroup_budget(ctx), ctx->num_cus > 0 ? ctx->num_cus : 256, ws, ws_bytes,
+    return launch_run(a, kernel, workgroup_budget(ctx), ctx->num_cus > 0 ? ctx->num_cus : 256, ctx->num_xcd, ws, ws_bytes,
                       (hipStream_t)stream);
 }
 
@@ -572,12 +571,19 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
     c->magic = kCtxMagic;
     c->device = device_ordinal;
     c->num_cus = prop.multiProcessorCount;
+    // XCDs: each has an L2 of its own, and consecutive workgroup ids are dispatched to them in turn
+    int nxcc = 0;
+    if (hipDeviceGetAttribute(&nxcc, hipDeviceAttributeNumberOfXccs, device_ordinal) != hipSuccess || nxcc < 1) {
+        (void)hipGetLastError();
+        nxcc = 8;                                    // the MI355X layout
+    }
+    c->num_xcd = nxcc;
     c->force_kernel = NGEMM_KERNEL_AUTO;
     c->max_workgroups = 0;
     {
         DeviceGuard g(device_ordinal);
         if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
-            allow_big_lds_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
+            allow_big_lds_dma<256, 256, 2, 2, kStages256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
             allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep<1>() != hipSuccess || allow_big_lds_deep<2>() != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 X64Cfg::kLdsBytes) != hipSuccess ||
@@ -685,8 +691,12 @@ ngemm_status ngemm_tune_u8s8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev,
             found = true;
         }
     if (!found) {
-        if (ctx->tuned.size() >= 4096) ctx->tuned.erase(ctx->tuned.begin());
-        ctx->tuned.push_back(ngemm_ctx::Tuned{M, B->N, B->K, best});
+        try {
+            if (ctx->tuned.size() >= 4096) ctx->tuned.erase(ctx->tuned.begin());
+            ctx->tuned.push_back(ngemm_ctx::Tuned{M, B->N, B->K, best});
+        } catch (...) {
+            return NGEMM_ERR_DEVICE;               // out of host memory: measured, but not remembered
+        }
     }
     if (best_kernel) *best_kernel = best;
     return NGEMM_OK;
@@ -943,6 +953,7 @@ ngemm_status ngemm_run_s16s16s32(ngemm_ctx *ctx, int64_t M, const int16_t *A_dev
     p.za_term = (uint32_t)(128 - a_zero_point);
     p.zb = (uint32_t)(b_zero_point - 128);
     p.kconst = 0u - (uint32_t)(b_zero_point - 128) * (uint32_t)(128 - a_zero_point) * (uint32_t)B->K;
+    p.nxcd = ctx->num_xcd;
     if (B->K > 0) {
         int32_t *rs = (int32_t *)workspace_dev;
         hipLaunchKernelGGL(rowsum_s16_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, A_dev, lda, (int)M,
@@ -992,7 +1003,7 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
         shape.K = K; shape.N = N; shape.Kp = round_up(K, 64); shape.Np = round_up(N, 32);
         shape.data = nullptr; shape.bytes = 0; shape.b_shift = 0; shape.elem_bytes = 1;
         RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, &shape, C_dev, ldc, false, 1.0f, 0};
-        GemmParams p = make_params(a);
+        GemmParams p = make_params(a, ctx->num_xcd);
         int32_t *colsum = (int32_t *)workspace_dev;
         int32_t *rowsum = (int32_t *)((uint8_t *)workspace_dev + round_up(shape.Np * 4, 256));
         p.Bp = nullptr;
@@ -1018,7 +1029,7 @@ ngemm_status ngemm_run_u8s8s32_unpacked(ngemm_ctx *ctx, int64_t M, int64_t N, in
             hipLaunchKernelGGL(gemm_tile_x64_kernel<true>, dim3((unsigned)(ntiles < budget ? ntiles : budget)), dim3(256),
                                X64Cfg::kLdsBytes, st, p, rawb);
             e = hipGetLastError();
-        } else e = launch_tile_dma<256, 256, NGEMM_WGM256, NGEMM_WGN256, NGEMM_STAGES256>(p, false, budget, st, &rawb);
+        } else e = launch_tile_dma<256, 256, 2, 2, kStages256>(p, false, budget, st, &rawb);
         return e == hipSuccess ? NGEMM_OK : NGEMM_ERR_DEVICE;
     }
     const size_t pb = (size_t)round_up((int64_t)ngemm_packed_b_bytes(K, N), 256);
@@ -1062,6 +1073,7 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
     // A fragments they read anyway.
     GroupParams tiles, skinny;
     tiles.count = skinny.count = 0;
+    tiles.nxcd = skinny.nxcd = ctx->num_xcd;
     tiles.unit_start[0] = skinny.unit_start[0] = 0;
     using TCfg = TileCfg<64, 64, 2, 2, 64>;
     auto flush = [&](GroupParams &gp, int which) -> hipError_t {
@@ -1108,7 +1120,7 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         const ngemm_problem &q = problems[t];
         if (q.M == 0 || q.B->N == 0) continue;
         RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
-        const GemmParams p = make_params(a);
+        const GemmParams p = make_params(a, ctx->num_xcd);
         if (q.M <= kSkinnyMaxM)
             skinny_members.push_back(Pending{p, p.npanels});
         else

@@ -57,6 +57,9 @@ struct GemmParams {
     // row pitch N rounded up to 4.
     int ksplit, kchunk;
     int32_t *part_ws;
+    // number of XCDs of the device (hipDeviceAttributeNumberOfXccs): consecutive workgroup ids are
+    // dispatched to them round-robin, which the tile order and the staggered epilogues build on
+    int nxcd;
 };
 
 // ---- small helpers -------------------------------------------------------------------------
@@ -304,15 +307,15 @@ struct TileCfg {
     static_assert(TM >= 1 && TN >= 1, "wave tile");
 };
 
-// XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them, each with
-// its own L2), so give each XCD one contiguous run of the logical tile order, and make that
+// XCD-aware tile order: consecutive workgroup ids land on different XCDs (`nxcd` of them, each
+// with its own L2), so give each XCD one contiguous run of the logical tile order, and make that
 // order walk groups of GM tile-rows column by column so that the tiles in flight on one XCD
 // share A row-panels and B column-panels.
-__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int &tm, int &tn)
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int nxcd, int &tm, int &tn)
 {
     const int nb = tiles_m * tiles_n;
-    const int q = nb >> 3, r = nb & 7;
-    const int xcd = bid & 7, local = bid >> 3;
+    const int q = nb / nxcd, r = nb - q * nxcd;
+    const int local = bid / nxcd, xcd = bid - local * nxcd;
     const int logical = xcd * q + (xcd < r ? xcd : r) + local;
     constexpr int GM = 4;
     const int per_group = GM * tiles_n;
@@ -561,7 +564,7 @@ __device__ __forceinline__ void tile_body_staged(const GemmParams &p, int tile, 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     int tm, tn;
-    tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
+    tile_of_block(tile, p.tiles_m, p.tiles_n, p.nxcd, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int nslices = p.Kp / 32;
     const int nfull = p.K / BK;                        // stages that lie completely inside K
@@ -870,6 +873,7 @@ struct GroupMember {
 };
 struct GroupParams {
     int count;
+    int nxcd;                // XCDs of the device (see GemmParams)
     int unit_start[kGroupMax + 1];
     GroupMember prob[kGroupMax];
 };
@@ -886,9 +890,10 @@ __device__ __forceinline__ int group_find(const GroupParams &g, int bid)
 
 // The full parameter set of a member; tiles are counted for BM x BN workgroup tiles.
 template <int BM, int BN>
-__device__ __forceinline__ GemmParams group_member_params(const GroupMember &m)
+__device__ __forceinline__ GemmParams group_member_params(const GroupMember &m, int nxcd)
 {
     GemmParams p;
+    p.nxcd = nxcd;
     p.A = m.A;
     p.lda = m.lda;
     p.Bp = m.Bp;
@@ -929,7 +934,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_group_tile_kernel(const G
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int q = group_find(g, blockIdx.x);
-    const GemmParams p = group_member_params<BM, BN>(g.prob[q]);
+    const GemmParams p = group_member_params<BM, BN>(g.prob[q], g.nxcd);
     tile_body_staged<BM, BN, WGM, WGN, BK, false, true, kGroupRing>(p, blockIdx.x - g.unit_start[q], lds);
 }
 
@@ -1036,7 +1041,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_dma_kernel(const Gem
 
     for (int tile = w; tile < ntiles; tile += G) {
         int tm, tn;
-        tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
+        tile_of_block(tile, p.tiles_m, p.tiles_n, p.nxcd, tm, tn);
         const int m0 = tm * BM, n0 = tn * BN;
 
         // Loader: this lane's source addresses for the blocks its wavefront copies.
@@ -1335,11 +1340,11 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     // moments (measured: epilogue 8.7 -> 6.7 us per tile on uniform data, 9.6 -> 5.7 us at the full
     // clock, for one start delay of at most 10 us).
     if (ntiles >= 3 * gsz)
-        for (int sk = 0; sk < 3 * (int)((blockIdx.x >> 3) & 3); ++sk) __builtin_amdgcn_s_sleep(32);
+        for (int sk = 0; sk < 3 * (int)((blockIdx.x / (unsigned)p.nxcd) & 3); ++sk) __builtin_amdgcn_s_sleep(32);
 
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
-        tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
+        tile_of_block(tile, p.tiles_m, p.tiles_n, p.nxcd, tm, tn);
         const int m0 = tm * 256, n0 = tn * 256;
 
         // (the loaders' lane arithmetic is redone per tile: kept across the main loop it would be
@@ -1832,7 +1837,7 @@ __global__ __launch_bounds__(256) void gemm_tile_deep_kernel(const GemmParams p)
         const int nstages = nst + (rem > 0 ? 1 : 0);
         const bool has_tail = nsub * 64 < kc;
         int tm, tn;
-        tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
+        tile_of_block(tile, p.tiles_m, p.tiles_n, p.nxcd, tm, tn);
         const int m0 = tm * BMN, n0 = tn * BMN;
 
         // Loader: wavefront v copies, for every sub-block, the 16-row blocks v, v+4, ... of the A
@@ -2201,7 +2206,7 @@ __global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
 
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
-        tile_of_block(tile, p.tiles_m, p.tiles_n, tm, tn);
+        tile_of_block(tile, p.tiles_m, p.tiles_n, p.nxcd, tm, tn);
         const int m0 = tm * 128, n0 = tn * 128;
 
         const uint8_t *a_src[2], *b_src[2];
@@ -2528,7 +2533,7 @@ __global__ __launch_bounds__(512) void gemm_group_skinny_kernel(const GroupParam
 {
     extern __shared__ int red[];
     const int q = group_find(g, blockIdx.x);
-    const GemmParams p = group_member_params<64, 64>(g.prob[q]);
+    const GemmParams p = group_member_params<64, 64>(g.prob[q], g.nxcd);
     skinny_body<false, 1, true>(p, blockIdx.x - g.unit_start[q], 4 * ((p.M + 7) / 8), red);
 }
 
