@@ -293,8 +293,45 @@ void launch_skinny_p(const GemmParams &p, bool requant, int nwaves, int nregs, s
         hipLaunchKernelGGL((gemm_skinny_kernel<false, P>), grid, block, smem, st, p, nregs);
 }
 
+// The streaming kernel (a panel per wavefront, A in LDS) can serve a problem when its A fits the
+// 64 KiB of LDS a kernel gets without asking and there is a K to stream.
+bool stream_can_serve(int64_t M, int64_t Kp)
+{
+    return Kp >= 64 && stream_lds_bytes((int)M, Kp, kStreamMaxChunk, 0) <= kStreamMaxLds;
+}
+
+// LDS of a streaming launch for one problem: what it needs, plus room to park the sums of all but
+// the last panel of each wavefront as far as the 64 KiB allow.
+int stream_launch_lds(int M, int64_t Kp, int chunk)
+{
+    const int per_wave = chunk / kStreamWaves - 1;
+    int64_t want = stream_lds_bytes(M, Kp, chunk, per_wave > 0 ? per_wave : 0);
+    return (int)(want < kStreamMaxLds ? want : kStreamMaxLds);
+}
+
+// Panels per workgroup of the streaming kernel for `panels` panels in all: R per wavefront, one
+// as long as that makes no more than two rounds of resident wavefronts (16 per compute unit);
+// measured on 59 x 128 panels: R = 1 (1888 workgroups) 5.6 TB/s, R = 2 (944, one round) 5.45.
+int stream_chunk(int64_t panels, int num_cus)
+{
+    const int64_t max_waves = (int64_t)num_cus * 32;
+    int64_t R = (panels + max_waves - 1) / max_waves;
+    R = R < 1 ? 1 : (R > kStreamMaxChunk / kStreamWaves ? kStreamMaxChunk / kStreamWaves : R);
+    return (int)(kStreamWaves * R);
+}
+
 hipError_t launch_skinny(const GemmParams &p, bool requant, int num_cus, hipStream_t st)
 {
+    if (p.npanels >= 8 * num_cus && stream_can_serve(p.M, p.Kp)) {
+        const int chunk = stream_chunk(p.npanels, num_cus);
+        const dim3 grid((unsigned)((p.npanels + chunk - 1) / chunk)), block(kStreamWaves * 64);
+        const int smem = stream_launch_lds(p.M, p.Kp, chunk);
+        if (requant)
+            hipLaunchKernelGGL(gemm_stream_skinny_kernel<true>, grid, block, (size_t)smem, st, p, chunk, smem);
+        else
+            hipLaunchKernelGGL(gemm_stream_skinny_kernel<false>, grid, block, (size_t)smem, st, p, chunk, smem);
+        return hipGetLastError();
+    }
     const int nslices = p.Kp / 32;
     int nwaves = 1;
     while (nwaves < 8 && nwaves * 4 <= nslices) nwaves *= 2;    // at least two fragments per wavefront, at most 8 wavefronts
@@ -1071,10 +1108,13 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
     // the panels of its skinny members.  Launch count, not arithmetic, is what a batch of small odd
     // shapes costs, so there is no launch for the row sums either: both kernels form them from the
     // A fragments they read anyway.
-    GroupParams tiles, skinny;
-    tiles.count = skinny.count = 0;
-    tiles.nxcd = skinny.nxcd = ctx->num_xcd;
-    tiles.unit_start[0] = skinny.unit_start[0] = 0;
+    GroupParams tiles, skinny, stream;
+    tiles.count = skinny.count = stream.count = 0;
+    tiles.nxcd = skinny.nxcd = stream.nxcd = ctx->num_xcd;
+    tiles.chunk = skinny.chunk = stream.chunk = 0;
+    tiles.lds_bytes = skinny.lds_bytes = stream.lds_bytes = 0;
+    tiles.unit_start[0] = skinny.unit_start[0] = stream.unit_start[0] = 0;
+    const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
     using TCfg = TileCfg<64, 64, 2, 2, 64>;
     auto flush = [&](GroupParams &gp, int which) -> hipError_t {
         if (gp.count == 0) return hipSuccess;
@@ -1083,12 +1123,27 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
             if (which == 1)
                 hipLaunchKernelGGL((gemm_group_tile_kernel<64, 64, 2, 2, 64>), dim3(grid), dim3(256),
                                    (size_t)TCfg::kLdsBytes, st, gp);
-            else {
+            else if (which == 3) {
+                // streaming kernel: unit_start holds panel counts so far; turn them into chunks of
+                // panels sized for one even round of wavefronts over the whole group
+                const int chunk = stream_chunk(gp.unit_start[gp.count], cus);
+                int lds = 0;
+                int units = 0;
+                for (int t = 0; t < gp.count; ++t) {
+                    const int panels = gp.unit_start[t + 1] - gp.unit_start[t];
+                    gp.unit_start[t] = units;
+                    units += (panels + chunk - 1) / chunk;
+                    lds = std::max(lds, stream_launch_lds(gp.prob[t].M, round_up(gp.prob[t].K, 64), chunk));
+                }
+                gp.unit_start[gp.count] = units;
+                gp.chunk = chunk;
+                gp.lds_bytes = lds;
+                hipLaunchKernelGGL(gemm_group_stream_kernel, dim3((unsigned)units), dim3(kStreamWaves * 64), (size_t)lds, st, gp);
+            } else {
                 // wavefronts per panel: eight hide latency when the panels are few; with several
                 // panels per compute unit anyway, fewer wavefronts with more fragments each spend
                 // less on the final sum across wavefronts
-                const unsigned cus = (unsigned)(ctx->num_cus > 0 ? ctx->num_cus : 256);
-                const unsigned nw = grid >= 8 * cus ? 2 : (grid >= 4 * cus ? 4 : 8);
+                const unsigned nw = grid >= 8u * cus ? 2 : (grid >= 4u * cus ? 4 : 8);
                 hipLaunchKernelGGL(gemm_group_skinny_kernel, dim3(grid), dim3(64 * nw), (size_t)(nw * 16 * 64 * 4), st, gp);
             }
         }
@@ -1109,10 +1164,11 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
     // Members with the longest K first: a workgroup's time grows with K, and the grid is handed out
     // in order, so the long ones start at once and the many short ones fill in around them.
     struct Pending { GemmParams p; int64_t units; };
-    std::vector<Pending> tile_members, skinny_members;
+    std::vector<Pending> tile_members, skinny_members, stream_members;
     try {
         tile_members.reserve((size_t)count);
         skinny_members.reserve((size_t)count);
+        stream_members.reserve((size_t)count);
     } catch (...) {
         return NGEMM_ERR_DEVICE;                   // out of host memory; nothing was launched
     }
@@ -1121,10 +1177,20 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         if (q.M == 0 || q.B->N == 0) continue;
         RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
         const GemmParams p = make_params(a, ctx->num_xcd);
-        if (q.M <= kSkinnyMaxM)
+        if (q.M <= kSkinnyMaxM && stream_can_serve(p.M, p.Kp))
+            stream_members.push_back(Pending{p, p.npanels});
+        else if (q.M <= kSkinnyMaxM)
             skinny_members.push_back(Pending{p, p.npanels});
         else
             tile_members.push_back(Pending{p, (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64)});
+    }
+    // The streaming kernel pays off once its members have panels for every compute unit several
+    // times over; a few panels are better served by the kernel that splits K over wavefronts.
+    int64_t stream_panels = 0;
+    for (const Pending &m : stream_members) stream_panels += m.units;
+    if (stream_panels < 4 * (int64_t)cus) {
+        skinny_members.insert(skinny_members.end(), stream_members.begin(), stream_members.end());
+        stream_members.clear();
     }
     auto longer_k = [](const Pending &x, const Pending &y) { return x.p.K > y.p.K; };
     std::stable_sort(tile_members.begin(), tile_members.end(), longer_k);
@@ -1139,8 +1205,14 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
             if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
         push(skinny, m.p, m.units);
     }
+    for (const Pending &m : stream_members) {
+        if (stream.count == kGroupMax || stream.unit_start[stream.count] + m.units > kMaxGrid)
+            if (flush(stream, 3) != hipSuccess) return NGEMM_ERR_DEVICE;
+        push(stream, m.p, m.units);
+    }
     if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
     if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
+    if (flush(stream, 3) != hipSuccess) return NGEMM_ERR_DEVICE;
     return NGEMM_OK;
 }
 

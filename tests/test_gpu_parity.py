@@ -319,6 +319,60 @@ def test_skinny_wide_outputs_share_a_fragments(rt, oracle):
         check_problem(rt, oracle, p, (0,))
 
 
+def test_streaming_skinny_single_calls(rt, oracle):
+    """Outputs wide enough (2048 panels and more) for the streaming kernel: a whole panel per
+    wavefront, A in LDS, a ragged last chunk and a ragged last panel, K tails, a K of one slice
+    pair, the row paddings 8 / 16 / 32, zero-points of both operands, int32 and requantised
+    outputs, an unaligned A."""
+    rng = np.random.default_rng(2024)
+    for (M, N, K, aoff) in ((1, 65536 + 5, 200, 0), (7, 65536 + 40, 64, 3), (16, 70001, 130, 0), (17, 65536 + 33, 1000, 1),
+                            (32, 66000, 96, 0), (8, 65537, 1, 0), (9, 65600, 2048, 0)):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        p = wl.Problem(f"stream{M}x{N}x{K}", A, B, za=int(rng.integers(0, 256)), zb=int(rng.integers(-5, 6)),
+                       scale=float(np.float32(0.004)), zc=77)
+        check_problem(rt, oracle, p, (0,), a_byte_offset=aoff, lda_pad=(5 if aoff else 0), ldc_pad=(3 if M == 7 else 0))
+        p0 = wl.Problem(f"stream{M}x{N}x{K}_nozb", A, B, za=int(rng.integers(0, 256)), zb=0)
+        check_problem(rt, oracle, p0, (0,))
+
+
+def test_streaming_skinny_grouped(rt, oracle):
+    """Grouped calls whose skinny members have panels enough for the streaming kernel: members of
+    different M, N, K (tails in all three), with and without a weight zero-point, next to members
+    the streaming kernel cannot serve (A too large for LDS, K = 0) and tiled members; more
+    members than one argument block holds."""
+    ng = ng_mod()
+    rng = np.random.default_rng(2025)
+    shapes = []
+    for t in range(70):
+        M = int(rng.integers(1, 33))
+        N = int(rng.integers(300, 1500))
+        K = int(rng.choice((64, 65, 128, 200, 1000, 1024, 2048, 2100, 4096 + 7)))
+        shapes.append((M, N, K))
+    shapes += [(32, 400, 2048), (32, 400, 2049), (16, 300, 4096), (16, 300, 4097), (8, 100, 8192), (8, 100, 8200),
+               (3, 50, 0), (40, 70, 300), (1, 1, 1)]
+    items, outs, probs, keep, handles = [], [], [], [], []
+    for t, (M, N, K) in enumerate(shapes):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        za, zb = int(rng.integers(0, 256)), (0 if t % 2 == 0 else int(rng.integers(-128, 128)))
+        h, packed = rt.pack(B)
+        Ad = torch.from_numpy(A).cuda() if A.size else torch.empty(16, dtype=torch.uint8, device="cuda")
+        Cd = torch.full((M + 1, N + 2), -9, dtype=torch.int32, device="cuda")
+        handles.append(h); keep.append((packed, Ad)); outs.append(Cd)
+        probs.append((A, B, za, zb))
+        items.append((M, Ad, K, za, zb, h, Cd, N + 2))
+    arr = ng.make_problems(items)
+    ng.ngemm_run_batched_u8s8s32(rt.ctx, arr)
+    torch.cuda.synchronize()
+    for (M, N, K), (A, B, za, zb), Cd in zip(shapes, probs, outs):
+        got = Cd.cpu().numpy()
+        assert np.all(got[M:, :] == -9) and np.all(got[:, N:] == -9), (M, N, K)
+        assert np.array_equal(got[:M, :N], oracle.gemm_u8s8s32(A, B, za, zb)), (M, N, K, za, zb)
+    for h in handles:
+        ng.ngemm_packed_b_free(h)
+
+
 def test_extreme_values_and_wrap(rt, oracle):
     """All-255 x all-(-128)/127 operands: no 16-bit stage, exact at the int32 bound, wraps beyond."""
     for (K, b) in ((64, 127), (64, -128), (65793, -128), (65794, -128), (66311, 127), (66312, 127)):
