@@ -48,7 +48,8 @@ typedef enum {
     NGEMM_ERR_BAD_SHAPE = -2,        /* negative dimension, leading dimension too small             */
     NGEMM_ERR_BUFFER_TOO_SMALL = -3, /* packed buffer or workspace smaller than the size functions say */
     NGEMM_ERR_DEVICE = -4,           /* a HIP call failed (no device, launch error)                 */
-    NGEMM_ERR_UNSUPPORTED_ARCH = -5  /* the device is not gfx950                                    */
+    NGEMM_ERR_UNSUPPORTED_ARCH = -5, /* the device is not gfx950                                    */
+    NGEMM_ERR_STATIC_LIMIT = -6      /* ngemm_run_u8s8s32_static: M beyond its static scratch       */
 } ngemm_status;
 
 /* Kernel selection for ngemm_set_kernel (tests and A/B measurements). */
@@ -189,6 +190,26 @@ ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M,
                                int32_t *C_dev, int64_t ldc,
                                void *workspace_dev, size_t workspace_bytes,
                                void *hip_stream);
+
+/*
+ * ngemm_run_u8s8s32 for callers that cannot allocate device memory, not even a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result,
+ * same arguments without the workspace: the row sums of A that b_zero_point != 0 needs (4 bytes
+ * per row; the only scratch memory of the int32 path) live in a static array inside the
+ * library's device image, NGEMM_STATIC_MAX_M * 4 = 256 KiB, which every GPU the library runs on
+ * holds until the process ends.  M > NGEMM_STATIC_MAX_M gives NGEMM_ERR_STATIC_LIMIT (whatever
+ * b_zero_point is) and nothing is launched.  The call allocates and frees nothing, on the host
+ * or the device.  All calls on one GPU share that GPU's array: two calls with b_zero_point != 0
+ * that may overlap in time (different streams, or different contexts of one device) race on it;
+ * calls on one stream are ordered and safe.  Nothing in the array needs clearing between calls
+ * (every call overwrites the entries it reads).
+ */
+#define NGEMM_STATIC_MAX_M 65536
+ngemm_status ngemm_run_u8s8s32_static(ngemm_ctx *ctx, int64_t M,
+                                      const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                      const ngemm_packed_b *B, int32_t b_zero_point,
+                                      int32_t *C_dev, int64_t ldc,
+                                      void *hip_stream);
 
 /*
  * Unsigned-weight variant, u8 x u8 -> s32 (Sec. 3.1: other integer types).  ngemm_pack_b_u8 is

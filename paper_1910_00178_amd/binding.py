@@ -18,6 +18,8 @@ NGEMM_ERR_BAD_SHAPE = -2
 NGEMM_ERR_BUFFER_TOO_SMALL = -3
 NGEMM_ERR_DEVICE = -4
 NGEMM_ERR_UNSUPPORTED_ARCH = -5
+NGEMM_ERR_STATIC_LIMIT = -6
+NGEMM_STATIC_MAX_M = 65536
 
 NGEMM_KERNEL_AUTO = -1
 NGEMM_KERNEL_SKINNY = 0
@@ -29,7 +31,7 @@ NGEMM_KERNEL_SPLIT_K = 4
 EXPORTS = (
     "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_tune_u8s8s32", "ngemm_tuned_kernel", "ngemm_set_max_workgroups",
     "ngemm_packed_b_bytes", "ngemm_pack_b", "ngemm_pack_b_u8", "ngemm_packed_b_free", "ngemm_packed_b_shape",
-    "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_s8s8s32", "ngemm_run_u8u8s32", "ngemm_packed_b_bytes_s16", "ngemm_pack_b_s16", "ngemm_run_s16s16s32", "ngemm_run_u8s8u8_requant",
+    "ngemm_workspace_bytes", "ngemm_run_u8s8s32", "ngemm_run_u8s8s32_static", "ngemm_run_s8s8s32", "ngemm_run_u8u8s32", "ngemm_packed_b_bytes_s16", "ngemm_pack_b_s16", "ngemm_run_s16s16s32", "ngemm_run_u8s8u8_requant",
     "ngemm_run_u8s8u8_requant_channel", "ngemm_unpacked_workspace_bytes", "ngemm_run_u8s8s32_unpacked",
     "ngemm_batched_workspace_bytes", "ngemm_run_batched_u8s8s32",
 )
@@ -64,6 +66,8 @@ _lib.ngemm_packed_b_shape.argtypes = [_p, ctypes.POINTER(_i64), ctypes.POINTER(_
 _lib.ngemm_workspace_bytes.restype = _sz
 _lib.ngemm_workspace_bytes.argtypes = [_i64, _i64, _i64]
 _lib.ngemm_run_u8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p]
+_lib.ngemm_run_u8s8s32_static.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p]
+_lib.ngemm_run_u8s8s32_static.restype = _int
 _lib.ngemm_tune_u8s8s32.argtypes = [_p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _p, _sz, _p, ctypes.POINTER(_int)]
 _lib.ngemm_tune_u8s8s32.restype = _int
 _lib.ngemm_tuned_kernel.argtypes = [_p, _i64, _i64, _i64, ctypes.POINTER(_int)]
@@ -185,6 +189,11 @@ def ngemm_run_u8s8s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, 
     _check(_lib.ngemm_run_u8s8s32(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B, int(b_zero_point),
                                   _dev(C_dev), int(ldc), _dev(workspace_dev), int(workspace_bytes),
                                   _stream(hip_stream)), "ngemm_run_u8s8s32")
+
+
+def ngemm_run_u8s8s32_static(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, ldc, hip_stream=None):
+    _check(_lib.ngemm_run_u8s8s32_static(ctx, int(M), _dev(A_dev), int(lda), int(a_zero_point), B, int(b_zero_point),
+                                         _dev(C_dev), int(ldc), _stream(hip_stream)), "ngemm_run_u8s8s32_static")
 
 
 def ngemm_tune_u8s8s32(ctx, M, A_dev, lda, a_zero_point, B, b_zero_point, C_dev, ldc,

@@ -13,6 +13,16 @@
 
 using namespace ngemm;
 
+// Scratch memory of ngemm_run_u8s8s32_static, the entry point for callers that cannot allocate:
+// the row sums of A that a zero-point of B needs (4 bytes per row), in the device image of the
+// library instead of a caller's workspace.  Every GPU the library runs on holds its own copy of
+// the array until the process ends.  In host code the name below only stands for the symbol: the
+// device address of a GPU's copy comes from hipGetSymbolAddress (ngemm_create keeps it in the
+// context), and only that address is ever handed to a kernel.
+constexpr int64_t kStaticMaxM = 65536;
+constexpr size_t kStaticScratchBytes = (size_t)kStaticMaxM * 4;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 struct ngemm_ctx {
     uint32_t magic;
     int device;
@@ -20,6 +30,7 @@ struct ngemm_ctx {
     int num_xcd;             // XCDs (L2 domains) of the device; workgroup ids go round them in turn
     int force_kernel;
     int max_workgroups;      // 0 = one per compute unit
+    void *static_scratch;    // device address of this device's copy of `scratch`
     // kernels found fastest by ngemm_tune_u8s8s32, by shape; consulted before the shape heuristic
     struct Tuned {
         int64_t M, N, K;
@@ -587,6 +598,7 @@ const char *ngemm_status_string(ngemm_status s)
     case NGEMM_ERR_BUFFER_TOO_SMALL: return "buffer too small";
     case NGEMM_ERR_DEVICE: return "HIP device error";
     case NGEMM_ERR_UNSUPPORTED_ARCH: return "unsupported architecture (gfx950 required)";
+    case NGEMM_ERR_STATIC_LIMIT: return "problem exceeds the static scratch of the no-allocation entry point (M > 65536)";
     }
     return "unknown status";
 }
@@ -619,7 +631,15 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
     c->max_workgroups = 0;
     {
         DeviceGuard g(device_ordinal);
-        if (!g.ok || allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
+        // this device's copy of the static scratch array (every device has its own, at its own address)
+        void *sp = nullptr;
+        if (!g.ok || hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp) {
+            (void)hipGetLastError();
+            delete c;
+            return NGEMM_ERR_DEVICE;
+        }
+        c->static_scratch = sp;
+        if (allow_big_lds<256, 256, 2, 2, BK256>() != hipSuccess ||
             allow_big_lds_dma<256, 256, 2, 2, kStages256>() != hipSuccess || allow_big_lds_dma<128, 128, 2, 2>() != hipSuccess ||
             allow_big_lds_dma<64, 64, 2, 2>() != hipSuccess || allow_big_lds_deep<1>() != hipSuccess || allow_big_lds_deep<2>() != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -855,6 +875,20 @@ ngemm_status ngemm_run_u8s8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, 
 {
     RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, false, 1.0f, 0};
     return run_common(ctx, a, workspace_dev, workspace_bytes, hip_stream);
+}
+
+ngemm_status ngemm_run_u8s8s32_static(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev, int64_t lda, int32_t a_zero_point,
+                                      const ngemm_packed_b *B, int32_t b_zero_point, int32_t *C_dev, int64_t ldc,
+                                      void *hip_stream)
+{
+    if (!ctx_ok(ctx)) return NGEMM_ERR_INVALID_ARG;
+    if (M > kStaticMaxM) return NGEMM_ERR_STATIC_LIMIT;
+    // ngemm_run_u8s8s32 with the row sums in this device's static array (its address, taken at
+    // ngemm_create; never the symbol).  The kernel that forms them writes all M entries before
+    // the GEMM kernel behind it on the stream reads them, so nothing needs clearing; room for a K
+    // split's partial results is not offered (int32 outputs add their parts into C).
+    RunArgs a{M, A_dev, lda, a_zero_point, b_zero_point, B, C_dev, ldc, false, 1.0f, 0};
+    return run_common(ctx, a, ctx->static_scratch, kStaticScratchBytes, hip_stream);
 }
 
 ngemm_status ngemm_run_s8s8s32(ngemm_ctx *ctx, int64_t M, const int8_t *A_dev, int64_t lda, int32_t a_zero_point,

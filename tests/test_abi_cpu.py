@@ -46,8 +46,8 @@ def test_workspace_and_status_strings():
     assert ng.ngemm_workspace_bytes(512, 512, 65536) == 2048 + 4 * 512 * 512 * 4
     assert ng.ngemm_workspace_bytes(512, 512, 1024) == 2048
     assert ng.ngemm_workspace_bytes(4096, 4096, 65536) == 16384
-    seen = {ng.ngemm_status_string(s) for s in range(-5, 1)}
-    assert len(seen) == 6 and "ok" in seen
+    seen = {ng.ngemm_status_string(s) for s in range(-6, 1)}
+    assert len(seen) == 7 and "ok" in seen
 
 
 def test_handles_reject_garbage_on_host():
