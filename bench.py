@@ -214,8 +214,8 @@ def bench_skinny(b, args):
     (iii) asymptotes."""
     ng, wl, torch, ctx = b.ng, b.wl, b.torch, b.ctx
     sk = {}
-    per = 59                       # members of one grouped call
-    ncopies = 4 * per              # distinct packed copies: 236 x 4 MiB, four times the 256 MiB memory-side cache
+    per = 84                       # members of one grouped call (what one launch of the streaming kernel holds)
+    ncopies = 3 * per              # distinct packed copies: 252 x 4 MiB, four times the 256 MiB memory-side cache
     for M in (1, 4, 16):
         probs = wl.skinny(M)
         B = probs[0].B
@@ -251,7 +251,7 @@ def bench_skinny(b, args):
         entry["rotating_weights_us"] = round(ms2 * 1e3, 3)
         entry["rotating_weights_GBps"] = round(abytes / (ms2 * 1e-3) / 1e9, 1)
         entry["rotating_frac_of_hbm_peak"] = round(abytes / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-        # the same rotating GEMMs through the batched entry point, 59 independent problems per call
+        # the same rotating GEMMs through the batched entry point, 84 independent problems per call
         # (one grouped launch each): what a server with many small GEMMs in flight would issue
         Cb = [torch.empty((M, N), dtype=torch.int32, device="cuda") for _ in range(per)]
         batches = [ng.make_problems([(M, A_dev[(g * per + t) % 16], K, 0, 0, hs[g * per + t], Cb[t], N)

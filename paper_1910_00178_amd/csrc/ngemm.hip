@@ -321,11 +321,13 @@ int stream_launch_lds(int M, int64_t Kp, int chunk)
 }
 
 // Panels per workgroup of the streaming kernel for `panels` panels in all: R per wavefront, one
-// as long as that makes no more than two rounds of resident wavefronts (16 per compute unit);
-// measured on 59 x 128 panels: R = 1 (1888 workgroups) 5.6 TB/s, R = 2 (944, one round) 5.45.
+// as long as that makes no more than eight rounds of resident wavefronts (16 per compute unit):
+// short-lived workgroups handed out by the dispatcher even out what a static share cannot
+// (measured on 59 x 128 panels: R = 1, 1888 workgroups, 5.6 TB/s; R = 2, 944, one round, 5.45;
+// on 84 x 128: R = 1 5.6, R = 2 5.5).
 int stream_chunk(int64_t panels, int num_cus)
 {
-    const int64_t max_waves = (int64_t)num_cus * 32;
+    const int64_t max_waves = (int64_t)num_cus * 128;
     int64_t R = (panels + max_waves - 1) / max_waves;
     R = R < 1 ? 1 : (R > kStreamMaxChunk / kStreamWaves ? kStreamMaxChunk / kStreamWaves : R);
     return (int)(kStreamWaves * R);
@@ -1142,12 +1144,10 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
     // the panels of its skinny members.  Launch count, not arithmetic, is what a batch of small odd
     // shapes costs, so there is no launch for the row sums either: both kernels form them from the
     // A fragments they read anyway.
-    GroupParams tiles, skinny, stream;
-    tiles.count = skinny.count = stream.count = 0;
-    tiles.nxcd = skinny.nxcd = stream.nxcd = ctx->num_xcd;
-    tiles.chunk = skinny.chunk = stream.chunk = 0;
-    tiles.lds_bytes = skinny.lds_bytes = stream.lds_bytes = 0;
-    tiles.unit_start[0] = skinny.unit_start[0] = stream.unit_start[0] = 0;
+    GroupParams tiles, skinny;
+    tiles.count = skinny.count = 0;
+    tiles.nxcd = skinny.nxcd = ctx->num_xcd;
+    tiles.unit_start[0] = skinny.unit_start[0] = 0;
     const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
     using TCfg = TileCfg<64, 64, 2, 2, 64>;
     auto flush = [&](GroupParams &gp, int which) -> hipError_t {
@@ -1157,23 +1157,7 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
             if (which == 1)
                 hipLaunchKernelGGL((gemm_group_tile_kernel<64, 64, 2, 2, 64>), dim3(grid), dim3(256),
                                    (size_t)TCfg::kLdsBytes, st, gp);
-            else if (which == 3) {
-                // streaming kernel: unit_start holds panel counts so far; turn them into chunks of
-                // panels sized for one even round of wavefronts over the whole group
-                const int chunk = stream_chunk(gp.unit_start[gp.count], cus);
-                int lds = 0;
-                int units = 0;
-                for (int t = 0; t < gp.count; ++t) {
-                    const int panels = gp.unit_start[t + 1] - gp.unit_start[t];
-                    gp.unit_start[t] = units;
-                    units += (panels + chunk - 1) / chunk;
-                    lds = std::max(lds, stream_launch_lds(gp.prob[t].M, round_up(gp.prob[t].K, 64), chunk));
-                }
-                gp.unit_start[gp.count] = units;
-                gp.chunk = chunk;
-                gp.lds_bytes = lds;
-                hipLaunchKernelGGL(gemm_group_stream_kernel, dim3((unsigned)units), dim3(kStreamWaves * 64), (size_t)lds, st, gp);
-            } else {
+            else {
                 // wavefronts per panel: eight hide latency when the panels are few; with several
                 // panels per compute unit anyway, fewer wavefronts with more fragments each spend
                 // less on the final sum across wavefronts
@@ -1184,6 +1168,40 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         gp.count = 0;
         gp.unit_start[0] = 0;
         return hipGetLastError();
+    };
+    // The streaming kernel's group: up to kStreamGroupMax members; unit_start collects panel counts
+    // until the launch, which turns them into chunks of panels sized for the whole group.
+    StreamGroupParams stream;
+    stream.count = 0;
+    stream.nxcd = ctx->num_xcd;
+    stream.unit_start[0] = 0;
+    auto flush_stream = [&]() -> hipError_t {
+        if (stream.count == 0) return hipSuccess;
+        const int chunk = stream_chunk(stream.unit_start[stream.count], cus);
+        int lds = 0, units = 0;
+        for (int t = 0; t < stream.count; ++t) {
+            const int panels = stream.unit_start[t + 1] - stream.unit_start[t];
+            stream.unit_start[t] = units;
+            units += (panels + chunk - 1) / chunk;
+            lds = std::max(lds, stream_launch_lds((int)(stream.mzz[t] & 63u), round_up(stream.K[t], 64), chunk));
+        }
+        stream.unit_start[stream.count] = units;
+        stream.chunk = chunk;
+        stream.lds_bytes = lds;
+        if (units > 0)
+            hipLaunchKernelGGL(gemm_group_stream_kernel, dim3((unsigned)units), dim3(kStreamWaves * 64), (size_t)lds, st, stream);
+        stream.count = 0;
+        stream.unit_start[0] = 0;
+        return hipGetLastError();
+    };
+    auto push_stream = [&](const GemmParams &p) {
+        const int t = stream.count;
+        stream.A[t] = p.A; stream.Bp[t] = p.Bp; stream.C[t] = p.C;
+        stream.lda[t] = (int)p.lda; stream.ldc[t] = (int)p.ldc;
+        stream.N[t] = p.N; stream.K[t] = p.K;
+        stream.mzz[t] = stream_pack_mzz(p.M, p.za_term, p.zb);
+        stream.unit_start[t + 1] = stream.unit_start[t] + p.npanels;
+        ++stream.count;
     };
     auto push = [&](GroupParams &gp, const GemmParams &p, int64_t units) {
         GroupMember &m = gp.prob[gp.count];          // the rest is rebuilt on the device
@@ -1211,7 +1229,7 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         if (q.M == 0 || q.B->N == 0) continue;
         RunArgs a{q.M, q.A_dev, q.lda, q.a_zero_point, q.b_zero_point, q.B, q.C_dev, q.ldc, false, 1.0f, 0};
         const GemmParams p = make_params(a, ctx->num_xcd);
-        if (q.M <= kSkinnyMaxM && stream_can_serve(p.M, p.Kp))
+        if (q.M <= kSkinnyMaxM && stream_can_serve(p.M, p.Kp) && q.lda <= 0x7fffffff && q.ldc <= 0x7fffffff)
             stream_members.push_back(Pending{p, p.npanels});
         else if (q.M <= kSkinnyMaxM)
             skinny_members.push_back(Pending{p, p.npanels});
@@ -1240,13 +1258,13 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         push(skinny, m.p, m.units);
     }
     for (const Pending &m : stream_members) {
-        if (stream.count == kGroupMax || stream.unit_start[stream.count] + m.units > kMaxGrid)
-            if (flush(stream, 3) != hipSuccess) return NGEMM_ERR_DEVICE;
-        push(stream, m.p, m.units);
+        if (stream.count == kStreamGroupMax || stream.unit_start[stream.count] + m.units > kMaxGrid)
+            if (flush_stream() != hipSuccess) return NGEMM_ERR_DEVICE;
+        push_stream(m.p);
     }
     if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
     if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
-    if (flush(stream, 3) != hipSuccess) return NGEMM_ERR_DEVICE;
+    if (flush_stream() != hipSuccess) return NGEMM_ERR_DEVICE;
     return NGEMM_OK;
 }
 

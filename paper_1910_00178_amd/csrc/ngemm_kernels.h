@@ -874,8 +874,6 @@ struct GroupMember {
 struct GroupParams {
     int count;
     int nxcd;                // XCDs of the device (see GemmParams)
-    int chunk;               // gemm_group_stream_kernel: panels per unit
-    int lds_bytes;           //   and the dynamic LDS of the launch
     int unit_start[kGroupMax + 1];
     GroupMember prob[kGroupMax];
 };
@@ -2761,13 +2759,46 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_skinny_kernel(c
     stream_body<REQUANT>(p, first, count, chunk, lds_bytes, lds);
 }
 
-// Grouped form: unit = a chunk of `g.chunk` consecutive panels of one member.
-__global__ __launch_bounds__(kStreamWaves * 64) void gemm_group_stream_kernel(const GroupParams g)
+// Grouped form: unit = a chunk of `chunk` consecutive panels of one member.  The launch's fixed
+// costs (ramp, tail, the gap to the next launch: some 5 us) are shared by all its members, so the
+// argument block is laid out to hold as many as 4 KiB can: 48 bytes per member, field by field
+// (no padding), 32-bit pitches, and M, 128 - za and zb in one word.
+constexpr int kStreamGroupMax = 84;
+struct StreamGroupParams {
+    int count;
+    int nxcd;
+    int chunk;               // panels per unit
+    int lds_bytes;           // dynamic LDS of the launch
+    int unit_start[kStreamGroupMax + 2];      // first unit of member q; [count] = grid size (one spare entry keeps the pointers aligned)
+    const uint8_t *A[kStreamGroupMax];
+    const uint8_t *Bp[kStreamGroupMax];
+    void *C[kStreamGroupMax];
+    int lda[kStreamGroupMax], ldc[kStreamGroupMax], N[kStreamGroupMax], K[kStreamGroupMax];
+    uint32_t mzz[kStreamGroupMax];            // M | (128 - za) << 6 (9 bits, signed) | zb << 15 (8 bits, signed)
+};
+static_assert(sizeof(StreamGroupParams) <= 4096, "kernel argument block");
+
+__host__ __device__ inline uint32_t stream_pack_mzz(int M, uint32_t za_term, uint32_t zb)
+{
+    return (uint32_t)M | (za_term & 0x1ffu) << 6 | (zb & 0xffu) << 15;
+}
+
+__global__ __launch_bounds__(kStreamWaves * 64) void gemm_group_stream_kernel(const StreamGroupParams g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int unit = blockIdx.x;
-    const int q = group_find(g, unit);
-    const GemmParams p = group_member_params<64, 64>(g.prob[q], g.nxcd);
+    int q = 0;
+    for (int t = 1; t < g.count; ++t)
+        if (unit >= g.unit_start[t]) q = t;
+    GroupMember m;
+    m.A = g.A[q]; m.Bp = g.Bp[q]; m.C = g.C[q];
+    m.lda = g.lda[q]; m.ldc = g.ldc[q];
+    m.N = g.N[q]; m.K = g.K[q];
+    const uint32_t mzz = g.mzz[q];
+    m.M = (int)(mzz & 63u);
+    m.za_term = (uint32_t)((int32_t)(mzz << 17) >> 23);       // sign-extend the 9 bits at [6, 15)
+    m.zb = (uint32_t)((int32_t)(mzz << 9) >> 24);             // ... the 8 bits at [15, 23)
+    const GemmParams p = group_member_params<64, 64>(m, g.nxcd);
     const int first = (unit - g.unit_start[q]) * g.chunk;
     const int count = p.npanels - first < g.chunk ? p.npanels - first : g.chunk;
     stream_body<false>(p, first, count, g.chunk, g.lds_bytes, lds);
