@@ -311,7 +311,8 @@ def test_skinny_wide_outputs_share_a_fragments(rt, oracle):
     """Outputs wide enough for the skinny kernel to give a workgroup 2 or 4 panels (one A
     fragment used against several panels), with a ragged last workgroup."""
     rng = np.random.default_rng(93)
-    for (M, N, K) in ((9, 32768 + 40, 96), (16, 40000, 64), (17, 32768 + 72, 100), (32, 32768 + 8, 64), (3, 40000, 70)):
+    for (M, N, K) in ((9, 32768 + 40, 96), (16, 40000, 64), (17, 32768 + 72, 100), (32, 32768 + 8, 64), (3, 40000, 70),
+                      (5, 9000, 200), (20, 8192 + 17, 64)):
         A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
         B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
         p = wl.Problem(f"wide{M}x{N}x{K}", A, B, za=int(rng.integers(0, 256)), zb=int(rng.integers(-5, 6)),
