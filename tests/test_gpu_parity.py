@@ -93,13 +93,16 @@ def test_config3_skinny_pack_once_reuse(rt, oracle, M):
     h, packed = rt.pack(B)
     before = packed.clone()
     A_dev = [torch.from_numpy(p.A).cuda() for p in probs]
-    C_dev = [torch.full((M, N), -7, dtype=torch.int32, device="cuda") for _ in probs]
+    # every output sits between two sentinel rows and has a sentinel column gap (ldc = N + 8)
+    C_dev = [torch.full((M + 2, N + 8), -7, dtype=torch.int32, device="cuda") for _ in probs]
     for it in range(1000):
         t = it % len(probs)
-        ng.ngemm_run_u8s8s32(rt.ctx, M, A_dev[t], K, 0, h, 0, C_dev[t], N)
+        ng.ngemm_run_u8s8s32(rt.ctx, M, A_dev[t], K, 0, h, 0, C_dev[t][1:], N + 8)
     torch.cuda.synchronize()
     for t, p in enumerate(probs):
-        assert np.array_equal(C_dev[t].cpu().numpy(), oracle.gemm_u8s8s32(p.A, B)), (M, t)
+        got = C_dev[t].cpu().numpy()
+        assert np.all(got[0] == -7) and np.all(got[M + 1] == -7) and np.all(got[:, N:] == -7), (M, t)
+        assert np.array_equal(got[1:M + 1, :N], oracle.gemm_u8s8s32(p.A, B)), (M, t)
     assert torch.equal(before, packed)
     ng.ngemm_packed_b_free(h)
 
@@ -125,7 +128,7 @@ def test_config4_large_square(rt, oracle):
     ci = rng.integers(0, n, size=20000)
     assert np.array_equal(C[ri, ci], oracle.gemm_u8s8s32_sampled(p.A, p.B, ri, ci))
     # (3) C x == A (B x) exactly in int64 for small random x: catches any single wrong element
-    for s in range(3):
+    for s in range(4):
         x = np.random.default_rng(100 + s).integers(-8, 9, size=n).astype(np.int64)
         Bx = np.zeros(n, dtype=np.int64)
         for j0 in range(0, n, 1024):
@@ -417,8 +420,11 @@ def test_kernels_agree_with_each_other(rt, oracle):
         rt.set_kernel(k)
         res.append(rt.run(A, h, 555, 13, -5))
     rt.set_kernel(ng.NGEMM_KERNEL_AUTO)
-    assert np.array_equal(res[0], res[1]) and np.array_equal(res[1], res[2])
-    assert np.array_equal(res[0], oracle.gemm_u8s8s32(A, B, 13, -5))
+    want = oracle.gemm_u8s8s32(A, B, 13, -5)
+    assert len(res) == len(TILE_KERNELS)
+    for k, got in zip(TILE_KERNELS, res):
+        assert np.array_equal(got, res[0]), k
+        assert np.array_equal(got, want), k
     ng.ngemm_packed_b_free(h)
 
 

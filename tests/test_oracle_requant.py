@@ -56,6 +56,41 @@ def test_clamp_edges(oracle):
     check(oracle, [-2**31, 2**31 - 1, 3, -3], 2.0**30, -5)
 
 
+def test_extreme_output_zero_points(oracle):
+    """zc at both ends of the int32 range and next to them, with a scale of 2^30 (r up to 2^61)
+    and with scales that bring r + zc back into [0, 255]: the sum r + zc is exact (no 32-bit
+    wrap, no float rounding), checked against the exact-rational helper."""
+    cs = [-2**31, -2**31 + 1, -2**31 + 300, -3, -1, 0, 1, 2, 3, 255, 2**31 - 300, 2**31 - 2, 2**31 - 1]
+    for zc in (-2**31, -2**31 + 300, 2**31 - 1, 2**31 - 300, -2**31 + 1):
+        for scale in (2.0**30, 1.0, 2.0**-30, 0.75, 2.0**-7):
+            check(oracle, cs, scale, zc)
+    # sums that land inside [0, 255] only because zc is huge: c * 1.0 + zc
+    check(oracle, [2**31 - 1, 2**31 - 100, 2**31 - 255, 2**31 - 256], 1.0, -2**31 + 300)
+    check(oracle, [-2**31, -2**31 + 100, -2**31 + 254, -2**31 + 300], 1.0, 2**31 - 1)
+
+
+def test_extreme_output_zero_points_channel_form_with_relu(oracle):
+    """The same extremes through the per-column form, with and without the ReLU floor at zc."""
+    rng = np.random.default_rng(44)
+    M, N, K = 5, 6, 40
+    A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+    bias = np.array([2**31 - 1, -2**31, 12345, -2**31 + 300, 2**31 - 300, 0], dtype=np.int64).astype(np.int32)
+    scale = np.array([2.0**30, 1.0, 2.0**-30, 0.75, 2.0**30, 1.0], np.float32)
+    for zc in (-2**31, -2**31 + 300, 2**31 - 1):
+        for relu in (False, True):
+            got = oracle.gemm_u8s8u8_requant_channel(A, B, 100, 3, scale, zc, bias=bias, relu=relu)
+            for i in range(M):
+                for j in range(N):
+                    c = sum((int(A[i, k]) - 100) * (int(B[j, k]) - 3) for k in range(K)) + int(bias[j])
+                    c = (c + 2**31) % 2**32 - 2**31              # the bias add wraps in 32 bits
+                    g = rne_to_binary32(rne_to_binary32(Fraction(c)) * Fraction(float(scale[j])))
+                    q = round(g) + zc
+                    if relu:
+                        q = max(q, zc)
+                    assert int(got[i, j]) == min(255, max(0, q)), (i, j, zc, relu)
+
+
 def test_above_2_pow_24_conversion_rounds(oracle):
     base = 1 << 24
     cs = [base + d for d in range(-4, 40)] + [-(base + d) for d in range(-4, 40)]
