@@ -86,7 +86,8 @@ def graph_time_ms(fn_seq, replays, torch):
 
 TRAFFIC_PROFILE = "large_square_8192_hbm_traffic.txt"
 SKINNY_PROFILE = "skinny_4096x1024_kernel_trace.txt"
-SECTIONS = ("skinny", "fc", "longk", "batched", "types")
+SECTIONS = ("skinny", "fc", "longk", "batched", "types")      # run by default
+OPT_IN_SECTIONS = ("power",)                                    # only when named
 
 
 class Bench:
@@ -461,6 +462,109 @@ def bench_types(b, args, extras):
         "matrix_pipe_only_rates": "profiles/matrix_pipe_power_limit.txt"}
 
 
+def smi_sample():
+    """One reading of rocm-smi (a child process; read-only queries): shader clock in MHz, socket
+    power in W, junction temperature in C; None for what it does not print."""
+    import re
+    import subprocess
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--showtemp"], stdout=subprocess.PIPE,
+                             stderr=subprocess.STDOUT, text=True, timeout=20).stdout
+    except Exception:
+        return None
+    sclk = re.search(r"sclk clock level[^\n]*\((\d+)Mhz\)", out)
+    pw = re.search(r"Power \(W\)\s*:\s*([0-9.]+)", out)
+    tj = re.search(r"junction\) \(C\)\s*:\s*([0-9.]+)", out)
+    return {"sclk_MHz": int(sclk.group(1)) if sclk else None, "power_W": float(pw.group(1)) if pw else None,
+            "junction_C": float(tj.group(1)) if tj else None}
+
+
+def bench_power(b, args):
+    """What the headline figure rests on, measured here: (1) the sustained rate, shader clock and
+    power of the headline launch on uniform and on constant operands (rocm-smi sampled from a
+    thread while the launches run); (2) the launch time as a function of K at M = N = 8192, fitted
+    as tiles-per-workgroup x (fixed + stages x per-stage), which splits the time of the headline
+    launch into its main loop and everything else (fill, epilogue, hand-over between tiles)."""
+    import statistics
+    import threading
+    ng, wl, torch, np, ctx = b.ng, b.wl, b.torch, b.np, b.ctx
+    n = args.size
+    out = {}
+    rng = wl.rng_for(4, 60)
+    nb = ng.ngemm_packed_b_bytes(n, n)
+    pk = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    C = torch.empty((n, n), dtype=torch.int32, device="cuda")
+    for name, A_np, B_np in (("uniform", wl.uniform_u8(rng, n, n), wl.uniform_s8(rng, n, n)),
+                             ("constant", np.full((n, n), 129, np.uint8), np.ones((n, n), np.int8))):
+        A = torch.from_numpy(A_np).cuda()
+        Bd = torch.from_numpy(B_np).cuda()
+        h = ng.ngemm_pack_b(ctx, n, n, Bd, n, pk, nb)
+        torch.cuda.synchronize()
+        seconds = 4.0
+        t_end = time.time() + seconds
+        samples = []
+
+        def sampler():
+            time.sleep(1.0)
+            while time.time() < t_end - 0.3:
+                r = smi_sample()
+                if r:
+                    samples.append(r)
+                time.sleep(0.25)
+        th = threading.Thread(target=sampler)
+        th.start()
+        calls = 0
+        t0 = time.time()
+        while time.time() < t_end:
+            for _ in range(100):
+                ng.ngemm_run_u8s8s32(ctx, n, A, n, 0, h, 0, C, n)
+            torch.cuda.synchronize()
+            calls += 100
+        dt = time.time() - t0
+        th.join()
+        ng.ngemm_packed_b_free(h)
+
+        def med(key):
+            v = [x[key] for x in samples if x.get(key) is not None]
+            return round(statistics.median(v), 1) if v else None
+        out[name] = {"TOPS_sustained": round(2.0 * n ** 3 * calls / dt / 1e12, 1), "seconds": round(dt, 2),
+                     "smi_samples": len(samples), "sclk_MHz_median": med("sclk_MHz"),
+                     "power_W_median": med("power_W"), "junction_C_median": med("junction_C")}
+        del A, Bd
+    # K sweep on uniform operands
+    sweep = {}
+    ks = (1024, 2048, 4096, 8192, 16384)
+    ncus = torch.cuda.get_device_properties(0).multi_processor_count
+    tiles_per_wg = math.ceil((n // 256) ** 2 / ncus)
+    for K in ks:
+        A = torch.from_numpy(wl.uniform_u8(rng, n, K)).cuda()
+        Bd = torch.from_numpy(wl.uniform_s8(rng, n, K)).cuda()
+        nbk = ng.ngemm_packed_b_bytes(K, n)
+        pkk = torch.empty(nbk, dtype=torch.uint8, device="cuda")
+        h = ng.ngemm_pack_b(ctx, K, n, Bd, K, pkk, nbk)
+        reps = max(40, int(200 * 8192 / K))
+        ms = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32(ctx, n, A, K, 0, h, 0, C, n), reps, reps, torch)
+        sweep[K] = ms * 1e3
+        ng.ngemm_packed_b_free(h)
+        del A, Bd, pkk
+    xs = [K / 64.0 for K in ks]
+    ys = [sweep[K] / tiles_per_wg for K in ks]
+    mx, my = sum(xs) / len(xs), sum(ys) / len(ys)
+    slope = sum((x - mx) * (y - my) for x, y in zip(xs, ys)) / sum((x - mx) ** 2 for x in xs)
+    icpt = my - slope * mx
+    sclk = out["uniform"].get("sclk_MHz_median")
+    fit = {"us_per_launch_by_K": {str(K): round(v, 2) for K, v in sweep.items()}, "tiles_per_workgroup": tiles_per_wg,
+           "fixed_us_per_tile": round(icpt, 3), "us_per_stage_of_64": round(slope, 5),
+           "main_loop_share_at_8192": round(128 * slope / (icpt + 128 * slope), 4),
+           "residual_us_max": round(max(abs(y - (icpt + slope * x)) for x, y in zip(xs, ys)) * tiles_per_wg, 2)}
+    if sclk:
+        ideal = 1024.0 / sclk          # 64 matrix ops of 16 cycles per stage and wavefront, at the sampled clock (us)
+        fit["ideal_us_per_stage_at_sampled_clock"] = round(ideal, 5)
+        fit["matrix_pipe_share_of_main_loop"] = round(ideal / slope, 4)
+    out["k_sweep_fit"] = fit
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -471,7 +575,8 @@ def main():
     ap.add_argument("--size", type=int, default=8192, help="square size of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
     ap.add_argument("--sections", default="all",
-                    help="comma-separated extras to run, of: %s (default all)" % ", ".join(SECTIONS))
+                    help="comma-separated extras to run, of: %s (default all of these), %s (only when named)"
+                    % (", ".join(SECTIONS), ", ".join(OPT_IN_SECTIONS)))
     ap.add_argument("--skip-headline", action="store_true",
                     help="run the chosen extras only (to profile one kernel class); the line then carries no "
                          "headline value")
@@ -485,7 +590,7 @@ def main():
     want = set(SECTIONS) if args.sections == "all" else set(x for x in args.sections.split(",") if x)
     if args.no_extras:
         want = set()
-    unknown = want - set(SECTIONS)
+    unknown = want - set(SECTIONS) - set(OPT_IN_SECTIONS)
     if unknown:
         print("bench.py: unknown section(s) %s" % ", ".join(sorted(unknown)), file=sys.stderr)
         sys.exit(2)
@@ -521,6 +626,8 @@ def main():
             extras["batched_64_odd_shapes"] = bench_batched(b, args)
         if "types" in want:
             bench_types(b, args, extras)
+        if "power" in want:
+            extras["power_and_time_budget_%d" % args.size] = bench_power(b, args)
         result["extras"] = extras
 
     ng.ngemm_destroy(ctx)

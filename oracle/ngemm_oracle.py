@@ -21,10 +21,18 @@ _CFLAGS = ["-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
            "-shared", "-fPIC", "-Wall", "-Wextra"]
 
 
+_CHECK_SRC = os.path.join(_HERE, "sanitize_check.c")
+_CHECK_EXE = os.path.join(_HERE, "sanitize_check.bin")
+
+
 def build(force=False):
-    """Compile the C oracle with gcc (seconds)."""
+    """Compile the C oracle with gcc (seconds); with force, also the plain (unsanitized) build of
+    the C driver that tests/test_oracle_sanitized.py runs under the sanitizers."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", *_CFLAGS, "-o", _LIB, _SRC, "-lm"])
+    if force:
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
+                               "-o", _CHECK_EXE, _SRC, _CHECK_SRC, "-lm"])
     return _LIB
 
 
