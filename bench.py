@@ -449,6 +449,23 @@ def bench_types(b, args, extras):
     ms_un = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32_unpacked(ctx, n, n, n, At, n, 0, Bt, n, 0, Ct, n, uws, uwb),
                         100, 100, torch)
     extras["unpacked_b_%d" % n] = {"ms": round(ms_un, 4), "TOPS": round(ops / (ms_un * 1e-3) / 1e12, 1)}
+    # an output that 256 x 256 tiles leave compute units idle on (3072^3: 144 tiles): the heuristic's 192 x 256 tiles
+    n3 = 3072
+    A3 = torch.from_numpy(wl.uniform_u8(rngt, n3, n3)).cuda()
+    B3 = torch.from_numpy(wl.uniform_s8(rngt, n3, n3)).cuda()
+    nb3 = ng.ngemm_packed_b_bytes(n3, n3)
+    pk3 = torch.empty(nb3, dtype=torch.uint8, device="cuda")
+    h3 = ng.ngemm_pack_b(ctx, n3, n3, B3, n3, pk3, nb3)
+    C3 = torch.empty((n3, n3), dtype=torch.int32, device="cuda")
+    ms_a = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32(ctx, n3, A3, n3, 0, h3, 0, C3, n3), 400, 400, torch)
+    ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_TILE_256)
+    ms_256 = gpu_time_ms(lambda: ng.ngemm_run_u8s8s32(ctx, n3, A3, n3, 0, h3, 0, C3, n3), 400, 400, torch)
+    ng.ngemm_set_kernel(ctx, ng.NGEMM_KERNEL_AUTO)
+    ng.ngemm_packed_b_free(h3)
+    o3 = 2.0 * n3 ** 3
+    extras["square_3072"] = {"heuristic_192x256_tiles_TOPS": round(o3 / (ms_a * 1e-3) / 1e12, 1),
+                             "forced_256x256_tiles_TOPS": round(o3 / (ms_256 * 1e-3) / 1e12, 1)}
+    del A3, B3, pk3, C3
     # The same launch on operands that do not change (A = 129, B = 1): on uniform data the chip runs
     # at its power cap (shader clock about 1.8 GHz), on such data at its full clock.  Context only.
     Ac = torch.full((n, n), 129, dtype=torch.uint8, device="cuda")
@@ -459,7 +476,7 @@ def bench_types(b, args, extras):
     extras["power_limit_context_%d" % n] = {
         "constant_operands_TOPS": round(ops / (ms_c * 1e-3) / 1e12, 1),
         "constant_operands_frac_of_peak": round(ops / (ms_c * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
-        "matrix_pipe_only_rates": "profiles/matrix_pipe_power_limit.txt"}
+        "matrix_pipe_only_rates": "profiles/large_square_8192_power_and_time_budget.txt"}
 
 
 def smi_sample():

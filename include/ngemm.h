@@ -60,7 +60,10 @@ enum {
     NGEMM_KERNEL_TILE_128 = 2,   /* 128 x 128 workgroup tile                              */
     NGEMM_KERNEL_TILE_256 = 3,   /* 256 x 256 workgroup tile (throughput configuration)   */
     NGEMM_KERNEL_SPLIT_K = 4,    /* 64 x 64 tiles, K split over workgroups; int32 outputs */
-    NGEMM_KERNEL_COUNT = 5
+    NGEMM_KERNEL_TILE_192 = 5,   /* 192 x 256 workgroup tile: the throughput configuration's form for outputs
+                                    that 256 x 256 tiles leave some compute units idle on; runs the 256 x 256
+                                    tiles where it cannot (rows of A not 16-byte aligned, K < 128)            */
+    NGEMM_KERNEL_COUNT = 6
 };
 
 /* Human-readable name of a status code (static string, never NULL). */

@@ -27,6 +27,7 @@ NGEMM_KERNEL_TILE_64 = 1
 NGEMM_KERNEL_TILE_128 = 2
 NGEMM_KERNEL_TILE_256 = 3
 NGEMM_KERNEL_SPLIT_K = 4
+NGEMM_KERNEL_TILE_192 = 5
 
 EXPORTS = (
     "ngemm_status_string", "ngemm_create", "ngemm_destroy", "ngemm_set_kernel", "ngemm_tune_u8s8s32", "ngemm_tuned_kernel", "ngemm_set_max_workgroups",

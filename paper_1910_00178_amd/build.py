@@ -15,6 +15,7 @@ FLAGS = [
     "-ffp-contract=off", "-fPIC", "-shared", "-std=c++17",
     "-I" + os.path.join(ROOT, "include"),
     "-Wall", "-Wextra", "-Wno-pass-failed",
+    "-Wl,--no-undefined",        # a kernel the host pass failed to emit must fail the build, not the first load
 ]
 
 

@@ -383,7 +383,13 @@ int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N, int64_t K)
         return NGEMM_KERNEL_SKINNY;
     }
     if (t64 * 2 <= cus && K >= kSplitMinK * ((t64 + step - 1) / step)) return NGEMM_KERNEL_SPLIT_K;
-    if (tiles(256) * 2 >= cus) return NGEMM_KERNEL_TILE_256;
+    if (tiles(256) * 2 >= cus) {
+        // rounds of resident workgroups times the rows of a tile: 192 x 256 tiles when they fill more of the
+        // compute units for less time (3072^3: 144 tiles of 256 rows against 192 of 192, one round each)
+        const int64_t t192 = ((M + 191) / 192) * ((N + 255) / 256);
+        const int64_t r256 = (tiles(256) + cus - 1) / cus * 256, r192 = (t192 + cus - 1) / cus * 192;
+        return r192 < r256 ? NGEMM_KERNEL_TILE_192 : NGEMM_KERNEL_TILE_256;
+    }
     if (tiles(128) >= cus) return NGEMM_KERNEL_TILE_128;
     return NGEMM_KERNEL_TILE_64;
 }
@@ -542,22 +548,27 @@ ngemm_status launch_run(const RunArgs &a, int kernel, int num_cus, int device_cu
             e = dma_ok ? launch_tile_dma<128, 128, 2, 2>(p, a.requant, num_cus, st, nullptr, rows_needed)
                        : launch_tile<128, 128, 2, 2, 64>(p, a.requant, st, rows_needed);
         break;
+    case NGEMM_KERNEL_TILE_192:
     case NGEMM_KERNEL_TILE_256:
         if (dma_ok && B->K >= X64Cfg::kMinK && x64_offsets_fit(256, a.lda, B->K) && x64_offsets_fit(9, 32 * round_up(B->K, 64), 0)) {
-            // the 16 x 16 x 64 form of the matrix instruction
-            p.tiles_m = (p.M + 255) / 256;
+            // the 16 x 16 x 64 form of the matrix instruction; 192 x 256 tiles on request
+            const int trows = kernel == NGEMM_KERNEL_TILE_192 ? 192 : 256;
+            p.tiles_m = (p.M + trows - 1) / trows;
             p.tiles_n = (p.N + 255) / 256;
             const int ntiles = p.tiles_m * p.tiles_n;
             const dim3 grid((unsigned)(ntiles < num_cus ? ntiles : num_cus));
-            if (a.requant)
-                hipLaunchKernelGGL((gemm_tile_x64_kernel<false, true>), grid, dim3(256), X64Cfg::kLdsBytes, st, p,
-                                   RawB{nullptr, 0});
+            const RawB none{nullptr, 0};
+            if (trows == 192) {
+                if (a.requant)
+                    hipLaunchKernelGGL((gemm_tile_x64_kernel<false, true, true, 6>), grid, dim3(256), X64Cfg::kLdsBytes, st, p, none);
+                else
+                    hipLaunchKernelGGL((gemm_tile_x64_kernel<false, false, true, 6>), grid, dim3(256), X64Cfg::kLdsBytes, st, p, none);
+            } else if (a.requant)
+                hipLaunchKernelGGL((gemm_tile_x64_kernel<false, true>), grid, dim3(256), X64Cfg::kLdsBytes, st, p, none);
             else if (a.a_signed)      // signed A: the form without the u8 -> s8 shift
-                hipLaunchKernelGGL((gemm_tile_x64_kernel<false, false, false>), grid, dim3(256), X64Cfg::kLdsBytes, st, p,
-                                   RawB{nullptr, 0});
+                hipLaunchKernelGGL((gemm_tile_x64_kernel<false, false, false>), grid, dim3(256), X64Cfg::kLdsBytes, st, p, none);
             else
-                hipLaunchKernelGGL((gemm_tile_x64_kernel<false, false>), grid, dim3(256), X64Cfg::kLdsBytes, st, p,
-                                   RawB{nullptr, 0});
+                hipLaunchKernelGGL((gemm_tile_x64_kernel<false, false>), grid, dim3(256), X64Cfg::kLdsBytes, st, p, none);
             e = hipGetLastError();
         } else {
             e = dma_ok ? launch_tile_dma<256, 256, 2, 2, kStages256>(p, a.requant, num_cus, st)
@@ -652,6 +663,10 @@ ngemm_status ngemm_create(ngemm_ctx **out, int device_ordinal)
                                 X64Cfg::kLdsBytes) != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<false, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 X64Cfg::kLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<false, false, true, 6>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                X64Cfg::kLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute((const void *)gemm_tile_x64_kernel<false, true, true, 6>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                X64Cfg::kLdsBytes) != hipSuccess ||
             hipFuncSetAttribute((const void *)gemm_s16_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 S16Cfg::kLdsBytes) != hipSuccess) {
             delete c;
@@ -702,16 +717,16 @@ ngemm_status ngemm_tune_u8s8s32(ngemm_ctx *ctx, int64_t M, const uint8_t *A_dev,
         (void)hipEventDestroy(e0);
         return NGEMM_ERR_DEVICE;
     }
-    const int candidates[5] = {NGEMM_KERNEL_SKINNY, NGEMM_KERNEL_TILE_64, NGEMM_KERNEL_TILE_128, NGEMM_KERNEL_TILE_256,
-                               NGEMM_KERNEL_SPLIT_K};
+    const int candidates[6] = {NGEMM_KERNEL_SKINNY, NGEMM_KERNEL_TILE_64, NGEMM_KERNEL_TILE_128, NGEMM_KERNEL_TILE_256,
+                               NGEMM_KERNEL_SPLIT_K, NGEMM_KERNEL_TILE_192};
     int best = NGEMM_KERNEL_AUTO;
     float best_ms = 0.0f;
     s = NGEMM_OK;
-    for (int c = 0; c < 5 && s == NGEMM_OK; ++c) {
+    for (int c = 0; c < 6 && s == NGEMM_OK; ++c) {
         const int k = candidates[c];
         if (k == NGEMM_KERNEL_SKINNY && M > kSkinnyMaxM) continue;
         // a tile far larger than the output cannot win: skip what would leave most of it empty
-        if (k == NGEMM_KERNEL_TILE_256 && (M <= 64 || B->N <= 64)) continue;
+        if ((k == NGEMM_KERNEL_TILE_256 || k == NGEMM_KERNEL_TILE_192) && (M <= 64 || B->N <= 64)) continue;
         if (k == NGEMM_KERNEL_SPLIT_K) {
             // only where it would really split (else it is the 64 x 64 candidate once more)
             int kchunk = 0;

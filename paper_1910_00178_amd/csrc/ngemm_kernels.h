@@ -1308,11 +1308,20 @@ struct X64Cfg {
 // The host launches this kernel for K >= kMinK only.
 // SHIFT = false: A holds signed bytes, the u8 -> s8 shift (32 vector instructions per stage and
 // wavefront, 1.7 % of the time on uniform data) is left out.
-template <bool BRAW, bool REQUANT = false, bool SHIFT = true>
+// RB: 16-row blocks per wavefront.  8 is the 256 x 256 tile; 6 a 192 x 256 tile (wavefront tile 96 x 128, 192
+// accumulator registers, three copies of A per wavefront and half stage instead of four; A's ring places keep
+// their size, 192 rows of each are used): for outputs that fill between half and all of the compute units with
+// 256 x 256 tiles, where the shorter tile fills more of them for three quarters of the time per tile
+// (Sec. 3.1.1: the tiling is chosen per problem size).
+template <bool BRAW, bool REQUANT = false, bool SHIFT = true, int RB = 8>
 __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, const RawB rawb)
 {
     using Cfg = X64Cfg;
-    constexpr int LPS = Cfg::kLoadsPerStage;
+    static_assert(RB == 8 || RB == 6, "wavefront tile of 128 or 96 rows");
+    constexpr int CPH = RB / 2;                          // copies of A per wavefront and half of a double stage
+    constexpr int LPS = CPH + 4;                         // copies per stage and wavefront: half a double stage of A, a stage of B
+    constexpr int WROWS = 16 * RB, TROWS = 2 * WROWS;    // rows of a wavefront's tile, of the workgroup's
+    constexpr int NMMA = 8 * RB;                         // matrix ops per stage and wavefront
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1327,7 +1336,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     const int ft = lane & 15, fc = lane >> 4;            // fragments: row / column of the block, 16-byte chunk
     // A fragment of a 16-row block: lane l takes row l % 16, chunk l / 16 (+ 4 in the odd position).
     // Eight consecutive lanes then cover eight different 16-byte columns of LDS: no bank conflicts.
-    const int a_off0 = (wm * 128 + ft) * 128 + (fc ^ (ft & 7)) * 16;
+    const int a_off0 = (wm * WROWS + ft) * 128 + (fc ^ (ft & 7)) * 16;
     const int a_off1 = a_off0 ^ 64;
     int b_off = Cfg::kBBase + (BRAW ? (wn * 8) * 1024 + (4 * ft + ((fc + (ft >> 1)) & 3)) * 16
                                     : (wn * 8 + (fc >> 1)) * 1024 + ((fc & 1) * 16 + ft) * 16);
@@ -1345,7 +1354,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
         tile_of_block(tile, p.tiles_m, p.tiles_n, p.nxcd, tm, tn);
-        const int m0 = tm * 256, n0 = tn * 256;
+        const int m0 = tm * TROWS, n0 = tn * 256;
 
         // (the loaders' lane arithmetic is redone per tile: kept across the main loop it would be
         // spilled, and a reload waits for every store of the tile before still in flight)
@@ -1360,7 +1369,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         // as base of a raw buffer descriptor (no bounds: every offset used below lies inside), a 32-bit
         // lane offset, and the advance along K as a scalar offset, so that a copy costs no vector
         // arithmetic (the host checks that 256 rows of A, and eight panels or 256 columns of B, span
-        // less than 4 GiB).  A: copy d of half h takes rows 8 * (16 * h + 4 * wave + d) .. +7.
+        // less than 4 GiB).  A: copy d of half h takes rows 8 * (4 * CPH * h + CPH * wave + d) .. +7.
         const uint8_t *b_tile = BRAW ? rawb.B + (int64_t)n0 * rawb.ldb
                                      : p.Bp + (int64_t)(n0 / 32) * nslices * kFragBytes;
         // A wavefront's four copies of one operand go to four consecutive KiB of LDS: the LDS base (M0)
@@ -1372,17 +1381,17 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             (void *)((uintptr_t)(p.A + (int64_t)m0 * p.lda) - Cfg::kCopyBias), (short)0, -1, 0x00020000);
         const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(
             (void *)((uintptr_t)b_tile - Cfg::kCopyBias), (short)0, -1, 0x00020000);
-        uint32_t a_voff[8], b_voff[4];
+        uint32_t a_voff[8], b_voff[4];                   // (2 * CPH of a_voff are used; an array of dependent size here makes the host pass drop the kernel)
         const uint32_t lda32 = (uint32_t)p.lda;                // 256 rows span less than 4 GiB
         // A B fragment (32 columns x 32 bytes of K, 1 KiB) is copied with its 16-byte chunks permuted:
         // LDS slot 16 * (2 * h + khalf) + t takes column 16 * h + t, k-half khalf (packed slot
         // 32 * khalf + 16 * h + t), so that the two k-halves of a 16-column block lie side by side
         const uint32_t b_lane = (uint32_t)((32 * ((lane_t >> 4) & 1) + 16 * (lane_t >> 5) + (lane_t & 15)) * 16);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int grow = m0 + ((i >> 2) * 16 + 4 * wave + (i & 3)) * 8 + r8;
+        for (int i = 0; i < 2 * CPH; ++i) {
+            int grow = m0 + ((i / CPH) * (4 * CPH) + CPH * wave + (i % CPH)) * 8 + r8;
             grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
-            a_voff[i] = (uint32_t)(grow - m0) * lda32 + (uint32_t)a_chunk8 * 16u + (uint32_t)(Cfg::kCopyBias - 1024 * (i & 3));
+            a_voff[i] = (uint32_t)(grow - m0) * lda32 + (uint32_t)a_chunk8 * 16u + (uint32_t)(Cfg::kCopyBias - 1024 * (i % CPH));
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -1401,14 +1410,17 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
         // K offset of double stage D's copies (past the end: the last one again, a copy nobody reads)
         auto a_soff = [&](int D) { return 128 * D < 64 * nfull - 128 ? 128 * D : 64 * nfull - 128; };
         // (slot: byte offset of the ring place, here and below)
-        auto dma_a = [&](auto half, int soff, int d, int slot) {     // copy d (0..3) of one half of a double stage
+        auto dma_a = [&](auto half, int soff, int d, int slot) {     // copy d (0..CPH-1) of one half of a double stage
             constexpr int H = decltype(half)::value;
-            const lptr_t to = (lptr_t)(lds + slot + (16 * H + 4 * wave) * 1024);
+            const lptr_t to = (lptr_t)(lds + slot + (4 * CPH * H + CPH * wave) * 1024);
             switch (d) {                                 // the immediate offset has to be a literal
-            case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[4 * H + 0], soff, 0, 0); break;
-            case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[4 * H + 1], soff, 1024, 0); break;
-            case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[4 * H + 2], soff, 2048, 0); break;
-            default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[4 * H + 3], soff, 3072, 0); break;
+            case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[CPH * H + 0], soff, 0, 0); break;
+            case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[CPH * H + 1], soff, 1024, 0); break;
+            case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[CPH * H + 2], soff, 2048, 0); break;
+            default:
+                if constexpr (CPH > 3)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, to, 16, a_voff[CPH * H + 3], soff, 3072, 0);
+                break;
             }
         };
         auto b_soff = [&](int s) {                       // K offset of stage s's copies
@@ -1427,29 +1439,38 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 
         // B fragments of a stage serve all 64 of its matrix ops: two register sets, the one of stage
         // it+1 filled while stage it runs.  An A fragment serves eight: a rolling window of four.
+        // The window's places: fragment i of a stage of parity S sits in place (i + S * RB) % 4, so that the
+        // fragments RB, RB + 1, ... a stage reads ahead are the next stage's 0, 1, ... (RB = 8: i % 4 throughout).
         v4i fb[2][8], fa[4];
         auto read_b = [&](auto set, const uint8_t *from, int j) {     // from: lds + place + b_off
             constexpr int S = decltype(set)::value;
             fb[S][j] = *(const v4i *)(from + (BRAW ? j * 1024 : (j >> 1) * 2048 + (j & 1) * 512));
         };
-        auto read_a = [&](const uint8_t *from, int i) {                // from: lds + place + a_off0 or a_off1
-            fa[i & 3] = *(const v4i *)(from + i * 2048);
+        auto read_a = [&](auto set, const uint8_t *from, int i, int frag) {   // from: lds + place + a_off0 or a_off1; block i into the place of fragment `frag`
+            constexpr int S = decltype(set)::value;
+            fa[(frag + S * RB) & 3] = *(const v4i *)(from + i * 2048);
         };
 
-        v4i acc[8][8];                                   // started by the first stage (K >= kMinK: there is one)
-        // matrix op m (0..63) of a stage: row block m / 8, column block m % 8
+        v4i acc[RB][8];                                  // started by the first stage (K >= kMinK: there is one)
+        // matrix op m of a stage: row block m / 8, column block m % 8
         auto mma = [&](auto set, int m) {
             constexpr int S = decltype(set)::value;
             const int i = m >> 3, j = m & 7;
-            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[S][j], fa[i & 3], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[S][j], fa[(i + S * RB) & 3], acc[i][j], 0, 0, 0);
         };
         auto mma_first = [&](auto set, int m) {          // the first stage starts the sums
             constexpr int S = decltype(set)::value;
             const int i = m >> 3, j = m & 7;
-            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[S][j], fa[i & 3], v4i{0, 0, 0, 0}, 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb[S][j], fa[(i + S * RB) & 3], v4i{0, 0, 0, 0}, 0, 0, 0);
         };
-        auto shift_a = [&](int i) { if (SHIFT) fa[i & 3] = shift_u8_to_s8(fa[i & 3], p.a_xor); };   // u8 -> s8
-        auto shift_a_word = [&](int i, int wd) { if (SHIFT) fa[i & 3][wd] ^= (int)p.a_xor; };      // one dword of it
+        auto shift_a = [&](auto set, int frag) {         // u8 -> s8
+            constexpr int S = decltype(set)::value;
+            if (SHIFT) fa[(frag + S * RB) & 3] = shift_u8_to_s8(fa[(frag + S * RB) & 3], p.a_xor);
+        };
+        auto shift_a_word = [&](auto set, int frag, int wd) {          // one dword of it
+            constexpr int S = decltype(set)::value;
+            if (SHIFT) fa[(frag + S * RB) & 3][wd] ^= (int)p.a_xor;
+        };
 
         if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
 
@@ -1458,28 +1479,28 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             {
                 const int s0 = a_soff(0), s1 = a_soff(1);
 #pragma unroll
-                for (int d = 0; d < 4; ++d) dma_a(IntC<0>{}, s0, d, 0);
+                for (int d = 0; d < CPH; ++d) dma_a(IntC<0>{}, s0, d, 0);
 #pragma unroll
-                for (int d = 0; d < 4; ++d) dma_a(IntC<1>{}, s0, d, 0);
+                for (int d = 0; d < CPH; ++d) dma_a(IntC<1>{}, s0, d, 0);
 #pragma unroll
                 for (int d = 0; d < 4; ++d) dma_b(b_soff(0), d, 0);
 #pragma unroll
                 for (int d = 0; d < 4; ++d) dma_b(b_soff(1), d, Cfg::kBBytes);
 #pragma unroll
-                for (int d = 0; d < 4; ++d) dma_a(IntC<0>{}, s1, d, Cfg::kADouble);
+                for (int d = 0; d < CPH; ++d) dma_a(IntC<0>{}, s1, d, Cfg::kADouble);
 #pragma unroll
-                for (int d = 0; d < 4; ++d) dma_a(IntC<1>{}, s1, d, Cfg::kADouble);
+                for (int d = 0; d < CPH; ++d) dma_a(IntC<1>{}, s1, d, Cfg::kADouble);
 #pragma unroll
                 for (int d = 0; d < 4; ++d) dma_b(b_soff(2), d, 2 * Cfg::kBBytes);
             }
-            wait_vmcnt<16>();                            // A's stages 0, 1 and B's stage 0 have landed (this wavefront's part)
+            wait_vmcnt<8 + 2 * CPH>();                   // A's stages 0, 1 and B's stage 0 have landed (this wavefront's part)
             __builtin_amdgcn_s_barrier();
 #pragma unroll
             for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, lds + b_off, j);
-            read_a(lds + a_off0, 0);
-            read_a(lds + a_off0, 1);
-            read_a(lds + a_off0, 2);
-            shift_a(0);
+            read_a(IntC<0>{}, lds + a_off0, 0, 0);
+            read_a(IntC<0>{}, lds + a_off0, 1, 1);
+            read_a(IntC<0>{}, lds + a_off0, 2, 2);
+            shift_a(IntC<0>{}, 0);
             __builtin_amdgcn_sched_barrier(0);
 
             // One stage: 64 matrix ops, row block by row block (eight ops each, gaps j = 0..7).  One
@@ -1509,7 +1530,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                 int as_n = 0, as_f = 0, bs_n = 0, soff_a = 0, soff_b = 0;
                 const uint8_t *pa_c = nullptr, *pa_n = nullptr, *pb_n = nullptr;
 #pragma unroll
-                for (int m = 0; m < 64; ++m) {
+                for (int m = 0; m < NMMA; ++m) {
                     const int i = m >> 3, j = m & 7;
                     if (m == 0) as_n = !S ? ra : (ra == 2 * kA ? 0 : ra + kA);    // double stage of stage it+1
                     if (m == 1) pa_c = lds + ra + (S ? a_off1 : a_off0);
@@ -1524,19 +1545,28 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                         __builtin_amdgcn_s_barrier();
                         __builtin_amdgcn_sched_barrier(0);
                     }
-                    if (j >= 4) shift_a_word(i + 1, j - 4);
+                    if (j >= 4) shift_a_word(set, i + 1, j - 4);
                     if (j == 5) {
-                        if (i < 5) read_a(pa_c, i + 3);
-                        else read_a(pa_n, i - 5);
+                        if (i < RB - 3) read_a(set, pa_c, i + 3, i + 3);
+                        else read_a(set, pa_n, i - (RB - 3), i + 3);
                     }
                     if (j >= 6 && i >= 2 && i < 6) read_b(other, pb_n, 2 * (i - 2) + (j - 6));
-                    if (i >= 2 && (j == 1 || (j == 3 && (i == 3 || i == 5)))) {
-                        // copies 0..7 in the gaps m = 17, 25, 27, 33, 41, 43, 49, 57
-                        const int d = i == 2 ? 0 : i == 3 ? (j == 1 ? 1 : 2) : i == 4 ? 3 : i == 5 ? (j == 1 ? 4 : 5) : i;
-                        if (d < 4) dma_a(set, soff_a, d, as_f);
-                        else dma_b(soff_b, d - 4, rb);
+                    if (RB == 8) {
+                        if (i >= 2 && (j == 1 || (j == 3 && (i == 3 || i == 5)))) {
+                            // copies 0..7 in the gaps m = 17, 25, 27, 33, 41, 43, 49, 57
+                            const int d = i == 2 ? 0 : i == 3 ? (j == 1 ? 1 : 2) : i == 4 ? 3 : i == 5 ? (j == 1 ? 4 : 5) : i;
+                            if (d < 4) dma_a(set, soff_a, d, as_f);
+                            else dma_b(soff_b, d - 4, rb);
+                        }
+                    } else {
+                        if (i >= 2 && (j == 1 || (j == 3 && i < 5))) {
+                            // copies 0..6 in the gaps m = 17, 19, 25, 27, 33, 35, 41
+                            const int d = 2 * (i - 2) + (j == 3);
+                            if (d < CPH) dma_a(set, soff_a, d, as_f);
+                            else dma_b(soff_b, d - CPH, rb);
+                        }
                     }
-                    if (m == 58) {                       // step the rings
+                    if (m == NMMA - 6) {                 // step the rings
                         rb = bs_n;
                         ra = as_n;
                     }
@@ -1569,14 +1599,17 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             const int kbase = ts * 64;
             __syncthreads();
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int q = 4 * wave + i;                // the blocks as the copies divide them (B: b_voff[i])
-                const int R = 16 * q + (lane_e >> 2), c = lane_e & 3;
+            for (int i = 0; i < CPH; ++i) {
+                const int R = 16 * (CPH * wave + i) + (lane_e >> 2), c = lane_e & 3;   // 16-row blocks of A
                 const int grow = m0 + R < p.M ? m0 + R : p.M - 1;
                 const int valid = p.K - (kbase + c * 16);
                 const uint8_t *src = p.A + (int64_t)grow * p.lda + kbase + c * 16;
                 v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
                 *(v4i *)(lds + R * 128 + (c ^ (R & 7)) * 16) = v;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int q = 4 * wave + i;                // B's blocks as the copies divide them (b_voff[i])
                 v4i z = {0, 0, 0, 0};
                 if (BRAW) {
                     const int bvalid = p.K - (kbase + (((lane_e & 3) - (lane_e >> 3)) & 3) * 16);
@@ -1591,10 +1624,10 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
 #pragma unroll
             for (int j = 0; j < 8; ++j) read_b(IntC<0>{}, lds + b_off, j);
 #pragma unroll
-            for (int m = 0; m < 64; ++m) {
+            for (int m = 0; m < NMMA; ++m) {
                 if ((m & 7) == 0) {
-                    read_a(lds + a_off0, m >> 3);
-                    shift_a(m >> 3);
+                    read_a(IntC<0>{}, lds + a_off0, m >> 3, m >> 3);
+                    shift_a(IntC<0>{}, m >> 3);
                 }
                 mma(IntC<0>{}, m);
             }
@@ -1623,7 +1656,7 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             constexpr int kRow8 = 128 + 16;              // byte patch: 16 rows of 128 bytes, padded
             const int cg8 = lane_e & 7, r8 = lane_e >> 3;    // read-back: 8 lanes of 16 bytes per row, 8 rows per pass
             const int bcol8 = n0 + wn * 128 + 16 * cg8;
-            const bool interior = m0 + (wm + 1) * 128 <= p.M && n0 + (wn + 1) * 128 <= p.N &&
+            const bool interior = m0 + (wm + 1) * WROWS <= p.M && n0 + (wn + 1) * 128 <= p.N &&
                                   ((((uintptr_t)p.C | (uintptr_t)p.ldc) & 15) == 0);
             const bool small_zc = p.zc > -8388608 && p.zc < 8388608;   // uniform: picks the binary32 form
             const float zcf = (float)p.zc;
@@ -1635,13 +1668,13 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             // sum_k (A[i][k] - za) of this lane's row in each of the eight blocks, multiplied per column
             // by that column's zero-point of B (all loaded first: a load between the blocks would wait
             // for the stores of the block before it)
-            uint32_t rsums[8];
+            uint32_t rsums[RB];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) rsums[i] = p.rconst;
+            for (int i = 0; i < RB; ++i) rsums[i] = p.rconst;
             if (p.rowsum) {                              // rows past M read row M - 1 and are never stored
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int row = m0 + wm * 128 + 16 * i + ft;
+                for (int i = 0; i < RB; ++i) {
+                    const int row = m0 + wm * WROWS + 16 * i + ft;
                     rsums[i] += (uint32_t)p.rowsum[row < p.M ? row : p.M - 1];
                 }
             }
@@ -1656,8 +1689,8 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                 scs[j] = *(const float4 *)((const float *)cterm + 512 + lcol);
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int brow0 = m0 + wm * 128 + 16 * i;
+            for (int i = 0; i < RB; ++i) {
+                const int brow0 = m0 + wm * WROWS + 16 * i;
                 const uint32_t rsum = rsums[i];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
@@ -1700,23 +1733,23 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             ct.x = p.za_term * (uint32_t)cs.x; ct.y = p.za_term * (uint32_t)cs.y;
             ct.z = p.za_term * (uint32_t)cs.z; ct.w = p.za_term * (uint32_t)cs.w;
         }
-        const bool interior = m0 + (wm + 1) * 128 <= p.M && n0 + (wn + 1) * 128 <= p.N;
+        const bool interior = m0 + (wm + 1) * WROWS <= p.M && n0 + (wn + 1) * 128 <= p.N;
         // the row terms of all eight blocks first, as eight independent loads (rows past M read row
         // M - 1 and are never stored): loaded block by block, each load would wait for its own
         // latency and for the stores of the block before it
-        uint32_t row_terms[8];
+        uint32_t row_terms[RB];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) row_terms[i] = p.kconst;
+        for (int i = 0; i < RB; ++i) row_terms[i] = p.kconst;
         if (p.rowsum) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int row = m0 + wm * 128 + 16 * i + ft;
+            for (int i = 0; i < RB; ++i) {
+                const int row = m0 + wm * WROWS + 16 * i + ft;
                 row_terms[i] -= p.zb * (uint32_t)p.rowsum[row < p.M ? row : p.M - 1];
             }
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int brow0 = m0 + wm * 128 + 16 * i;
+        for (int i = 0; i < RB; ++i) {
+            const int brow0 = m0 + wm * WROWS + 16 * i;
             const uint32_t row_term = row_terms[i];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {

@@ -27,7 +27,7 @@ def ng_mod():
     return ng
 
 
-TILE_KERNELS = (1, 2, 3, 4)      # 4: the K split; it runs the 64 x 64 tiles where it cannot split
+TILE_KERNELS = (1, 2, 3, 4, 5)   # 4: the K split; it runs the 64 x 64 tiles where it cannot split; 5: 192 x 256 tiles
 
 
 def check_problem(rt, oracle, prob, kernels, **kw):
@@ -238,7 +238,7 @@ def test_large_tile_kernel_k_edges(rt, oracle):
         A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
         B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
         p = wl.Problem(f"kedge_{M}x{N}x{K}", A, B, za=za, zb=zb, scale=float(np.float32(0.003)), zc=31)
-        check_problem(rt, oracle, p, (3,), lda_pad=(-K) % 16, ldb_pad=t % 3)
+        check_problem(rt, oracle, p, (3, 5), lda_pad=(-K) % 16, ldb_pad=t % 3)   # 5: the 192 x 256 form of the same kernel
         if M > 32:
             ld = K + (-K) % 16
             Ah = np.zeros((M, ld), dtype=np.uint8); Ah[:, :K] = A
@@ -429,7 +429,7 @@ def test_kernels_agree_with_each_other(rt, oracle):
 
 
 def test_persistent_workgroups_many_tiles_each(rt, oracle):
-    """Few persistent workgroups over many 256 x 256 tiles: every workgroup walks several tiles,
+    """Few persistent workgroups over many 256 x 256 (and 192 x 256) tiles: every workgroup walks several tiles,
     reusing its LDS ring and epilogue patches.  Ragged M, N, K, zero-points, a leading-dimension
     gap in C, and the requantised output."""
     ng = ng_mod()
@@ -442,7 +442,7 @@ def test_persistent_workgroups_many_tiles_each(rt, oracle):
         for nwg in (1, 3, 7, 8):
             ng.ngemm_set_max_workgroups(rt.ctx, nwg)
             # lda_pad 27 keeps rows 16-byte aligned (K + 27 = 2064), so the direct-to-LDS kernel runs
-            check_problem(rt, oracle, p, (3,), lda_pad=27, ldc_pad=5)
+            check_problem(rt, oracle, p, (3, 5), lda_pad=27, ldc_pad=5)      # 256 x 256 and 192 x 256 tiles
     finally:
         ng.ngemm_set_max_workgroups(rt.ctx, 0)
 
