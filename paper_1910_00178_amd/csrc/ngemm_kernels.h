@@ -2127,18 +2127,16 @@ __global__ __launch_bounds__(64 * kReduceWaves) void splitk_reduce_kernel(const 
 //     a - 128 = 256 * ah + al',   ah = a >> 8 (signed),   al' = (a & 255) - 128 = (a & 255) xor 0x80,
 // and likewise for b, so that
 //     sum (a-128)(b-128) = 65536 * sum ah*bh + 256 * (sum ah*bl' + sum al'*bh) + sum al'*bl'   (mod 2^32)
-// is three int32 accumulators fed by four 8-bit matrix ops per 32 x 32 x 32 block; every step is
-// exact in the ring of integers mod 2^32.  The zero-points enter as for the unsigned 8-bit operand:
+// is four 8-bit matrix ops per block of the output, one per product of byte planes, summed with the
+// shifts in the epilogue; every step is exact in the ring of integers mod 2^32.  The zero-points enter as for the unsigned 8-bit operand:
 //     sum (a-za)(b-zb) = sum (a-128)(b-128) + (128-zb) * rowsum'[i] + (128-za) * colsum'[j] + K (128-za)(128-zb)
 // with rowsum'[i] = sum_k (a[i][k] - 128), colsum'[j] = sum_k (b[k][j] - 128): the epilogue above with
 // zb - 128 in the place of zb.
 //
 // Packed B: per 32-column panel and 32 elements of K two fragments, the ah-plane and the al'-plane, in
 // the fragment layout of the 8-bit pack (byte n of lane l = element 16 * (l / 32) + n of column l % 32),
-// panel contiguous over K; zero padded to (K rounded up to 32) x (N rounded up to 32).  A stage of the
-// kernel is 32 elements of K: 64 bytes per row of A in the block layout of the 8-bit kernel, and the
-// two planes of B, which have exactly the shape of the two k-halves there, so the copies are the same.
-// A's bytes are separated after the LDS read by byte permutes.
+// panel contiguous over K; zero padded to (K rounded up to 32) x (N rounded up to 32).  A's bytes are
+// separated after the LDS read by byte permutes.
 
 // Row sums of an int16 matrix minus 128 per element: out[i] = sum_k (X[i][k] - 128), rows >= rows_valid
 // give 0.  One wavefront per row.
@@ -2198,17 +2196,33 @@ __global__ __launch_bounds__(256) void pack_b_s16_kernel(const int16_t *__restri
 }
 
 struct S16Cfg {
-    static constexpr int NSTAGE = 8;
-    static constexpr int kABytes = 128 * 64;               // 128 rows x 32 elements
-    static constexpr int kStageBytes = 2 * kABytes;        // + 4 panels x 2 planes x 1 KiB
-    static constexpr int kLoadsPerStage = 4;               // per lane: 2 blocks of A, 2 fragments of B
-    static constexpr int kEpiBytes = 4 * kXposeBytes<2> + 128 * 12;
-    static constexpr int kLdsBytes = NSTAGE * kStageBytes > kEpiBytes ? NSTAGE * kStageBytes : kEpiBytes;
+    static constexpr int NSTAGE = 4;
+    static constexpr int kABytes = 128 * 128;              // 128 rows x 64 elements
+    static constexpr int kStageBytes = 2 * kABytes;        // + 4 panels x (2 slices x 2 planes) x 1 KiB
+    static constexpr int kLoadsPerStage = 8;               // per lane: 4 copies of A (8 rows each), 4 fragments of B
+    static constexpr int kPatchRow = 64 * 4 + 16;          // epilogue patch: 16 rows of 64 int32, padded
+    static constexpr int kPatchBytes = 16 * kPatchRow;     // per wavefront
+    static constexpr int kLdsBytes = NSTAGE * kStageBytes;
+    static_assert(4 * kPatchBytes <= kLdsBytes, "epilogue patches fit the ring");
+    static_assert(kLdsBytes <= 160 * 1024, "LDS of a compute unit");
 };
 
 // p.A / p.lda: the int16 matrix as bytes (lda in bytes, a multiple of 16, rows 16-byte aligned);
 // p.K: elements; p.Kp: bytes of one packed column (2 * K rounded up to 32 elements); p.zb: zb - 128;
-// p.rowsum / p.colsum: the sums above.  128 x 128 tiles, four wavefronts of 64 x 64.
+// p.rowsum / p.colsum: the sums above.  128 x 128 tiles, four wavefronts of 64 x 64 as 4 x 4 blocks of
+// v_mfma_i32_16x16x64_i8 (on random operands that form does a fifth more work per joule than
+// 32 x 32 x 32, and this kernel runs at the power limit like the 8-bit one).
+// A stage is 64 elements of K: 128 bytes per row of A, copied as whole lines (one copy = 8 rows), and per
+// panel the four fragments of two slices (ah, al', ah, al') as they lie in the pack.  Row R of A's tile
+// lies in place R ^ ((R / 8) % 2) (the rows of every other group of eight swapped in pairs), chunk c of it
+// at place c ^ (R % 8) of the 128 bytes: the sixteen lanes of a fragment read that share a chunk index
+// then hit sixteen different 16-byte columns of the 256 bytes the banks span (measured: without the
+// swap, rows R and R + 8 collide and every read of A takes twice the cycles).
+// Operands of a 16-row / 16-column block: lane l takes row / column l % 16 and elements 16 (l / 16) .. + 15
+// of the stage, i.e. two 16-byte chunks of A (separated into the byte planes by permutes) and from each
+// plane of B the half (l / 16) % 2 of slice l / 32.
+// With the packed operand first, lane l of a result block holds, for row l % 16 of A's block, the four
+// consecutive columns 4 (l / 16) .. + 3 of B's block.
 __global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
 {
     using Cfg = S16Cfg;
@@ -2219,103 +2233,86 @@ __global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int nfrag = p.Kp / 32;                         // fragments per panel (two per 32 elements)
-    const int nst = p.K / 32;                            // full stages
-    const bool has_tail = nst * 32 < p.K;
+    const int nfull = p.K / 64 & ~1;                     // stages of the pipelined loop: an even number
+    const int nstages = (p.K + 63) / 64;                 // the one or two after them (full, partial) go unpipelined
     const int ntiles = p.tiles_m * p.tiles_n;
     const int gsz = gridDim.x, w = blockIdx.x;
 
-    const int t16 = lane >> 2;
-    const int a_chunk = ((lane & 3) - (t16 >> 2)) & 3;
-    int a_off[2];                                        // this lane's two 16-byte chunks (8 elements each)
-    {
-        const int r = lane & 31, t = r & 15;
-#pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2) {
-            const int c = 2 * (lane >> 5) + c2;
-            a_off[c2] = (wm * 4 + (r >> 4)) * 1024 + (4 * t + ((c + (t >> 2)) & 3)) * 16;
-        }
-    }
-    const int b_off = Cfg::kABytes + (wn * 4) * kFragBytes + lane * 16;
+    const int ft = lane & 15, fc = lane >> 4;
+    const int a_off0 = (wm * 64 + (ft ^ (ft >> 3))) * 128 + ((2 * fc) ^ (ft & 7)) * 16;   // chunk 2 fc of the row; chunk 2 fc + 1: ^ 16
+    const int b_off = Cfg::kABytes + (wn * 8 + (fc >> 1) * 2) * kFragBytes + ((fc & 1) * 32 + ft) * 16;
+    // a copy of A (8 rows, group q = wave + 4 d: its parity is the wavefront's): lane -> row of the eight, chunk
+    const int cp_row = (lane >> 3) ^ (wave & 1), cp_chunk = (lane & 7) ^ cp_row;
 
     for (int tile = w; tile < ntiles; tile += gsz) {
         int tm, tn;
         tile_of_block(tile, p.tiles_m, p.tiles_n, p.nxcd, tm, tn);
         const int m0 = tm * 128, n0 = tn * 128;
 
-        const uint8_t *a_src[2], *b_src[2];
+        // copy d of this wavefront: rows 8 q .. + 7 of A's tile, q = wave + 4 d; fragment `wave` (plane and
+        // slice) of panel d of B's tile
+        const uint8_t *a_src[4], *b_src[4];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int grow = m0 + (wave + 4 * i) * 16 + t16;
+        for (int d = 0; d < 4; ++d) {
+            int grow = m0 + (wave + 4 * d) * 8 + cp_row;
             grow = grow < p.M ? grow : p.M - 1;          // rows past M: read a valid row, never stored
-            a_src[i] = p.A + (int64_t)grow * p.lda + a_chunk * 16;
-            const int q = wave + 4 * i;                  // panel q / 2, plane q % 2
-            int pnl = n0 / 32 + (q >> 1);
+            a_src[d] = p.A + (int64_t)grow * p.lda + cp_chunk * 16;
+            int pnl = n0 / 32 + d;
             pnl = pnl < p.npanels ? pnl : p.npanels - 1;
-            b_src[i] = p.Bp + ((int64_t)pnl * nfrag + (q & 1)) * kFragBytes + lane * 16;
+            b_src[d] = p.Bp + ((int64_t)pnl * nfrag + wave) * kFragBytes + lane * 16;
         }
-        auto dma_one = [&](int s, int d, int buf) {      // copy d (0..3) of stage s
-            const int g = s < nst ? s : nst - 1;         // past the end: a copy nobody reads
+        auto dma_one = [&](int s, int d, int buf) {      // copy d (0..7) of stage s
+            const int g = s < nfull ? s : nfull - 1;     // past the end: a copy nobody reads
             uint8_t *dst = lds + buf * Cfg::kStageBytes;
-            if (d < 2)
-                __builtin_amdgcn_global_load_lds((gptr_t)(a_src[d] + (int64_t)g * 64),
+            if (d < 4)
+                __builtin_amdgcn_global_load_lds((gptr_t)(a_src[d] + (int64_t)g * 128),
                                                  (lptr_t)(dst + (wave + 4 * d) * 1024), 16, 0, 0);
             else
-                __builtin_amdgcn_global_load_lds((gptr_t)(b_src[d - 2] + (int64_t)g * (2 * kFragBytes)),
-                                                 (lptr_t)(dst + Cfg::kABytes + (wave + 4 * (d - 2)) * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)(b_src[d - 4] + (int64_t)g * (4 * kFragBytes)),
+                                                 (lptr_t)(dst + Cfg::kABytes + (4 * (d - 4) + wave) * 1024), 16, 0, 0);
         };
 
-        v4i ar[2][2][2], br[2][2][2];                    // [register set][block][chunk | plane]
-        auto read_one = [&](auto set, int buf, int r) {  // fragment read r (0..7) of a stage
+        // Raw chunks of A's blocks (one set: block i's are consumed by the separation into planes before
+        // the next stage's are read) and the fragments of B (two sets, [set][block][plane]).
+        v4i ar[4][2], br[2][4][2];
+        auto read_one = [&](auto set, int buf, int r) {  // fragment read r (0..15) of a stage: A's blocks, then B's
             constexpr int S = decltype(set)::value;
             const uint8_t *base = lds + buf * Cfg::kStageBytes;
-            const int blk = (r >> 1) & 1, x = r & 1;
-            if (r < 4)
-                ar[S][blk][x] = *(const v4i *)(base + a_off[x] + blk * 2048);
+            const int blk = (r >> 1) & 3, x = r & 1;
+            if (r < 8)
+                ar[blk][x] = *(const v4i *)(base + (a_off0 ^ (x * 16)) + blk * 2048);
             else
-                br[S][blk][x] = *(const v4i *)(base + b_off + (blk * 2 + x) * kFragBytes);
+                br[S][blk][x] = *(const v4i *)(base + b_off + (blk >> 1) * (4 * kFragBytes) + (blk & 1) * 256 + x * kFragBytes);
         };
 
-        v16i hh[2][2], xx[2][2], ll[2][2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    hh[i][j][r] = 0;
-                    xx[i][j][r] = 0;
-                    ll[i][j][r] = 0;
-                }
-        v4i ah[2], al[2];
-        // bytes of 16 consecutive elements (two chunks) -> the high bytes and the shifted low bytes
-        auto split = [&](auto set, int i) {
-            constexpr int S = decltype(set)::value;
-            const v4i c0 = ar[S][i][0], c1 = ar[S][i][1];
-            ah[i].x = (int)__builtin_amdgcn_perm((uint32_t)c0.y, (uint32_t)c0.x, 0x07050301u);
-            ah[i].y = (int)__builtin_amdgcn_perm((uint32_t)c0.w, (uint32_t)c0.z, 0x07050301u);
-            ah[i].z = (int)__builtin_amdgcn_perm((uint32_t)c1.y, (uint32_t)c1.x, 0x07050301u);
-            ah[i].w = (int)__builtin_amdgcn_perm((uint32_t)c1.w, (uint32_t)c1.z, 0x07050301u);
-            al[i].x = (int)(__builtin_amdgcn_perm((uint32_t)c0.y, (uint32_t)c0.x, 0x06040200u) ^ 0x80808080u);
-            al[i].y = (int)(__builtin_amdgcn_perm((uint32_t)c0.w, (uint32_t)c0.z, 0x06040200u) ^ 0x80808080u);
-            al[i].z = (int)(__builtin_amdgcn_perm((uint32_t)c1.y, (uint32_t)c1.x, 0x06040200u) ^ 0x80808080u);
-            al[i].w = (int)(__builtin_amdgcn_perm((uint32_t)c1.w, (uint32_t)c1.z, 0x06040200u) ^ 0x80808080u);
+        // Four accumulators per block, one per product of byte planes (0: ah bh, 1: ah bl', 2: al' bl',
+        // 3: al' bh): 256 registers, each updated once per stage.  (Products 1 and 3 could share one; with
+        // every accumulator register taken the compiler keeps each sum in place, and operands out of them.)
+        v4i acc[4][4][4];
+        v4i ah[4], al[4];
+        // bytes of 4 consecutive elements of block i (word wd of the two chunks) -> their high bytes and
+        // their shifted low bytes
+        auto split_word = [&](int i, int wd) {
+            const v4i c = ar[i][wd >> 1];
+            const uint32_t lo = (uint32_t)((wd & 1) ? c.z : c.x), hi = (uint32_t)((wd & 1) ? c.w : c.y);
+            ah[i][wd] = (int)__builtin_amdgcn_perm(hi, lo, 0x07050301u);
+            al[i][wd] = (int)(__builtin_amdgcn_perm(hi, lo, 0x06040200u) ^ 0x80808080u);
         };
-        // matrix op m (0..15) of a stage; the two ops that share an accumulator are eight apart.
-        // Packed operand first, as in the 8-bit kernels (the epilogue expects that register layout).
-        auto mma = [&](auto set, int m) {
+        // matrix op m (0..63) of a stage: row block m / 16, product (m / 4) % 4, column block m % 4.
+        // Packed operand first.  FIRST: the stage that starts the sums (a literal zero: accumulators
+        // zeroed ahead of the loop make the compiler shuffle them between registers inside it).
+        auto mma = [&](auto set, auto first, int m) {
             constexpr int S = decltype(set)::value;
-            const int i = (m >> 1) & 1, j = m & 1;
-            switch (m >> 2) {
-            case 0: hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(br[S][j][0], ah[i], hh[i][j], 0, 0, 0); break;
-            case 1: xx[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(br[S][j][1], ah[i], xx[i][j], 0, 0, 0); break;
-            case 2: ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(br[S][j][1], al[i], ll[i][j], 0, 0, 0); break;
-            default: xx[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(br[S][j][0], al[i], xx[i][j], 0, 0, 0); break;
-            }
+            constexpr bool FIRST = decltype(first)::value != 0;
+            const int i = m >> 4, q = (m >> 2) & 3, j = m & 3;
+            const v4i b = br[S][j][(q == 1 || q == 2) ? 1 : 0], a = q < 2 ? ah[i] : al[i];
+            if (FIRST) acc[q][i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b, a, v4i{0, 0, 0, 0}, 0, 0, 0);
+            else acc[q][i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b, a, acc[q][i][j], 0, 0, 0);
         };
 
         if (tile != w) __syncthreads();                  // the previous tile's LDS traffic is over
 
-        if (nst > 0) {
+        if (nfull > 0) {
 #pragma unroll
             for (int s = 0; s < NSTAGE - 1; ++s)
 #pragma unroll
@@ -2323,82 +2320,149 @@ __global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
             wait_vmcnt<(NSTAGE - 2) * LPS>();            // stage 0 has landed (this wavefront's part)
             __builtin_amdgcn_s_barrier();
 #pragma unroll
-            for (int r = 0; r < 8; ++r) read_one(IntC<0>{}, 0, r);
+            for (int r = 0; r < 16; ++r) read_one(IntC<0>{}, 0, r);
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd) split_word(0, wd);
             __builtin_amdgcn_sched_barrier(0);
 
-            // One stage: set S holds its raw fragments, the other set receives those of stage it+1
-            // in the gaps of the second half, behind the barrier that makes stage it+1 complete and
-            // the buffer of stage it-1 free; the copies of stage it+NSTAGE-1 follow into that buffer.
-            auto body = [&](auto set, auto other, int it) {
+            // One stage: 64 matrix ops of sixteen cycles each; one wavefront per SIMD issues in order, about
+            // one instruction every four cycles, so a gap between two matrix ops has room for three other
+            // instructions.  Block i + 1's bytes are separated in the gaps 4..7 of block i (three
+            // instructions each).  Behind the barrier in the middle, which makes stage it+1 complete and
+            // the buffer of stage it-1 free: the fragments of stage it+1 (A's into the one set as its
+            // blocks fall free, B's into the other set), one read per gap; then the copies of stage
+            // it+NSTAGE-1 into the free buffer, every other gap; the gaps 56..59 separate block 0 of
+            // stage it+1.
+            auto body = [&](auto set, auto other, auto first, int it) {
                 const int buf_n = (it + 1) % NSTAGE, buf_f = (it + NSTAGE - 1) % NSTAGE;
-                split(set, 0);
-                split(set, 1);
 #pragma unroll
-                for (int m = 0; m < 8; ++m) {
-                    mma(set, m);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                wait_vmcnt<(NSTAGE - 3) * LPS>();
-                __builtin_amdgcn_s_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int m = 8; m < 16; ++m) {
-                    if (m < 12) {
-                        read_one(other, buf_n, 2 * (m - 8));
-                        read_one(other, buf_n, 2 * (m - 8) + 1);
+                for (int m = 0; m < 64; ++m) {
+                    if (m == 32) {
+                        wait_vmcnt<(NSTAGE - 3) * LPS>();
+                        __builtin_amdgcn_s_barrier();
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    if (m & 1) dma_one(it + NSTAGE - 1, (m - 9) >> 1, buf_f);   // copies every other gap
-
+                    if ((m & 15) >= 4 && (m & 15) < 8 && m < 48) split_word((m >> 4) + 1, m & 3);
+                    if (m >= 56 && m < 60) split_word(0, m & 3);
+                    // reads 0..5 (A's blocks 0..2), 8, 9 (B's block 0), 6, 7 (A's block 3, whose old chunks
+                    // the gaps 36..39 consume), 10..15
+                    if (m >= 32 && m < 48) read_one(other, buf_n, m < 38 ? m - 32 : m < 40 ? m - 30 : m < 42 ? m - 34 : m - 32);
+                    if (m >= 48 && (m & 1)) dma_one(it + NSTAGE - 1, (m - 49) >> 1, buf_f);
                     __builtin_amdgcn_sched_barrier(0);
-                    mma(set, m);
+                    mma(set, first, m);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
-            int it = 0;
-            for (; it + 1 < nst; it += 2) {
-                body(IntC<0>{}, IntC<1>{}, it);
-                body(IntC<1>{}, IntC<0>{}, it + 1);
+            body(IntC<0>{}, IntC<1>{}, IntC<1>{}, 0);
+            body(IntC<1>{}, IntC<0>{}, IntC<0>{}, 1);
+            for (int it = 2; it < nfull; it += 2) {
+                body(IntC<0>{}, IntC<1>{}, IntC<0>{}, it);
+                body(IntC<1>{}, IntC<0>{}, IntC<0>{}, it + 1);
             }
-            if (it < nst) body(IntC<0>{}, IntC<1>{}, it);
             wait_vmcnt<0>();                             // drain the copies nobody reads
         }
 
-        // K tail: fewer than 32 elements.  Guarded register loads of A, the zero-padded planes of B.
-        if (has_tail) {
-            const int kbase = nst * 64;                  // bytes into a row of A
+        // What is left of K: an odd last full stage and / or a partial one.  Guarded register loads of A,
+        // the zero-padded planes of B (a slice the pack does not hold counts as zero), into the first
+        // buffer in the stage's layout; no pipelining.  Without a pipelined part (K < 128) the first of them
+        // starts the sums; K = 0 leaves a stage of zeros to do that.
+        bool started = nfull > 0;
+        for (int ts = nfull; ts < (nstages > 0 ? nstages : 1); ++ts) {
+            const int kbase = ts * 128;                  // bytes into a row of A
             __syncthreads();
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int q = wave + 4 * i;
-                const int valid = 2 * p.K - (kbase + a_chunk * 16);
-                const uint8_t *src = a_src[i] + kbase;
-                v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
-                *(v4i *)(lds + q * 1024 + lane * 16) = v;
-                *(v4i *)(lds + Cfg::kABytes + q * 1024 + lane * 16) =
-                    *(const v4i *)(b_src[i] + (int64_t)nst * (2 * kFragBytes));
+            for (int d = 0; d < 4; ++d) {
+                const int valid = 2 * p.K - (kbase + cp_chunk * 16);
+                const uint8_t *src = a_src[d] + kbase;
+                const v4i v = valid >= 16 ? load16_any(src) : load16_partial(src, valid < 0 ? 0 : valid);
+                *(v4i *)(lds + (wave + 4 * d) * 1024 + lane * 16) = v;
+                v4i z = {0, 0, 0, 0};
+                if (ts * 4 + wave < nfrag) z = *(const v4i *)(b_src[d] + (int64_t)ts * (4 * kFragBytes));
+                *(v4i *)(lds + Cfg::kABytes + (4 * d + wave) * 1024 + lane * 16) = z;
             }
             __syncthreads();
 #pragma unroll
-            for (int r = 0; r < 8; ++r) read_one(IntC<0>{}, 0, r);
-            split(IntC<0>{}, 0);
-            split(IntC<0>{}, 1);
+            for (int r = 0; r < 16; ++r) read_one(IntC<0>{}, 0, r);
 #pragma unroll
-            for (int m = 0; m < 16; ++m) mma(IntC<0>{}, m);
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int wd = 0; wd < 4; ++wd) split_word(i, wd);
+            if (started) {
+#pragma unroll
+                for (int m = 0; m < 64; ++m) mma(IntC<0>{}, IntC<0>{}, m);
+            } else {
+#pragma unroll
+                for (int m = 0; m < 64; ++m) mma(IntC<0>{}, IntC<1>{}, m);
+            }
+            started = true;
         }
 
-        // (a-128)(b-128) sums: 65536 * hh + 256 * xx + ll, wrapping
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    hh[i][j][r] = (int)(((uint32_t)hh[i][j][r] << 16) + ((uint32_t)xx[i][j][r] << 8) +
-                                        (uint32_t)ll[i][j][r]);
-
         __syncthreads();                                 // every wavefront is done with the stage buffers
-        tile_epilogue<2, 2, 128, false>(p, hh, m0, n0, wm, wn, lane, tid, 256, lds + wave * kXposeBytes<2>,
-                                        (uint32_t *)(lds + 4 * kXposeBytes<2>));
+
+        // Epilogue.  Per 16-row block: (a-128)(b-128) sums = 65536 * acc0 + 256 * (acc1 + acc3) + acc2
+        // (wrapping) plus the row term, written to the wavefront's LDS patch as they lie in the accumulators, read back
+        // four rows per instruction, column terms added, stored as 256-byte row pieces.
+        uint8_t *patch = lds + wave * Cfg::kPatchBytes;
+        const int cg = lane & 15, r4 = lane >> 4;
+        const int bcol = n0 + wn * 64 + 4 * cg;
+        uint4 ct = {0u, 0u, 0u, 0u};
+        if (bcol < p.N) {
+            const int4 cs = *(const int4 *)(p.colsum + bcol);        // colsum is padded to 32 columns
+            ct.x = p.za_term * (uint32_t)cs.x; ct.y = p.za_term * (uint32_t)cs.y;
+            ct.z = p.za_term * (uint32_t)cs.z; ct.w = p.za_term * (uint32_t)cs.w;
+        }
+        const bool interior = m0 + (wm + 1) * 64 <= p.M && n0 + (wn + 1) * 64 <= p.N;
+        uint32_t row_terms[4];                           // all four first: independent loads
+#pragma unroll
+        for (int i = 0; i < 4; ++i) row_terms[i] = p.kconst;
+        if (p.rowsum) {                                  // rows past M read row M - 1 and are never stored
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = m0 + wm * 64 + 16 * i + ft;
+                row_terms[i] -= p.zb * (uint32_t)p.rowsum[row < p.M ? row : p.M - 1];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int brow0 = m0 + wm * 64 + 16 * i;
+            const uint32_t rt = row_terms[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v4i v;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    v[t] = (int)(((uint32_t)acc[0][i][j][t] << 16) + (((uint32_t)acc[1][i][j][t] + (uint32_t)acc[3][i][j][t]) << 8) +
+                                 (uint32_t)acc[2][i][j][t] + rt);
+                *(v4i *)(patch + ft * Cfg::kPatchRow + (16 * j + 4 * fc) * 4) = v;
+            }
+            v4i o[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = *(const v4i *)(patch + (4 * q + r4) * Cfg::kPatchRow + cg * 16);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                o[q].x = (int)((uint32_t)o[q].x + ct.x); o[q].y = (int)((uint32_t)o[q].y + ct.y);
+                o[q].z = (int)((uint32_t)o[q].z + ct.z); o[q].w = (int)((uint32_t)o[q].w + ct.w);
+            }
+            int32_t *dst = (int32_t *)p.C + (int64_t)(brow0 + r4) * p.ldc + bcol;   // this lane's first row of the block
+            if (interior) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q, dst += 4 * p.ldc) __builtin_nontemporal_store(o[q], (v4i_a4 *)dst);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q, dst += 4 * p.ldc) {
+                    const v4i v = o[q];
+                    if (brow0 + 4 * q + r4 < p.M && bcol < p.N) {
+                        if (bcol + 3 < p.N) {
+                            __builtin_memcpy(dst, &v, 16);
+                        } else {
+                            dst[0] = v.x;
+                            if (bcol + 1 < p.N) dst[1] = v.y;
+                            if (bcol + 2 < p.N) dst[2] = v.z;
+                        }
+                    }
+                }
+            }
+        }
     }
 }
 

@@ -591,7 +591,9 @@ def test_per_channel_epilogue(rt, oracle):
     kernel, against the oracle's per-column form; ragged shapes and odd leading dimensions."""
     ng = ng_mod()
     rng = np.random.default_rng(94)
-    cases = [(7, 100, 300), (32, 4096, 128), (200, 333, 500), (300, 520, 1008), (64, 64, 64), (33, 1, 17), (260, 300, 1024)]
+    # the 65700-column case is wide enough for the streaming skinny kernel (one panel per wavefront)
+    cases = [(7, 100, 300), (32, 4096, 128), (200, 333, 500), (300, 520, 1008), (64, 64, 64), (33, 1, 17), (260, 300, 1024),
+             (3, 65700, 96)]
     for t, (M, N, K) in enumerate(cases):
         A = np.clip(np.rint(rng.normal(128, 40, size=(M, K))), 0, 255).astype(np.uint8)
         B = np.clip(np.rint(rng.normal(0, 30, size=(N, K))), -127, 127).astype(np.int8)
@@ -751,7 +753,7 @@ def test_16bit_variant(rt, oracle):
     ng = ng_mod()
     rng = np.random.default_rng(101)
     shapes = ((1, 1, 1), (5, 7, 31), (64, 64, 32), (100, 130, 100), (130, 257, 320), (300, 200, 1000), (128, 128, 2048),
-              (257, 129, 65))
+              (257, 129, 65), (70, 90, 128), (129, 64, 209), (40, 300, 448))
     for t, (M, N, K) in enumerate(shapes):
         if t == 3:      # extremes: every product near 2^30, sums wrap
             A = rng.choice(np.array([-32768, 32767], dtype=np.int16), size=(M, K))
