@@ -2402,8 +2402,13 @@ __global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
         // Epilogue.  Per 16-row block: (a-128)(b-128) sums = 65536 * acc0 + 256 * (acc1 + acc3) + acc2
         // (wrapping) plus the row term, written to the wavefront's LDS patch as they lie in the accumulators, read back
         // four rows per instruction, column terms added, stored as 256-byte row pieces.
+        // (what the epilogue derives from the lane index is computed here: prepared ahead of the main loop
+        // it would be carried across it in registers the loop needs, and spilled)
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int ft = lane_e & 15, fc = lane_e >> 4;
         uint8_t *patch = lds + wave * Cfg::kPatchBytes;
-        const int cg = lane & 15, r4 = lane >> 4;
+        const int cg = lane_e & 15, r4 = lane_e >> 4;
         const int bcol = n0 + wn * 64 + 4 * cg;
         uint4 ct = {0u, 0u, 0u, 0u};
         if (bcol < p.N) {
@@ -2424,6 +2429,12 @@ __global__ __launch_bounds__(256) void gemm_s16_tile_kernel(const GemmParams p)
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            // (block by block: the compiler would otherwise move all 256 accumulators into vector registers
+            // ahead of the first block, where they do not fit beside what is live, and spill some of them)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) asm volatile("" : "+a"(acc[q][i][j]));
             const int brow0 = m0 + wm * 64 + 16 * i;
             const uint32_t rt = row_terms[i];
 #pragma unroll
