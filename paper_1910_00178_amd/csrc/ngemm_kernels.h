@@ -1284,7 +1284,6 @@ struct X64Cfg {
     static constexpr int kADouble = 256 * 128;
     static constexpr int kBBytes = 256 * 64;
     static constexpr int kBBase = kARing * kADouble;
-    static constexpr int kLoadsPerStage = 8;               // per lane: 4 blocks of A, 4 fragments of B
     static constexpr int kPatchRow = 128 * 4 + 16;         // epilogue patch: 16 rows of 128 int32, padded
     static constexpr int kPatchBytes = 16 * kPatchRow;     // per wavefront
     static constexpr int kLdsBytes = kBBase + kBRing * kBBytes;
@@ -2204,6 +2203,7 @@ struct S16Cfg {
     static constexpr int kPatchBytes = 16 * kPatchRow;     // per wavefront
     static constexpr int kLdsBytes = NSTAGE * kStageBytes;
     static_assert(4 * kPatchBytes <= kLdsBytes, "epilogue patches fit the ring");
+    static_assert((NSTAGE - 2) * kLoadsPerStage <= 63, "vmcnt range");
     static_assert(kLdsBytes <= 160 * 1024, "LDS of a compute unit");
 };
 
