@@ -753,7 +753,7 @@ def test_16bit_variant(rt, oracle):
     ng = ng_mod()
     rng = np.random.default_rng(101)
     shapes = ((1, 1, 1), (5, 7, 31), (64, 64, 32), (100, 130, 100), (130, 257, 320), (300, 200, 1000), (128, 128, 2048),
-              (257, 129, 65), (70, 90, 128), (129, 64, 209), (40, 300, 448))
+              (257, 129, 65), (70, 90, 128), (129, 64, 209), (40, 300, 448), (512, 640, 4096))
     for t, (M, N, K) in enumerate(shapes):
         if t == 3:      # extremes: every product near 2^30, sums wrap
             A = rng.choice(np.array([-32768, 32767], dtype=np.int16), size=(M, K))
