@@ -355,8 +355,8 @@ size_t ngemm_batched_workspace_bytes(int count, const ngemm_problem *problems);
  * Run `count` independent int32-output GEMMs (arbitrary shapes, per-GEMM
  * zero-points) on one stream.  All members are validated before anything is
  * launched.  Results are those of `count` calls of ngemm_run_u8s8s32.  The members run in
- * grouped launches (one grid for the tiles of all members with M > 32, one for the panels of
- * the others, at most 59 members per grid); workspace_dev may be NULL.
+ * grouped launches (one grid for the panels of the members with M <= 32 and the tiles of the
+ * others, at most 67 members per grid); workspace_dev may be NULL.
  */
 ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_problem *problems,
                                        void *workspace_dev, size_t workspace_bytes,

@@ -1155,33 +1155,36 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
     hipStream_t st = (hipStream_t)hip_stream;
 
     // Grouped launches: the members' parameters ride in the kernel argument block, up to
-    // kGroupMax per launch; one grid covers the 64 x 64 tiles of a group's members with M > 32, one
-    // the panels of its skinny members.  Launch count, not arithmetic, is what a batch of small odd
-    // shapes costs, so there is no launch for the row sums either: both kernels form them from the
-    // A fragments they read anyway.
-    GroupParams tiles, skinny;
-    tiles.count = skinny.count = 0;
-    tiles.nxcd = skinny.nxcd = ctx->num_xcd;
-    tiles.unit_start[0] = skinny.unit_start[0] = 0;
+    // kGroupMax per launch; one grid covers the panels of a group's skinny members and the 64 x 64
+    // tiles of its members with M > 32.  Launch count, not arithmetic, is what a batch of small odd
+    // shapes costs (and two launches run one after the other, however few compute units each can use),
+    // so there is no launch for the row sums either: both bodies form them from the A fragments they
+    // read anyway.
+    GroupParams grp;
+    grp.count = 0;
+    grp.nxcd = ctx->num_xcd;
+    grp.first_tile = 0;
+    grp.unit_start[0] = 0;
     const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
     using TCfg = TileCfg<64, 64, 2, 2, 64>;
-    auto flush = [&](GroupParams &gp, int which) -> hipError_t {
-        if (gp.count == 0) return hipSuccess;
-        const unsigned grid = (unsigned)gp.unit_start[gp.count];
+    auto flush = [&]() -> hipError_t {
+        if (grp.count == 0) return hipSuccess;
+        const unsigned grid = (unsigned)grp.unit_start[grp.count];
         if (grid > 0) {
-            if (which == 1)
-                hipLaunchKernelGGL((gemm_group_tile_kernel<64, 64, 2, 2, 64>), dim3(grid), dim3(256),
-                                   (size_t)TCfg::kLdsBytes, st, gp);
-            else {
-                // wavefronts per panel: eight hide latency when the panels are few; with several
-                // panels per compute unit anyway, fewer wavefronts with more fragments each spend
-                // less on the final sum across wavefronts
+            if (grp.first_tile == grp.count) {
+                // skinny members only.  Wavefronts per panel: eight hide latency when the panels are
+                // few; with several panels per compute unit anyway, fewer wavefronts with more
+                // fragments each spend less on the final sum across wavefronts
                 const unsigned nw = grid >= 8u * cus ? 2 : (grid >= 4u * cus ? 4 : 8);
-                hipLaunchKernelGGL(gemm_group_skinny_kernel, dim3(grid), dim3(64 * nw), (size_t)(nw * 16 * 64 * 4), st, gp);
+                hipLaunchKernelGGL(gemm_group_skinny_kernel, dim3(grid), dim3(64 * nw), (size_t)(nw * 16 * 64 * 4), st, grp);
+            } else {
+                const size_t lds = std::max((size_t)TCfg::kLdsBytes, (size_t)(4 * 16 * 64 * 4));
+                hipLaunchKernelGGL((gemm_group_kernel<64, 64, 2, 2, 64>), dim3(grid), dim3(256), lds, st, grp);
             }
         }
-        gp.count = 0;
-        gp.unit_start[0] = 0;
+        grp.count = 0;
+        grp.first_tile = 0;
+        grp.unit_start[0] = 0;
         return hipGetLastError();
     };
     // The streaming kernel's group: up to kStreamGroupMax members; unit_start collects panel counts
@@ -1218,14 +1221,16 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
         stream.unit_start[t + 1] = stream.unit_start[t] + p.npanels;
         ++stream.count;
     };
-    auto push = [&](GroupParams &gp, const GemmParams &p, int64_t units) {
-        GroupMember &m = gp.prob[gp.count];          // the rest is rebuilt on the device
+    auto push = [&](const GemmParams &p, int64_t units, bool is_skinny) {
+        GroupMember &m = grp.prob[grp.count];        // the rest is rebuilt on the device
         m.A = p.A; m.Bp = p.Bp; m.C = p.C;
         m.lda = p.lda; m.ldc = p.ldc;
         m.M = p.M; m.N = p.N; m.K = p.K;
-        m.za_term = p.za_term; m.zb = p.zb;
-        gp.unit_start[gp.count + 1] = gp.unit_start[gp.count] + (int)units;
-        ++gp.count;
+        m.za_term = (int16_t)(int32_t)p.za_term;     // 128 - za and zb: small signed values
+        m.zb = (int16_t)(int32_t)p.zb;
+        grp.unit_start[grp.count + 1] = grp.unit_start[grp.count] + (int)units;
+        ++grp.count;
+        if (is_skinny) grp.first_tile = grp.count;   // the skinny members of a group come first
     };
     constexpr int64_t kMaxGrid = 1 << 30;
     // Members with the longest K first: a workgroup's time grows with K, and the grid is handed out
@@ -1262,23 +1267,24 @@ ngemm_status ngemm_run_batched_u8s8s32(ngemm_ctx *ctx, int count, const ngemm_pr
     auto longer_k = [](const Pending &x, const Pending &y) { return x.p.K > y.p.K; };
     std::stable_sort(tile_members.begin(), tile_members.end(), longer_k);
     std::stable_sort(skinny_members.begin(), skinny_members.end(), longer_k);
-    for (const Pending &m : tile_members) {
-        if (tiles.count == kGroupMax || tiles.unit_start[tiles.count] + m.units > kMaxGrid)
-            if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
-        push(tiles, m.p, m.units);
-    }
+    // skinny members first: in a grid that also holds tiles they start with the launch (the longest
+    // of them take as long as all the tiles together)
     for (const Pending &m : skinny_members) {
-        if (skinny.count == kGroupMax || skinny.unit_start[skinny.count] + m.units > kMaxGrid)
-            if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
-        push(skinny, m.p, m.units);
+        if (grp.count == kGroupMax || grp.unit_start[grp.count] + m.units > kMaxGrid)
+            if (flush() != hipSuccess) return NGEMM_ERR_DEVICE;
+        push(m.p, m.units, true);
+    }
+    for (const Pending &m : tile_members) {
+        if (grp.count == kGroupMax || grp.unit_start[grp.count] + m.units > kMaxGrid)
+            if (flush() != hipSuccess) return NGEMM_ERR_DEVICE;
+        push(m.p, m.units, false);
     }
     for (const Pending &m : stream_members) {
         if (stream.count == kStreamGroupMax || stream.unit_start[stream.count] + m.units > kMaxGrid)
             if (flush_stream() != hipSuccess) return NGEMM_ERR_DEVICE;
         push_stream(m.p);
     }
-    if (flush(tiles, 1) != hipSuccess) return NGEMM_ERR_DEVICE;
-    if (flush(skinny, 2) != hipSuccess) return NGEMM_ERR_DEVICE;
+    if (flush() != hipSuccess) return NGEMM_ERR_DEVICE;
     if (flush_stream() != hipSuccess) return NGEMM_ERR_DEVICE;
     return NGEMM_OK;
 }

@@ -857,27 +857,31 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_tile_kernel(const GemmPar
 
 // ---- grouped launches: several independent problems in one grid -------------------------------
 // The problems' parameters travel in the kernel argument block, which holds 4 KiB: each member is
-// cut down to what cannot be derived (GroupMember, 64 bytes), so that kGroupMax of them fit, and a
+// cut down to what cannot be derived (GroupMember, 56 bytes), so that kGroupMax of them fit, and a
 // workgroup rebuilds the full parameter set of its own member with a few scalar operations.
-// unit_start[q] is the first workgroup id of problem q, unit_start[count] the grid size.  What a
-// "unit" is depends on the kernel: a 64 x 64 tile or a 32-column panel.
+// unit_start[q] is the first workgroup id of problem q, unit_start[count] the grid size.  A unit is a
+// 32-column panel for the members [0, first_tile) (M <= 32: the skinny body) and a 64 x 64 tile for the
+// rest: one grid holds both kinds, so that a long-K skinny member and the tiles of the large members
+// run side by side instead of one launch after the other.
 // Members are u8 x s8 -> s32 problems with per-tensor zero-points.
-constexpr int kGroupMax = 59;
+constexpr int kGroupMax = 67;
 struct GroupMember {
     const uint8_t *A;
     const uint8_t *Bp;       // packed fragments; the column sums follow them
     void *C;
     int64_t lda, ldc;
     int M, N, K;
-    uint32_t za_term, zb;
+    int16_t za_term, zb;     // 128 - za (-127..128) and zb (-128..127)
 };
 struct GroupParams {
     int count;
     int nxcd;                // XCDs of the device (see GemmParams)
+    int first_tile;          // members before it are skinny (units = panels), from it on tiled (units = tiles)
     int unit_start[kGroupMax + 1];
     GroupMember prob[kGroupMax];
 };
 
+static_assert(sizeof(GroupMember) == 56, "member record");
 static_assert(sizeof(GroupParams) <= 4096, "kernel argument block");
 
 __device__ __forceinline__ int group_find(const GroupParams &g, int bid)
@@ -908,15 +912,15 @@ __device__ __forceinline__ GemmParams group_member_params(const GroupMember &m, 
     p.ldc = m.ldc;
     p.tiles_m = (m.M + BM - 1) / BM;
     p.tiles_n = (m.N + BN - 1) / BN;
-    p.za_term = m.za_term;
-    p.zb = m.zb;
-    p.kconst = 0u - m.zb * m.za_term * (uint32_t)m.K;
+    p.za_term = (uint32_t)(int32_t)m.za_term;
+    p.zb = (uint32_t)(int32_t)m.zb;
+    p.kconst = 0u - p.zb * p.za_term * (uint32_t)m.K;
     p.scale = 1.0f;
     p.zc = 0;
     p.scale_vec = nullptr;
     p.bias_vec = nullptr;
     p.zb_vec = nullptr;
-    p.rconst = m.za_term * (uint32_t)m.K;
+    p.rconst = p.za_term * (uint32_t)m.K;
     p.relu = 0;
     p.a_xor = 0x80808080u;
     p.ksplit = 1;
@@ -925,18 +929,10 @@ __device__ __forceinline__ GemmParams group_member_params(const GroupMember &m, 
     return p;
 }
 
-// Register ring of the grouped tile kernel: with four sets the batch of 64 odd shapes takes 28.8 us,
+// Register ring of the grouped kernel's tiles: with four sets the batch of 64 odd shapes takes 28.8 us,
 // with one 34.8 (a long-K member's loads no longer wait behind the other members' traffic); stages
 // of 128 bytes instead of 64 gain nothing.
 constexpr int kGroupRing = 4;
-template <int BM, int BN, int WGM, int WGN, int BK>
-__global__ __launch_bounds__(WGM * WGN * 64) void gemm_group_tile_kernel(const GroupParams g)
-{
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const int q = group_find(g, blockIdx.x);
-    const GemmParams p = group_member_params<BM, BN>(g.prob[q], g.nxcd);
-    tile_body_staged<BM, BN, WGM, WGN, BK, false, true, kGroupRing>(p, blockIdx.x - g.unit_start[q], lds);
-}
 
 // ---- tiled MFMA kernel, direct-to-LDS variant -------------------------------------------------
 // Same tiling and epilogue, but each stage (64 bytes of K) is copied memory -> LDS by the
@@ -2653,6 +2649,21 @@ __global__ __launch_bounds__(512) void gemm_group_skinny_kernel(const GroupParam
     skinny_body<false, 1, true>(p, blockIdx.x - g.unit_start[q], 4 * ((p.M + 7) / 8), red);
 }
 
+// Both kinds of member in one grid (see GroupParams): four wavefronts; a skinny member's panel is
+// summed over K by the four of them, a tile is the 2 x 2 wavefront form of the staged kernel.  The
+// skinny members come first in the grid: the longest of them take as long as the whole launch and
+// have to start with it.
+template <int BM, int BN, int WGM, int WGN, int BK>
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_group_kernel(const GroupParams g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int q = group_find(g, blockIdx.x);
+    const GemmParams p = group_member_params<BM, BN>(g.prob[q], g.nxcd);
+    const int unit = blockIdx.x - g.unit_start[q];
+    if (q < g.first_tile) skinny_body<false, 1, true>(p, unit, 4 * ((p.M + 7) / 8), (int *)lds);
+    else tile_body_staged<BM, BN, WGM, WGN, BK, false, true, kGroupRing>(p, unit, lds);
+}
+
 // ---- streaming skinny kernel (M <= 32, K short enough for A to sit in LDS) ---------------------
 // For outputs of many panels (wide N, or the panels of all members of a grouped call): the unit
 // of work is a whole 32-column panel over all of K, one per wavefront, so the partial sums of a
@@ -2904,8 +2915,8 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_group_stream_kernel(co
     m.N = g.N[q]; m.K = g.K[q];
     const uint32_t mzz = g.mzz[q];
     m.M = (int)(mzz & 63u);
-    m.za_term = (uint32_t)((int32_t)(mzz << 17) >> 23);       // sign-extend the 9 bits at [6, 15)
-    m.zb = (uint32_t)((int32_t)(mzz << 9) >> 24);             // ... the 8 bits at [15, 23)
+    m.za_term = (int16_t)((int32_t)(mzz << 17) >> 23);        // sign-extend the 9 bits at [6, 15)
+    m.zb = (int16_t)((int32_t)(mzz << 9) >> 24);              // ... the 8 bits at [15, 23)
     const GemmParams p = group_member_params<64, 64>(m, g.nxcd);
     const int first = (unit - g.unit_start[q]) * g.chunk;
     const int count = p.npanels - first < g.chunk ? p.npanels - first : g.chunk;

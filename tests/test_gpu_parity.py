@@ -377,6 +377,43 @@ def test_streaming_skinny_grouped(rt, oracle):
         ng.ngemm_packed_b_free(h)
 
 
+def test_batched_mixed_groups_over_the_member_limit(rt, oracle):
+    """Grouped calls whose skinny and tiled members share one grid: 150 members (more than two argument
+    blocks hold), skinny ones of few panels next to tiled ones, extreme zero-points on both kinds
+    (the member record keeps 128 - za and zb as 16-bit values), long K on a few panels, sentinel rows
+    and columns around every output."""
+    ng = ng_mod()
+    rng = np.random.default_rng(77)
+    shapes = []
+    for t in range(150):
+        if t % 3 == 0:
+            shapes.append((int(rng.integers(1, 33)), int(rng.integers(1, 200)), int(rng.integers(1, 700))))
+        else:
+            shapes.append((int(rng.integers(33, 200)), int(rng.integers(1, 200)), int(rng.integers(1, 400))))
+    shapes += [(4, 40, 3000), (150, 3, 2700), (32, 33, 65), (33, 32, 64)]
+    zps = [(0, -128), (255, 127), (0, 127), (255, -128)]
+    items, outs, probs, keep, handles = [], [], [], [], []
+    for t, (M, N, K) in enumerate(shapes):
+        A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+        B = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        za, zb = zps[t % 4] if t % 5 == 0 else (int(rng.integers(0, 256)), int(rng.integers(-128, 128)))
+        h, packed = rt.pack(B)
+        Ad = torch.from_numpy(A).cuda()
+        Cd = torch.full((M + 1, N + 3), -9, dtype=torch.int32, device="cuda")
+        handles.append(h); keep.append((packed, Ad)); outs.append(Cd)
+        probs.append((A, B, za, zb))
+        items.append((M, Ad, K, za, zb, h, Cd, N + 3))
+    arr = ng.make_problems(items)
+    ng.ngemm_run_batched_u8s8s32(rt.ctx, arr)
+    torch.cuda.synchronize()
+    for (M, N, K), (A, B, za, zb), Cd in zip(shapes, probs, outs):
+        got = Cd.cpu().numpy()
+        assert np.all(got[M:, :] == -9) and np.all(got[:, N:] == -9), (M, N, K)
+        assert np.array_equal(got[:M, :N], oracle.gemm_u8s8s32(A, B, za, zb)), (M, N, K, za, zb)
+    for h in handles:
+        ng.ngemm_packed_b_free(h)
+
+
 def test_extreme_values_and_wrap(rt, oracle):
     """All-255 x all-(-128)/127 operands: no 16-bit stage, exact at the int32 bound, wraps beyond."""
     for (K, b) in ((64, 127), (64, -128), (65793, -128), (65794, -128), (66311, 127), (66312, 127)):
