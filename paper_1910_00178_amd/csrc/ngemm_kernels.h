@@ -430,6 +430,13 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
     constexpr int LPR = TN * 8, RPP = 64 / LPR, NPASS = 32 / RPP;   // read-back: LPR lanes per row
     const int bcol = n0 + wn * TN * 32 + 4 * (lane % LPR);
     const bool interior = m0 + (wm + 1) * TM * 32 <= p.M && n0 + (wn + 1) * TN * 32 <= p.N;   // this wavefront's part
+    // u8 output of a wavefront part that lies inside C with 16-byte aligned rows: the bytes go through
+    // the wavefront's patch as well (32 rows of TN * 32 bytes, padded) and leave as 16-byte pieces of
+    // whole rows; straight from the accumulators a store instruction touches 32 rows with 8 bytes each
+    // (1-2.5 % of the u8 calls of one tile per workgroup; plain stores: streaming stores of pieces of a
+    // line are far slower)
+    constexpr int kRow8 = TN * 32 + 16, LPR8 = TN * 2, RPP8 = 64 / LPR8, NPASS8 = 32 / RPP8;
+    const bool u8_rows = REQUANT && interior && ((((uintptr_t)p.C | (uintptr_t)p.ldc) & 15) == 0);
     uint4 ct_back = {0u, 0u, 0u, 0u};
     if (REQUANT) {
         // per column: (128-za)*colsum + bias, zero-point of B, scale (vectors or the scalars); thread c
@@ -494,7 +501,10 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
                         b[2] = requant_u8(v[2], sc.z, p.zc, p.relu);
                         b[3] = requant_u8(v[3], sc.w, p.zc, p.relu);
                     }
-                    if (col + 3 < p.N && c_vec_ok) {
+                    if (u8_rows) {
+                        *(uint32_t *)(xpose + (lane & 31) * kRow8 + j * 32 + 8 * q + 4 * (lane >> 5)) =
+                            (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16) | ((uint32_t)b[3] << 24);
+                    } else if (col + 3 < p.N && c_vec_ok) {
                         *(uint32_t *)dst = (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16) |
                                            ((uint32_t)b[3] << 24);
                     } else {
@@ -509,6 +519,17 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
                     *(v4i *)(xpose + xpose_off<TN>(lane & 31, 8 * j + 2 * q + (lane >> 5))) = o;
                 }
             }
+        }
+        if (u8_rows) {
+            const int brow0 = m0 + (wm * TM + i) * 32;
+            uint8_t *dst0 = (uint8_t *)p.C + (int64_t)(brow0 + lane / LPR8) * p.ldc + n0 + wn * TN * 32 + 16 * (lane % LPR8);
+            v4i o[NPASS8];
+#pragma unroll
+            for (int pass = 0; pass < NPASS8; ++pass)
+                o[pass] = *(const v4i *)(xpose + (RPP8 * pass + lane / LPR8) * kRow8 + 16 * (lane % LPR8));
+#pragma unroll
+            for (int pass = 0; pass < NPASS8; ++pass)
+                *(v4i *)(dst0 + (int64_t)(RPP8 * pass) * p.ldc) = o[pass];
         }
         if (!REQUANT) {
             // read the block row back row-wise, add the column terms, store full lines
