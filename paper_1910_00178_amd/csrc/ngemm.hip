@@ -383,14 +383,22 @@ int choose_kernel(const ngemm_ctx *ctx, int64_t M, int64_t N, int64_t K)
         return NGEMM_KERNEL_SKINNY;
     }
     if (t64 * 2 <= cus && K >= kSplitMinK * ((t64 + step - 1) / step)) return NGEMM_KERNEL_SPLIT_K;
-    if (tiles(256) * 2 >= cus) {
+    const int64_t t192 = ((M + 191) / 192) * ((N + 255) / 256);
+    // The large tiles pay off from 0.7 of the compute units filled with K >= 512 (4096 x 4096 x 256: 16.5 / 15.0), from 0.5 with K >= 1024,
+    // from 0.4 with K >= 2048: their fill and epilogue want stages to spread over (us, large against
+    // 128 x 128 tiles: 3072 x 3072 x 512 13.2 / 15.0, 2560 x 2560 x 512 10.8 / 9.6, 2176 x 2176 x 1024
+    // 13.4 / 12.1, 2304^3 20.8 / 22.5, 2560^3 24.0 / 26.6).
+    const int64_t big = tiles(256) > t192 ? tiles(256) : t192;
+    if ((big * 10 >= cus * 7 && K >= 512) || (big * 2 >= cus && K >= 1024) || (big * 5 >= cus * 2 && K >= 2048)) {
         // rounds of resident workgroups times the rows of a tile: 192 x 256 tiles when they fill more of the
-        // compute units for less time (3072^3: 144 tiles of 256 rows against 192 of 192, one round each)
-        const int64_t t192 = ((M + 191) / 192) * ((N + 255) / 256);
+        // compute units for less time (3072^3: 144 tiles of 256 rows against 192 of 192, one round each;
+        // 2560^3: 100 against 140, 29.3 us against 24.0 us, 128 x 128 tiles 26.6 us)
         const int64_t r256 = (tiles(256) + cus - 1) / cus * 256, r192 = (t192 + cus - 1) / cus * 192;
         return r192 < r256 ? NGEMM_KERNEL_TILE_192 : NGEMM_KERNEL_TILE_256;
     }
-    if (tiles(128) >= cus) return NGEMM_KERNEL_TILE_128;
+    // (1536^3, 144 tiles of 128 x 128: 10.0 us against 10.6 us with 64 x 64 tiles; 1024^3, 64 tiles: 7.9
+    // against 5.5; 1536 x 1536 x 512: 6.9 against 6.4)
+    if (tiles(128) >= cus || (tiles(128) * 5 >= cus * 2 && K >= 1024)) return NGEMM_KERNEL_TILE_128;
     return NGEMM_KERNEL_TILE_64;
 }
 
