@@ -122,17 +122,21 @@ __device__ __forceinline__ uint8_t requant_u8(int32_t c, float scale, int32_t zc
     return (uint8_t)q;
 }
 
-// The same value when |zc| < 2^23 (the caller checks; every practical zero-point), in binary32
-// throughout.  r beyond +-2^24 cannot land in [0, 255] after adding zc, nor on the other side of zc, so
-// it may be clamped there first; then |r + zc| < 2^24 + 2^23, where binary32 addition of two integers
-// is exact up to 2^24 and off by at most one beyond, far from 0, 255 and zc.
-__device__ __forceinline__ uint8_t requant_u8_small_zc(int32_t c, float scale, float zcf, int relu)
+// The same values when |zc| < 2^23 (the caller checks; every practical zero-point), in binary32 throughout,
+// four packed into a word: r = rint(c * scale), q = r + zc, the ReLU floor, and v_cvt_pk_u8_f32, which converts
+// with saturation to [0, 255] and writes one byte of the word (checked on the target: -inf .. 0.5 -> 0,
+// 255.5 .. +inf -> 255, ties to even) -- five vector instructions per value, no clamps, no shifts to pack.
+// r beyond +-2^24 cannot land in [0, 255] after adding zc, nor on the other side of zc; up to there binary32
+// addition of two integers is exact, beyond it the sum is off by little and far from 0, 255 and zc.
+// floor_f: zc for the ReLU form, -FLT_MAX otherwise.
+__device__ __forceinline__ uint32_t requant4_u8_small_zc(const int32_t (&c)[4], const float4 &scale, float zcf, float floor_f)
 {
-    float r = rintf(__fmul_rn((float)c, scale));
-    r = fminf(fmaxf(r, -16777216.0f), 16777216.0f);
-    float q = r + zcf;
-    if (relu) q = fmaxf(q, zcf);
-    return (uint8_t)(int)fminf(fmaxf(q, 0.0f), 255.0f);
+    uint32_t w = 0u;
+    w = __builtin_amdgcn_cvt_pk_u8_f32(fmaxf(rintf(__fmul_rn((float)c[0], scale.x)) + zcf, floor_f), 0, w);
+    w = __builtin_amdgcn_cvt_pk_u8_f32(fmaxf(rintf(__fmul_rn((float)c[1], scale.y)) + zcf, floor_f), 1, w);
+    w = __builtin_amdgcn_cvt_pk_u8_f32(fmaxf(rintf(__fmul_rn((float)c[2], scale.z)) + zcf, floor_f), 2, w);
+    w = __builtin_amdgcn_cvt_pk_u8_f32(fmaxf(rintf(__fmul_rn((float)c[3], scale.w)) + zcf, floor_f), 3, w);
+    return w;
 }
 
 // General (per-column capable) value of one requantised element from its shifted-form
@@ -488,29 +492,22 @@ __device__ __forceinline__ void tile_epilogue(const GemmParams &p, v16i (&acc)[T
                 if (REQUANT) {
                     uint8_t *dst = (uint8_t *)p.C + (int64_t)row * p.ldc + col;
                     const float4 sc = *(const float4 *)((const float *)cterm_lds + 2 * BN + lcol);
-                    uint8_t b[4];
+                    uint32_t bw;
                     if (SMALLZC) {
                         const float zcf = (float)p.zc;
-                        b[0] = requant_u8_small_zc(v[0], sc.x, zcf, p.relu);
-                        b[1] = requant_u8_small_zc(v[1], sc.y, zcf, p.relu);
-                        b[2] = requant_u8_small_zc(v[2], sc.z, zcf, p.relu);
-                        b[3] = requant_u8_small_zc(v[3], sc.w, zcf, p.relu);
+                        bw = requant4_u8_small_zc(v, sc, zcf, p.relu ? zcf : -3.402823466e38f);
                     } else {
-                        b[0] = requant_u8(v[0], sc.x, p.zc, p.relu);
-                        b[1] = requant_u8(v[1], sc.y, p.zc, p.relu);
-                        b[2] = requant_u8(v[2], sc.z, p.zc, p.relu);
-                        b[3] = requant_u8(v[3], sc.w, p.zc, p.relu);
+                        bw = (uint32_t)requant_u8(v[0], sc.x, p.zc, p.relu) | ((uint32_t)requant_u8(v[1], sc.y, p.zc, p.relu) << 8) |
+                             ((uint32_t)requant_u8(v[2], sc.z, p.zc, p.relu) << 16) | ((uint32_t)requant_u8(v[3], sc.w, p.zc, p.relu) << 24);
                     }
                     if (u8_rows) {
-                        *(uint32_t *)(xpose + (lane & 31) * kRow8 + j * 32 + 8 * q + 4 * (lane >> 5)) =
-                            (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16) | ((uint32_t)b[3] << 24);
+                        *(uint32_t *)(xpose + (lane & 31) * kRow8 + j * 32 + 8 * q + 4 * (lane >> 5)) = bw;
                     } else if (col + 3 < p.N && c_vec_ok) {
-                        *(uint32_t *)dst = (uint32_t)b[0] | ((uint32_t)b[1] << 8) | ((uint32_t)b[2] << 16) |
-                                           ((uint32_t)b[3] << 24);
+                        *(uint32_t *)dst = bw;
                     } else {
 #pragma unroll
                         for (int t = 0; t < 4; ++t)
-                            if (col + t < p.N) dst[t] = b[t];
+                            if (col + t < p.N) dst[t] = (uint8_t)(bw >> (8 * t));
                     }
                 } else {
                     // row r = lane%32 of the block row, chunk c = 8j + 2q + lane/32
@@ -1715,9 +1712,8 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
             const float zcf = (float)p.zc;
             auto requant_rows = [&](auto small) __attribute__((always_inline)) {
             constexpr bool SMALL = decltype(small)::value != 0;
-            auto rq = [&](uint32_t v, float sc) -> uint32_t {
-                return SMALL ? requant_u8_small_zc((int32_t)v, sc, zcf, p.relu) : requant_u8((int32_t)v, sc, p.zc, p.relu);
-            };
+            auto rq = [&](uint32_t v, float sc) -> uint32_t { return requant_u8((int32_t)v, sc, p.zc, p.relu); };
+            const float floor_f = p.relu ? zcf : -3.402823466e38f;
             // sum_k (A[i][k] - za) of this lane's row in each of the eight blocks, multiplied per column
             // by that column's zero-point of B (all loaded first: a load between the blocks would wait
             // for the stores of the block before it)
@@ -1750,11 +1746,12 @@ __global__ __launch_bounds__(256) void gemm_tile_x64_kernel(const GemmParams p, 
                     const uint4 cb = cbs[j], zv = zvs[j];
                     const float4 sc = scs[j];
                     const v4i v = acc[i][j];
-                    const uint32_t b0 = rq((uint32_t)v.x + cb.x - zv.x * rsum, sc.x);
-                    const uint32_t b1 = rq((uint32_t)v.y + cb.y - zv.y * rsum, sc.y);
-                    const uint32_t b2 = rq((uint32_t)v.z + cb.z - zv.z * rsum, sc.z);
-                    const uint32_t b3 = rq((uint32_t)v.w + cb.w - zv.w * rsum, sc.w);
-                    *(uint32_t *)(patch + ft * kRow8 + 16 * j + 4 * fc) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+                    const int32_t c4[4] = {(int32_t)((uint32_t)v.x + cb.x - zv.x * rsum), (int32_t)((uint32_t)v.y + cb.y - zv.y * rsum),
+                                           (int32_t)((uint32_t)v.z + cb.z - zv.z * rsum), (int32_t)((uint32_t)v.w + cb.w - zv.w * rsum)};
+                    uint32_t bw;
+                    if (SMALL) bw = requant4_u8_small_zc(c4, sc, zcf, floor_f);
+                    else bw = rq((uint32_t)c4[0], sc.x) | (rq((uint32_t)c4[1], sc.y) << 8) | (rq((uint32_t)c4[2], sc.z) << 16) | (rq((uint32_t)c4[3], sc.w) << 24);
+                    *(uint32_t *)(patch + ft * kRow8 + 16 * j + 4 * fc) = bw;
                 }
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
